@@ -1,0 +1,57 @@
+"""TEST INFRASTRUCTURE ONLY: the paper's counting formulas, written out.
+
+* mu(F(m,r)) and mu(F(m x n, r x s)): Section 4, Eq. (3) and Eq. (4).
+* Normalised complexities alpha', beta', gamma', delta' of Section 5 (Eq. (20)-(23)), in
+  the reading that reproduces Table 1: alpha = m + r - 1, alpha' = alpha^2 / m^2, and
+  beta' = beta / alpha^2 (likewise gamma', delta'), with beta, gamma, delta the per-tile
+  transform instruction counts stated in Section 4.1 and Section 4.3.
+* Direct-convolution flop count behind Table 3 and the "effective TFLOPS" of Section 7.
+
+Parity pins: tests/test_oracle_complexity.py against tests/golden/*.txt.
+"""
+
+# per-tile transform instruction counts (data, filter, inverse), Sections 4.1 and 4.3
+TRANSFORM_FLOPS = {2: (32, 28, 24), 4: (156, 72, 100)}
+
+
+def mu_1d(m, r):
+    return m + r - 1
+
+
+def mu_2d(m, n, r, s):
+    return mu_1d(m, r) * mu_1d(n, s)
+
+
+def normalized_complexity(m, r=3):
+    a = m + r - 1
+    beta, gamma, delta = TRANSFORM_FLOPS[m]
+    return (a * a / (m * m), beta / (a * a), gamma / (a * a), delta / (a * a))
+
+
+def layer_complexity(N, C, H, W, K, m, r=3):
+    """Eq. (23): L = alpha'(1 + beta'/K + gamma'/P + delta'/C) N H W C K, no remainders assumed."""
+    ap, bp, gp, dp = normalized_complexity(m, r)
+    P = N * H * W / (m * m)
+    return ap * (1 + bp / K + gp / P + dp / C) * N * H * W * C * K
+
+
+def direct_flops(N, C, H, W, K, R=3, S=3):
+    """2 flops per multiply-add of Eq. (1) with H x W outputs (the Table 3 convention)."""
+    return 2 * N * K * C * R * S * H * W
+
+
+# Table 3: (name, depth in network E, C, H=W, K)
+VGG_E_LAYERS = [
+    ("conv1.1", 1, 3, 224, 64), ("conv1.2", 1, 64, 224, 64), ("conv2.1", 1, 64, 112, 128),
+    ("conv2.2", 1, 128, 112, 128), ("conv3.1", 1, 128, 56, 256), ("conv3.2", 3, 256, 56, 256),
+    ("conv4.1", 1, 256, 28, 512), ("conv4.2", 3, 512, 28, 512), ("conv5", 4, 512, 14, 512),
+]
+
+
+def vgg_e_gflops(N=1):
+    return [(n, d * direct_flops(N, C, HW, HW, K) / 1e9) for n, d, C, HW, K in VGG_E_LAYERS]
+
+
+def effective_tflops(gflops, msec):
+    """Section 7: direct-algorithm GFLOPs divided by run time in milliseconds."""
+    return gflops / msec

@@ -1,0 +1,116 @@
+/*
+ * TEST INFRASTRUCTURE ONLY -- the CPU oracle for the convnet-layer forward pass.
+ *
+ * This file is the plain definition of what the fast algorithm must reproduce: the
+ * layer output of Section 3, Eq. (1) of Lavin & Gray, "Fast Algorithms for
+ * Convolutional Neural Networks" -- a 2-D correlation (no filter flip) of every image
+ * channel with the matching filter channel, summed over channels.  Following the
+ * accuracy protocol of Section 7 (Experiments), every output is reduced in a
+ * double-precision accumulator.
+ *
+ * Readings taken where the paper is silent (Eq. (1) is 1-based with swapped summation
+ * limits and never states padding): indices are 0-based; the first spatial index of G
+ * pairs with the first spatial index of D (rows, H), the second with columns (W);
+ * zero padding `pad` on every side, stride `stride`; output extent
+ * (H + 2*pad - R)/stride + 1.  With R=S=3, pad=1, stride=1 the output is H x W, which
+ * is what Table 3's GFLOP column implies.
+ *
+ * Nothing here is blocked, fused, vectorised by hand or shared with the GPU library.
+ * Only tests, the smoke check and the CPU-baseline leg of the benchmark may call it.
+ * Parity pins: tests/test_oracle_direct.py (brute force, torch float64 conv2d,
+ * delta-filter identity, linearity, shift equivariance).
+ */
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+static inline int out_extent(int in, int pad, int filt, int stride)
+{
+    return (in + 2 * pad - filt) / stride + 1;
+}
+
+/* Eq. (1), inputs already widened to double.  Layouts: D[N][C][H][W], G[K][C][R][S],
+ * Y[N][K][Ho][Wo], all dense row-major.  Summation order for one output is c, u, v. */
+void oracle_conv2d_fwd_f64(int N, int C, int H, int W, int K, int R, int S, int pad, int stride,
+                           const double *D, const double *G, double *Y)
+{
+    const int Ho = out_extent(H, pad, R, stride), Wo = out_extent(W, pad, S, stride);
+    #pragma omp parallel for collapse(2) schedule(static)
+    for (int i = 0; i < N; ++i)
+        for (int k = 0; k < K; ++k)
+            for (int x = 0; x < Ho; ++x)
+                for (int y = 0; y < Wo; ++y) {
+                    double acc = 0.0;
+                    for (int c = 0; c < C; ++c)
+                        for (int u = 0; u < R; ++u)
+                            for (int v = 0; v < S; ++v) {
+                                const int xx = x * stride + u - pad;
+                                const int yy = y * stride + v - pad;
+                                if (xx >= 0 && xx < H && yy >= 0 && yy < W)
+                                    acc += D[(((size_t)i * C + c) * H + xx) * W + yy] *
+                                           G[(((size_t)k * C + c) * R + u) * S + v];
+                            }
+                    Y[(((size_t)i * K + k) * Ho + x) * Wo + y] = acc;
+                }
+}
+
+/* Same definition on the stored single-precision tensors (fp16 tensors are widened to
+ * fp32 exactly by the caller): each product and the whole reduction are in double. */
+void oracle_conv2d_fwd_f32in(int N, int C, int H, int W, int K, int R, int S, int pad, int stride,
+                             const float *D, const float *G, double *Y)
+{
+    const int Ho = out_extent(H, pad, R, stride), Wo = out_extent(W, pad, S, stride);
+    #pragma omp parallel for collapse(2) schedule(static)
+    for (int i = 0; i < N; ++i)
+        for (int k = 0; k < K; ++k)
+            for (int x = 0; x < Ho; ++x)
+                for (int y = 0; y < Wo; ++y) {
+                    double acc = 0.0;
+                    for (int c = 0; c < C; ++c)
+                        for (int u = 0; u < R; ++u)
+                            for (int v = 0; v < S; ++v) {
+                                const int xx = x * stride + u - pad;
+                                const int yy = y * stride + v - pad;
+                                if (xx >= 0 && xx < H && yy >= 0 && yy < W)
+                                    acc += (double)D[(((size_t)i * C + c) * H + xx) * W + yy] *
+                                           (double)G[(((size_t)k * C + c) * R + u) * S + v];
+                            }
+                    Y[(((size_t)i * K + k) * Ho + x) * Wo + y] = acc;
+                }
+}
+
+/* Eq. (1) evaluated one output at a time: pts holds npts quadruples (i, k, x, y); out[j]
+ * receives Y[i][k][x][y].  Used where a whole layer is too large to recompute on the CPU. */
+void oracle_conv2d_points_f32in(int N, int C, int H, int W, int K, int R, int S, int pad, int stride,
+                                const float *D, const float *G, long npts, const int32_t *pts,
+                                double *out)
+{
+    (void)N; (void)K;
+    #pragma omp parallel for schedule(static)
+    for (long j = 0; j < npts; ++j) {
+        const int i = pts[4 * j + 0], k = pts[4 * j + 1], x = pts[4 * j + 2], y = pts[4 * j + 3];
+        double acc = 0.0;
+        for (int c = 0; c < C; ++c)
+            for (int u = 0; u < R; ++u)
+                for (int v = 0; v < S; ++v) {
+                    const int xx = x * stride + u - pad;
+                    const int yy = y * stride + v - pad;
+                    if (xx >= 0 && xx < H && yy >= 0 && yy < W)
+                        acc += (double)D[(((size_t)i * C + c) * H + xx) * W + yy] *
+                               (double)G[(((size_t)k * C + c) * R + u) * S + v];
+                }
+        out[j] = acc;
+    }
+}

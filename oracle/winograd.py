@@ -1,0 +1,224 @@
+"""TEST INFRASTRUCTURE ONLY: the minimal-filtering algorithm, stage by stage, on the CPU.
+
+What is written out here, all from Section 4 of the paper:
+
+* the transform matrices B^T, G, A^T of F(2,3) (Eq. (7)) and F(4,3) (Eq. (15)) as exact
+  rationals, plus F(3,2) (Eq. (14)) which the weight-gradient variant uses;
+* the 1-D matrix form Y = A^T[(G g) . (B^T d)] (Eq. (6)) and its 2-D nesting
+  Y = A^T[[G g G^T] . [B^T d B]]A (Eq. (8)), usable on Fractions or floats;
+* Algorithm 1 in its four loops -- filter transform and scatter to U, tile gather,
+  data transform and scatter to V, the alpha^2 products M = U V (Eq. (13)), gather and
+  inverse transform -- in numpy float64 with no blocking or fusion;
+* the integer tile bookkeeping that Algorithm 1 leaves implicit.
+
+Readings where the paper is silent: tiles per image are T_h x T_w with
+T = ceil(out_extent / m); tile index b = (i*T_h + tx)*T_w + ty (ty fastest); the tile
+origin in the input is (m*tx - pad, m*ty - pad); reads outside the image are zero;
+outputs past the image edge are dropped.
+
+Parity pins: tests/test_oracle_winograd.py (rational exactness against direct
+correlation, the printed F(2,3) products m1..m4, multiplication counts, agreement with
+the direct oracle).
+"""
+from fractions import Fraction as Fr
+
+import numpy as np
+
+_MATRICES = {
+    # F(2,3), Eq. (7)
+    (2, 3): dict(
+        BT=[[1, 0, -1, 0],
+            [0, 1, 1, 0],
+            [0, -1, 1, 0],
+            [0, 1, 0, -1]],
+        G=[[Fr(1), 0, 0],
+           [Fr(1, 2), Fr(1, 2), Fr(1, 2)],
+           [Fr(1, 2), Fr(-1, 2), Fr(1, 2)],
+           [0, 0, Fr(1)]],
+        AT=[[1, 1, 1, 0],
+            [0, 1, -1, -1]]),
+    # F(4,3), Eq. (15)
+    (4, 3): dict(
+        BT=[[4, 0, -5, 0, 1, 0],
+            [0, -4, -4, 1, 1, 0],
+            [0, 4, -4, -1, 1, 0],
+            [0, -2, -1, 2, 1, 0],
+            [0, 2, -1, -2, 1, 0],
+            [0, 4, 0, -5, 0, 1]],
+        G=[[Fr(1, 4), 0, 0],
+           [Fr(-1, 6), Fr(-1, 6), Fr(-1, 6)],
+           [Fr(-1, 6), Fr(1, 6), Fr(-1, 6)],
+           [Fr(1, 24), Fr(1, 12), Fr(1, 6)],
+           [Fr(1, 24), Fr(-1, 12), Fr(1, 6)],
+           [0, 0, Fr(1)]],
+        AT=[[1, 1, 1, 1, 1, 0],
+            [0, 1, -1, 2, -2, 0],
+            [0, 1, 1, 4, 4, 0],
+            [0, 1, -1, 8, -8, 1]]),
+    # F(3,2), Eq. (14)
+    (3, 2): dict(
+        BT=[[1, 0, -1, 0],
+            [0, 1, 1, 0],
+            [0, -1, 1, 0],
+            [0, -1, 0, 1]],
+        G=[[Fr(1), 0],
+           [Fr(1, 2), Fr(1, 2)],
+           [Fr(1, 2), Fr(-1, 2)],
+           [0, Fr(1)]],
+        AT=[[1, 1, 1, 0],
+            [0, 1, -1, 0],
+            [0, 1, 1, 1]]),
+}
+
+
+def matrices(m, r=3):
+    """(B^T, G, A^T) of F(m, r) as lists of lists of Fractions."""
+    e = _MATRICES[(m, r)]
+    return tuple([[Fr(x) for x in row] for row in e[n]] for n in ("BT", "G", "AT"))
+
+
+def matrices_f64(m, r=3):
+    return tuple(np.array([[float(x) for x in row] for row in mat]) for mat in matrices(m, r))
+
+
+# ---- tiny exact linear algebra on lists (works for Fractions, ints, floats) ----------------
+
+def matmul(A, B):
+    return [[sum(A[i][t] * B[t][j] for t in range(len(B))) for j in range(len(B[0]))]
+            for i in range(len(A))]
+
+
+def transpose(A):
+    return [list(col) for col in zip(*A)]
+
+
+def hadamard(A, B):
+    return [[a * b for a, b in zip(ra, rb)] for ra, rb in zip(A, B)]
+
+
+def fir_1d(m, r, d, g):
+    """Eq. (6): the m outputs of an r-tap filter over m+r-1 inputs, via the transforms."""
+    BT, G, AT = matrices(m, r)
+    Gg = [sum(G[i][j] * g[j] for j in range(r)) for i in range(len(G))]
+    Bd = [sum(BT[i][j] * d[j] for j in range(len(d))) for i in range(len(BT))]
+    prod = [a * b for a, b in zip(Gg, Bd)]          # the m+r-1 general multiplications
+    return [sum(AT[i][j] * prod[j] for j in range(len(prod))) for i in range(m)], len(prod)
+
+
+def filter_transform_tile(m, g, r=3):
+    """u = G g G^T (Algorithm 1, first loop) for one r x r filter."""
+    _, G, _ = matrices(m, r)
+    return matmul(matmul(G, g), transpose(G))
+
+
+def data_transform_tile(m, d, r=3):
+    """v = B^T d B (Algorithm 1, second loop) for one alpha x alpha tile."""
+    BT, _, _ = matrices(m, r)
+    return matmul(matmul(BT, d), transpose(BT))
+
+
+def inverse_transform_tile(m, mm, r=3):
+    """Y = A^T m A (Algorithm 1, fourth loop) for one alpha x alpha product tile."""
+    _, _, AT = matrices(m, r)
+    return matmul(matmul(AT, mm), transpose(AT))
+
+
+def fir_2d(m, r, d, g):
+    """Eq. (8): m x m outputs of an r x r filter over an alpha x alpha tile; also the
+    number of general multiplications used."""
+    u = filter_transform_tile(m, g, r)
+    v = data_transform_tile(m, d, r)
+    prod = hadamard(u, v)
+    return inverse_transform_tile(m, prod, r), sum(len(row) for row in prod)
+
+
+# ---- integer bookkeeping of Algorithm 1 ------------------------------------------------------
+
+def tile_counts(H, W, pad, m, r=3):
+    Ho, Wo = H + 2 * pad - r + 1, W + 2 * pad - r + 1
+    return -(-Ho // m), -(-Wo // m)
+
+
+def num_tiles(N, H, W, pad, m, r=3):
+    Th, Tw = tile_counts(H, W, pad, m, r)
+    return N * Th * Tw
+
+
+def tile_of(b, H, W, pad, m, r=3):
+    """b -> (image, tile row, tile column, input row of the tile origin, input column)."""
+    Th, Tw = tile_counts(H, W, pad, m, r)
+    ty = b % Tw
+    tx = (b // Tw) % Th
+    i = b // (Tw * Th)
+    return i, tx, ty, m * tx - pad, m * ty - pad
+
+
+# ---- Algorithm 1, loop by loop, float64 ------------------------------------------------------
+
+def filter_transform(G4, m):
+    """Loop 1: U[xi,nu,k,c] = (G g_{k,c} G^T)[xi,nu]."""
+    _, Gm, _ = matrices_f64(m)
+    g = np.asarray(G4, dtype=np.float64)
+    u = np.einsum("ai,kcij,bj->kcab", Gm, g, Gm)
+    return np.ascontiguousarray(u.transpose(2, 3, 0, 1))
+
+
+def gather_tiles(D4, pad, m, r=3):
+    """The alpha x alpha input tiles d_{c,b} with r-1 overlap and zero fill: [C, P, alpha, alpha]."""
+    D = np.asarray(D4, dtype=np.float64)
+    N, C, H, W = D.shape
+    a = m + r - 1
+    Th, Tw = tile_counts(H, W, pad, m, r)
+    tiles = np.zeros((C, N * Th * Tw, a, a))
+    for b in range(N * Th * Tw):
+        i, tx, ty, x0, y0 = tile_of(b, H, W, pad, m, r)
+        for p in range(a):
+            for q in range(a):
+                x, y = x0 + p, y0 + q
+                if 0 <= x < H and 0 <= y < W:
+                    tiles[:, b, p, q] = D[i, :, x, y]
+    return tiles
+
+
+def data_transform(D4, pad, m):
+    """Loop 2: V[xi,nu,c,b] = (B^T d_{c,b} B)[xi,nu]."""
+    BT, _, _ = matrices_f64(m)
+    d = gather_tiles(D4, pad, m)
+    v = np.einsum("ai,cbij,ej->cbae", BT, d, BT)
+    return np.ascontiguousarray(v.transpose(2, 3, 0, 1))
+
+
+def multiply(U, V):
+    """Loop 3: M^(xi,nu) = U^(xi,nu) V^(xi,nu), one K x C by C x P product per component."""
+    a = U.shape[0]
+    M = np.empty((a, a, U.shape[2], V.shape[3]))
+    for xi in range(a):
+        for nu in range(a):
+            M[xi, nu] = U[xi, nu] @ V[xi, nu]
+    return M
+
+
+def inverse_transform(M, N, H, W, pad, m, r=3):
+    """Loop 4: Y_{k,b} = A^T m_{k,b} A, written to Y[N,K,Ho,Wo] with edge outputs dropped."""
+    _, _, AT = matrices_f64(m)
+    K = M.shape[2]
+    Ho, Wo = H + 2 * pad - r + 1, W + 2 * pad - r + 1
+    y = np.einsum("pa,abkt,qb->ktpq", AT, M, AT)
+    Y = np.zeros((N, K, Ho, Wo))
+    for b in range(M.shape[3]):
+        i, tx, ty, _, _ = tile_of(b, H, W, pad, m, r)
+        for p in range(m):
+            for q in range(m):
+                x, yy = m * tx + p, m * ty + q
+                if x < Ho and yy < Wo:
+                    Y[i, :, x, yy] = y[:, b, p, q]
+    return Y
+
+
+def conv2d_fwd(D4, G4, pad, m):
+    """Algorithm 1 end to end; returns Y and the intermediates U, V, M."""
+    N, C, H, W = np.shape(D4)
+    U = filter_transform(G4, m)
+    V = data_transform(D4, pad, m)
+    M = multiply(U, V)
+    return inverse_transform(M, N, H, W, pad, m), U, V, M
