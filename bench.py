@@ -1,0 +1,280 @@
+#!/usr/bin/env python3
+"""Benchmark of the Winograd F(m x m, 3 x 3) forward path on one MI355X.
+
+A step is one forward pass of the 13 VGG-16 3x3 convolution layers (shapes of Table 3 of
+Lavin & Gray) on synthetic N(0,1) data and He-scaled filters resident in HBM: conv1.1 through
+the direct kernel, every other layer through wino_conv2d_fwd_ex (filter transform, input
+transform, batched multiply, inverse transform).  The headline value is effective TFLOP/s as
+the paper defines it (Section 7): direct-convolution flops divided by run time.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch 64] [--dtype f32]
+
+Prints ONE JSON line.  Besides the contract fields it carries
+  roofline      the dominant kernel (the transform-domain multiply) against the MFMA peak,
+                timed per launch with HIP events in a separate pass over the same launches;
+  stages        per-stage achieved GB/s (transforms) and TFLOP/s (multiply), per layer;
+  n1            the same stack at batch 1 (the latency case of the paper's Table 5);
+  cpu_baseline  the fp64 CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"hbm_GBs": 8000.0, "mfma_f32_TFs": 157.3, "mfma_f16_TFs": 2500.0}
+# Titan X (Maxwell) numbers of the paper, F(2x2,3x3), VGG network E (Tables 5 and 6): context only.
+PAPER_TITANX = {"fp32": {1: 7.03, 64: 9.37}, "fp16": {1: 7.06, 64: 10.28}}
+
+
+def direct_flops(N, C, H, W, K, R=3, S=3):
+    """Flops of Eq. (1) with H x W outputs: 2 per multiply-add (the convention of Table 3)."""
+    return 2 * N * K * C * R * S * H * W
+
+
+def choose_m(HW, policy):
+    """F(4x4,3x3) where 4 divides the image, else F(2x2,3x3) ('auto'); or a fixed m."""
+    if policy == "auto":
+        return 4 if HW % 4 == 0 else 2
+    return int(policy)
+
+
+class Layer:
+    pass
+
+
+def make_layers(N, np_dtype, policy, config_idx):
+    import torch
+    import paper_1509_09308_amd as w
+    from paper_1509_09308_amd import synth
+    layers = []
+    for li, (name, C, HW, K) in enumerate(synth.VGG16_LAYERS):
+        L = Layer()
+        L.name, L.C, L.HW, L.K, L.N = name, C, HW, K, N
+        L.direct = C < 16
+        L.m = None if L.direct else choose_m(HW, policy)
+        D, G = synth.make_layer(N, C, HW, HW, K, synth.layer_seed(config_idx, li), dtype=np_dtype)
+        L.D_host, L.G_host = D, G
+        L.D, L.G = torch.from_numpy(D).cuda(), torch.from_numpy(G).cuda()
+        L.Y = torch.empty((N, K, HW, HW), dtype=torch.float32 if not L.direct else L.D.dtype, device="cuda")
+        L.flops = direct_flops(N, C, HW, HW, K)
+        if not L.direct:
+            L.dt = w.WINO_F32 if L.D.dtype == torch.float32 else w.WINO_F16
+            L.P = w.wino_num_tiles(N, HW, HW, 1, L.m)
+            L.ws_bytes = w.wino_workspace_bytes(N, C, HW, HW, K, 1, L.m, L.dt)
+        layers.append(L)
+    return layers
+
+
+def run_step(w, layers, ws):
+    for L in layers:
+        if L.direct:
+            w.direct_conv2d_fwd(L.D, L.G, pad=1, Y=L.Y)
+        else:
+            w.wino_conv2d_fwd_ex(L.D, G=L.G, pad=1, m=L.m, Y=L.Y, workspace=ws)
+
+
+def time_steps(torch, w, layers, ws, steps, warmup):
+    for _ in range(warmup):
+        run_step(w, layers, ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run_step(w, layers, ws)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def time_layers(torch, w, layers, ws, steps):
+    """Per-layer time of the same calls, HIP events on the launch stream."""
+    out = []
+    for L in layers:
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        run_step(w, [L], ws)
+        ev[0].record()
+        for i in range(steps):
+            run_step(w, [L], ws)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        ts = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
+        out.append(sum(ts) / len(ts))
+    return out
+
+
+def time_stages(torch, w, layers, ws, steps):
+    """Second pass over the same launches, one stage entry point at a time, each bracketed by
+    HIP events on the stream the kernels run on.  Returns per-layer stage times in ms."""
+    res = []
+    es = lambda: torch.cuda.Event(enable_timing=True)
+    for L in layers:
+        if L.direct:
+            res.append(None)
+            continue
+        a2 = (L.m + 2) ** 2
+        U = w.alloc_u(L.K, L.C, L.m, L.dt)
+        V = w.alloc_v(L.C, L.P, L.m, L.dt)
+        M = w.alloc_m(L.K, L.P, L.m)
+        acc = {"filter": 0.0, "input": 0.0, "gemm": 0.0, "output": 0.0}
+        for it in range(steps + 1):
+            e = [es() for _ in range(5)]
+            e[0].record()
+            w.wino_filter_transform(L.G, L.m, U=U)
+            e[1].record()
+            w.wino_input_transform(L.D, 1, L.m, V=V)
+            e[2].record()
+            w.wino_batched_gemm(U, V, L.K, L.C, L.P, L.m, M=M)
+            e[3].record()
+            w.wino_output_transform(M, L.N, L.K, L.HW, L.HW, 1, L.m, Y=L.Y)
+            e[4].record()
+            torch.cuda.synchronize()
+            if it == 0:
+                continue  # warm-up
+            for j, k in enumerate(("filter", "input", "gemm", "output")):
+                acc[k] += e[j].elapsed_time(e[j + 1]) / steps
+        s = 4 if L.dt == w.WINO_F32 else 2
+        Kp, Cp, Pp = w.wino_padded_dims(L.K, L.C, L.P, L.m, L.dt)
+        st = dict(acc)
+        st["gemm_flops"] = 2 * a2 * L.K * L.C * L.P
+        st["bytes"] = {
+            "filter": 9 * L.K * L.C * s + a2 * L.K * L.C * s,
+            "input": L.N * L.C * L.HW * L.HW * s + a2 * L.C * L.P * s,
+            "output": a2 * L.K * L.P * 4 + L.N * L.K * L.HW * L.HW * 4,
+        }
+        st["gemm_variant"] = "%dx%d" % (128 if Kp >= 128 else 64, 128 if Pp >= 128 else 64)
+        res.append(st)
+        del U, V, M
+    return res
+
+
+def cpu_baseline(layers, budget_s=12.0):
+    """The fp64 oracle (Eq. (1)) on the host cores over whole images of the same workload."""
+    from oracle import direct
+    flops, secs, imgs = 0.0, 0.0, 0
+    nmax = layers[0].N
+    while secs < budget_s and imgs < min(nmax, 4):
+        for L in layers:
+            D = L.D_host[imgs:imgs + 1]
+            t0 = time.perf_counter()
+            direct.conv2d_fwd(D, L.G_host, pad=1)
+            secs += time.perf_counter() - t0
+            flops += direct_flops(1, L.C, L.HW, L.HW, L.K)
+        imgs += 1
+    return {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": direct.num_threads(), "kind": "oracle",
+            "images_per_sec": imgs / secs,
+            "sample": "fp64 direct convolution of all 13 layers for %d of %d images (%.1f s)" % (imgs, nmax, secs)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--batch", type=int, default=64)
+    ap.add_argument("--dtype", choices=["f32", "f16"], default="f32")
+    ap.add_argument("--m", default="auto", help="auto | 2 | 4")
+    ap.add_argument("--no-n1", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stages", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (batch sharding across GPUs is a design note, "
+              "not built); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_1509_09308_amd as w
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    w.build.ensure_built()
+    torch.cuda.set_device(0)
+    np_dtype = np.float32 if args.dtype == "f32" else np.float16
+    cfg_idx = 4 if args.dtype == "f32" else 5
+    policy = args.m if args.dtype == "f32" else ("4" if args.m == "auto" else args.m)
+
+    layers = make_layers(args.batch, np_dtype, policy, cfg_idx)
+    ws = torch.empty(max(L.ws_bytes for L in layers if not L.direct), dtype=torch.uint8, device="cuda")
+    total_flops = sum(L.flops for L in layers)
+
+    sec = time_steps(torch, w, layers, ws, args.steps, args.warmup)
+    value = total_flops / sec / 1e12
+
+    layer_ms = time_layers(torch, w, layers, ws, max(3, args.steps))
+    # the same per-layer times re-weighted with the depths of VGG network E (Table 3 of the paper)
+    from paper_1509_09308_amd import synth
+    shape = lambda L: (L.C, L.HW, L.K)
+    count16 = {}
+    for L in layers:
+        count16[shape(L)] = count16.get(shape(L), 0) + 1
+    wE = [synth.VGG_E_DEPTH[shape(L)] / count16[shape(L)] for L in layers]
+    e_flops = sum(x * L.flops for x, L in zip(wE, layers))
+    e_ms = sum(x * t for x, t in zip(wE, layer_ms))
+
+    out = {
+        "metric": "effective conv TFLOPS, VGG-16 3x3 conv stack forward, N=%d, 1 GPU" % args.batch,
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": "vgg16_3x3_conv_stack_N%d_%s" % (args.batch, args.dtype), "batch": args.batch,
+                   "layers": 13, "algorithm": "F(4x4,3x3) where 4 divides H, else F(2x2,3x3); conv1.1 direct"
+                   if policy == "auto" else "F(%sx%s,3x3); conv1.1 direct" % (policy, policy),
+                   "filter_transform": "inside the timed step"},
+        "images_per_sec": args.batch / sec,
+        "direct_gflop_per_step": total_flops / 1e9,
+        "per_layer": [{"layer": L.name, "m": L.m, "ms": t, "eff_tflops": L.flops / t / 1e9}
+                      for L, t in zip(layers, layer_ms)],
+        "vgg_e_weighted": {"eff_tflops": e_flops / e_ms / 1e9, "ms": e_ms,
+                           "paper_titanx_f2x2_tflops": PAPER_TITANX["fp32" if args.dtype == "f32" else "fp16"].get(args.batch)},
+    }
+
+    if not args.no_stages:
+        stages = time_stages(torch, w, layers, ws, max(3, args.steps))
+        rows, dom = [], {}
+        for L, st in zip(layers, stages):
+            if st is None:
+                continue
+            row = {"layer": L.name, "m": L.m, "gemm_variant": st["gemm_variant"],
+                   "gemm_ms": st["gemm"], "gemm_tflops": st["gemm_flops"] / st["gemm"] / 1e9}
+            for k in ("filter", "input", "output"):
+                row[k + "_ms"] = st[k]
+                row[k + "_GBs"] = st["bytes"][k] / st[k] / 1e6
+            rows.append(row)
+            d = dom.setdefault(st["gemm_variant"], {"flops": 0.0, "ms": 0.0, "launches": 0})
+            d["flops"] += st["gemm_flops"]
+            d["ms"] += st["gemm"]
+            d["launches"] += 1
+        out["stages"] = rows
+        if dom:
+            name, d = max(dom.items(), key=lambda kv: kv[1]["ms"])
+            peak = PEAK["mfma_f32_TFs"] if args.dtype == "f32" else PEAK["mfma_f16_TFs"]
+            ach = d["flops"] / d["ms"] / 1e9
+            out["roofline"] = {"bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
+                               "traffic": None, "kernel": "gemm_%s_kernel<%s>" % (args.dtype, name.replace("x", ", ")),
+                               "launches_per_step": d["launches"], "avg_launch_ms": d["ms"] / d["launches"],
+                               "flops_per_launch": d["flops"] / d["launches"]}
+            tb = sum(st["bytes"]["input"] + st["bytes"]["output"] for st in stages if st)
+            tms = sum(st["input"] + st["output"] for st in stages if st)
+            out["transform_roofline"] = {"bound": "hbm", "achieved": tb / tms / 1e6, "peak": PEAK["hbm_GBs"],
+                                         "unit": "GB/s", "frac": tb / tms / 1e6 / PEAK["hbm_GBs"]}
+
+    if not args.no_n1 and args.batch != 1:
+        del layers, ws
+        torch.cuda.empty_cache()
+        l1 = make_layers(1, np_dtype, policy if args.dtype == "f16" else "auto", 3)
+        ws1 = torch.empty(max(L.ws_bytes for L in l1 if not L.direct), dtype=torch.uint8, device="cuda")
+        s1 = time_steps(torch, w, l1, ws1, max(args.steps, 20), max(args.warmup, 5))
+        f1 = sum(L.flops for L in l1)
+        out["n1"] = {"eff_tflops": f1 / s1 / 1e12, "ms_per_step": s1 * 1e3, "images_per_sec": 1.0 / s1}
+        layers = l1
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(layers)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

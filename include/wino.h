@@ -1,0 +1,129 @@
+/*
+ * wino.h -- C ABI of the MI355X (gfx950) Winograd minimal-filtering convolution library.
+ *
+ * The library computes the forward pass of a convnet layer (Lavin & Gray, "Fast Algorithms
+ * for Convolutional Neural Networks", Section 3, Eq. (1)):
+ *
+ *     Y[i][k][x][y] = sum_c sum_u sum_v D[i][c][x+u-pad][y+v-pad] * G[k][c][u][v]
+ *
+ * (2-D correlation, no filter flip, zeros outside the image) for 3x3 filters at stride 1 with
+ * the algorithm F(m x m, 3 x 3) of Section 4, m = 2 (Eq. (7), (8)) or m = 4 (Eq. (15)), in
+ * the four stages of Algorithm 1, plus a direct evaluation of Eq. (1) for layers the fast
+ * algorithm does not cover.
+ *
+ * Conventions for every entry point
+ *   - D, G, U, V, M, Y and workspaces are DEVICE pointers owned by the caller; the library
+ *     never frees or keeps them.  Bases must be 16-byte aligned.
+ *   - Dense layouts: D[N][C][H][W], G[K][C][3][3], Y[N][K][Ho][Wo], Ho = H + 2*pad - 2.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work on it; they never synchronise the device.
+ *   - Return value: a wino_status_t.  No exceptions, no abort.  Arguments are checked before
+ *     any GPU call, so bad arguments are reported even on a machine with no GPU.
+ *   - Storage type `dt` is that of D, G, U and V; products are always accumulated in fp32 and
+ *     M is always fp32.
+ *
+ * Transform-domain layouts (alpha = m + 2; component index e = xi*alpha + nu; all row-major):
+ *     fp32:  U[e][c][k]          extents [alpha^2][Cp][Kp]
+ *            V[e][c][b]          extents [alpha^2][Cp][Pp]
+ *     fp16:  U[e][c/8][k][c%8]   extents [alpha^2][Cp/8][Kp][8]
+ *            V[e][c/8][b][c%8]   extents [alpha^2][Cp/8][Pp][8]
+ *     M[e][k][b]                 extents [alpha^2][Kp][Pp], fp32
+ * with the padded extents reported by wino_padded_dims(); padding elements of U and V are
+ * written as zeros by the transforms, padding elements of M are unspecified.  A tile index b
+ * stands for (image i, tile row tx, tile column ty) as b = (i*Th + tx)*Tw + ty, Th =
+ * ceil(Ho/m), Tw = ceil(Wo/m); its input origin is (m*tx - pad, m*ty - pad) (Section 4.1's
+ * tiling with overlap r-1 = 2; the collapse of (i, x~, y~) to b is Eq. (12)).
+ */
+#ifndef WINO_H_
+#define WINO_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    WINO_OK = 0,
+    WINO_EINVAL = 1,       /* null / misaligned pointer, non-positive extent, bad enum */
+    WINO_EUNSUPPORTED = 2, /* m not in {2,4}, pad not in {0,1}, empty output, unsupported dtype */
+    WINO_EWORKSPACE = 3,   /* workspace smaller than wino_workspace_bytes() */
+    WINO_EHIP = 4          /* a HIP call failed; see wino_last_hip_error() */
+} wino_status_t;
+
+typedef enum { WINO_F32 = 0, WINO_F16 = 1 } wino_dtype_t;
+
+/* Variant selection for wino_conv2d_fwd_ex (`flags`). 0 lets the library choose. */
+#define WINO_FLAG_AUTO 0u
+#define WINO_FLAG_UNFUSED 1u      /* four separate stages exactly as in Algorithm 1 */
+#define WINO_FLAG_FUSED_OUTPUT 2u /* inverse transform applied in the multiply kernel's epilogue */
+
+const char *wino_status_string(int status);
+/* hipError_t of the most recent failing HIP call made by the calling thread (0 if none). */
+int wino_last_hip_error(void);
+
+/* ---- host-side integer bookkeeping (no GPU involved) ------------------------------------ */
+
+/* Number of tiles P = N * ceil(Ho/m) * ceil(Wo/m) (Algorithm 1, first line); -1 on bad input. */
+long long wino_num_tiles(int N, int H, int W, int pad, int m);
+/* out[0..4] = image i, tile row tx, tile column ty, input row m*tx-pad, input column m*ty-pad
+ * of tile b. */
+int wino_tile_coords(int N, int H, int W, int pad, int m, long long b, int out[5]);
+/* Padded extents used by the transform-domain layouts above. P may be 0 when only Kp, Cp are
+ * wanted (then *Pp = 0). Any output pointer may be NULL. */
+int wino_padded_dims(int K, int C, long long P, int m, int dt, int *Kp, int *Cp, long long *Pp);
+/* Element offsets (in units of the element type) into U, V and M; -1 on bad input. */
+long long wino_u_offset(int K, int C, int m, int dt, int xi, int nu, int k, int c);
+long long wino_v_offset(int C, long long P, int m, int dt, int xi, int nu, int c, long long b);
+long long wino_m_offset(int K, long long P, int m, int xi, int nu, int k, long long b);
+
+/* Buffer sizes in bytes (0 on bad input). */
+size_t wino_filter_bytes(int K, int C, int m, int dt);           /* U */
+size_t wino_v_bytes(int C, long long P, int m, int dt);          /* V */
+size_t wino_m_bytes(int K, long long P, int m);                  /* M */
+/* Workspace wino_conv2d_fwd_ex needs: room for U, V and M of this problem. */
+size_t wino_workspace_bytes(int N, int C, int H, int W, int K, int pad, int m, int dt);
+
+/* ---- the four stages of Algorithm 1, one entry point each ------------------------------- */
+
+/* Loop 1: u = G g G^T for every (k, c), scattered to U (Algorithm 1; the "FX" external filter
+ * transform of Section 6).  fp32 G -> fp32 U. */
+int wino_filter_transform(int K, int C, int m, const void *G, void *U, void *stream);
+/* Same with a storage type: G and U both of type dt; arithmetic in fp32, one rounding to dt. */
+int wino_filter_transform_ex(int K, int C, int m, int dt, const void *G, void *U, void *stream);
+/* Loop 2: gather tile d_{c,b} (zeros outside the image), v = B^T d B, scatter to V. */
+int wino_input_transform(int N, int C, int H, int W, int pad, int m, int dt, const void *D, void *V,
+                         void *stream);
+/* Loop 3: M^(xi,nu) = U^(xi,nu) V^(xi,nu) for all alpha^2 components (Eq. (13)). */
+int wino_batched_gemm(int K, int C, long long P, int m, int dt, const void *U, const void *V, void *M,
+                      void *stream);
+/* Loop 4: gather m_{k,b} from M, Y_{k,b} = A^T m A, write the outputs that fall inside
+ * Ho x Wo.  y_dt is the storage type of Y. */
+int wino_output_transform(int N, int K, int H, int W, int pad, int m, int y_dt, const void *M, void *Y,
+                          void *stream);
+
+/* ---- whole layer ------------------------------------------------------------------------ */
+
+/* fp32 layer with F(m x m, 3 x 3): all four loops of Algorithm 1.  Uses a workspace the
+ * library allocates on first use and grows when needed (one per process, so calls on
+ * different streams must not overlap); released by wino_shutdown(). */
+int wino_conv2d_fwd(int N, int C, int H, int W, int K, int pad, int m, const void *D, const void *G, void *Y,
+                    void *stream);
+/* General form.  U may be NULL (then G is transformed into the workspace first) or the output
+ * of wino_filter_transform_ex for the same (K, C, m, dt) (then G may be NULL).  Never
+ * allocates.  `workspace` must hold wino_workspace_bytes() bytes. */
+int wino_conv2d_fwd_ex(int N, int C, int H, int W, int K, int pad, int m, int dt, int y_dt, const void *D,
+                       const void *G, const void *U, void *Y, void *workspace, size_t workspace_bytes,
+                       unsigned flags, void *stream);
+/* Eq. (1) evaluated directly on the GPU: any R x S filter, stride and padding; for layers the
+ * fast algorithm does not cover (e.g. the 3-channel first layer of Table 3). */
+int direct_conv2d_fwd(int N, int C, int H, int W, int K, int R, int S, int pad, int stride, int dt,
+                      const void *D, const void *G, void *Y, void *stream);
+
+/* Frees the cached workspace of wino_conv2d_fwd (synchronises the device first). */
+int wino_shutdown(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WINO_H_ */

@@ -1,0 +1,148 @@
+// Loop 3 of Algorithm 1 (Lavin & Gray): the alpha^2 independent products
+// M^(xi,nu) = U^(xi,nu) V^(xi,nu) (Eq. (13)), K x C by C x P each, on the MFMA units.
+#include "wino_internal.h"
+
+namespace wino {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// fp32 operands, v_mfma_f32_32x32x2_f32.  A workgroup of 4 wavefronts (2 x 2) owns a BM x BN
+// block of one M^(e); every wavefront owns (BM/2) x (BN/2) of it as TM x TN MFMA tiles of
+// 32 x 32.  Both operands are stored reduction-index-major (U[e][c][k], V[e][c][b]), so a
+// BK-deep slab is BK contiguous row segments: loaded with 16-byte accesses, kept in LDS as
+// [c][k] / [c][b], and read by the MFMA lanes (lane = column + 32 * (c & 1)) without bank
+// conflicts.  LDS slabs are double buffered: the next slab's global loads are in flight
+// while the current one feeds the MFMAs.
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__ U, const float *__restrict__ V,
+                                                       float *__restrict__ Mo, int Kp, int Cp, int Pp, int tiles_m,
+                                                       int tiles_n)
+{
+    constexpr int BK = 16;
+    constexpr int TM = BM / 64, TN = BN / 64;
+    constexpr int A4 = BK * BM / 4, B4 = BK * BN / 4;          // float4s per slab
+    constexpr int AL = (A4 + 255) / 256, BL = (B4 + 255) / 256; // float4 loads per thread
+    __shared__ float As[2][BK * BM];
+    __shared__ float Bs[2][BK * BN];
+
+    int bid = blockIdx.x;
+    const int tm_i = bid % tiles_m;
+    bid /= tiles_m;
+    const int tn_i = bid % tiles_n;
+    const int e = bid / tiles_n;
+    const int k0 = tm_i * BM, p0 = tn_i * BN;
+
+    const float *Ue = U + (size_t)e * Cp * Kp;
+    const float *Ve = V + (size_t)e * Cp * Pp;
+    float *Me = Mo + (size_t)e * Kp * Pp;
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int li = lane & 31, lg = lane >> 5;
+
+    float4 ra[AL], rb[BL];
+    auto load_global = [&](int c0) {
+#pragma unroll
+        for (int j = 0; j < AL; ++j) {
+            const int idx = tid + j * 256;
+            const int row = idx / (BM / 4), col = (idx % (BM / 4)) * 4;
+            ra[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (idx < A4 && k0 + col < Kp)
+                ra[j] = *reinterpret_cast<const float4 *>(Ue + (size_t)(c0 + row) * Kp + k0 + col);
+        }
+#pragma unroll
+        for (int j = 0; j < BL; ++j) {
+            const int idx = tid + j * 256;
+            const int row = idx / (BN / 4), col = (idx % (BN / 4)) * 4;
+            rb[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (idx < B4 && p0 + col < Pp)
+                rb[j] = *reinterpret_cast<const float4 *>(Ve + (size_t)(c0 + row) * Pp + p0 + col);
+        }
+    };
+    auto store_lds = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < AL; ++j) {
+            const int idx = tid + j * 256;
+            if (idx < A4) *reinterpret_cast<float4 *>(&As[buf][idx * 4]) = ra[j];
+        }
+#pragma unroll
+        for (int j = 0; j < BL; ++j) {
+            const int idx = tid + j * 256;
+            if (idx < B4) *reinterpret_cast<float4 *>(&Bs[buf][idx * 4]) = rb[j];
+        }
+    };
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int nk = Cp / BK;
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) load_global((kt + 1) * BK);
+        const float *as = &As[cur][wm * (BM / 2) + li];
+        const float *bs = &Bs[cur][wn * (BN / 2) + li];
+#pragma unroll
+        for (int kk = 0; kk < BK / 2; ++kk) {
+            float a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = as[(2 * kk + lg) * BM + i * 32];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = bs[(2 * kk + lg) * BN + j * 32];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) store_lds(cur ^ 1);
+        __syncthreads();
+    }
+
+    // accumulator register r of lane (li, lg) is row 8*(r/4) + 4*lg + r%4, column li of its tile
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = p0 + wn * (BN / 2) + j * 32 + li;
+            const int rbase = k0 + wm * (BM / 2) + i * 32 + 4 * lg;
+            if (col < Pp) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = rbase + 8 * (r / 4) + (r % 4);
+                    if (row < Kp) Me[(size_t)row * Pp + col] = acc[i][j][r];
+                }
+            }
+        }
+}
+
+template <int BM, int BN>
+static hipError_t launch_f32(const Geo &g, const float *U, const float *V, float *M, hipStream_t s)
+{
+    const int tiles_m = (g.Kp + BM - 1) / BM, tiles_n = (g.Pp + BN - 1) / BN;
+    const long long blocks = (long long)tiles_m * tiles_n * g.a2;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    gemm_f32_kernel<BM, BN><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(U, V, M, g.Kp, g.Cp, g.Pp, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+hipError_t launch_batched_gemm(const Geo &g, const void *U, const void *V, float *M, hipStream_t s)
+{
+    if (g.dt != WINO_F32) return hipErrorNotSupported;
+    const float *u = (const float *)U, *v = (const float *)V;
+    const bool wide_m = g.Kp >= 128, wide_n = g.Pp >= 128;
+    if (wide_m && wide_n) return launch_f32<128, 128>(g, u, v, M, s);
+    if (wide_m) return launch_f32<128, 64>(g, u, v, M, s);
+    if (wide_n) return launch_f32<64, 128>(g, u, v, M, s);
+    return launch_f32<64, 64>(g, u, v, M, s);
+}
+
+}  // namespace wino

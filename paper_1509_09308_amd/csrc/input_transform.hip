@@ -1,0 +1,92 @@
+// Loop 2 of Algorithm 1 (Lavin & Gray): gather each alpha x alpha input tile d_{c,b} (tiles
+// overlap by r-1 = 2, zeros outside the image -- the implicit zero padding of Section 6),
+// v = B^T d B (Eq. (8)), scatter to the alpha^2 matrices V^(xi,nu)[c][b].
+// Bound by memory traffic: every input element is needed once, alpha^2/m^2 values are written
+// per input element.
+#include "wino_internal.h"
+#include "transforms.h"
+
+namespace wino {
+
+template <typename T> __device__ __forceinline__ float ld_in(const T *p);
+template <> __device__ __forceinline__ float ld_in<float>(const float *p) { return *p; }
+template <> __device__ __forceinline__ float ld_in<__half>(const __half *p) { return __half2float(*p); }
+
+// One thread per (c, b); b is the fastest index of a workgroup so the stores to every
+// V^(xi,nu) row are contiguous across a wavefront.  Channels c >= C and tiles b >= P are
+// padding and are written as zeros.
+template <int M, typename T>
+__global__ __launch_bounds__(256) void input_transform_kernel(const T *__restrict__ D, T *__restrict__ V, Geo g)
+{
+    constexpr int A = M + 2;
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    const int c = blockIdx.y;
+    if (b >= g.Pp) return;
+    float d[A][A];
+#pragma unroll
+    for (int p = 0; p < A; ++p)
+#pragma unroll
+        for (int q = 0; q < A; ++q) d[p][q] = 0.0f;
+    if (c < g.C && b < g.P) {
+        const int ty = b % g.Tw;
+        const int t2 = b / g.Tw;
+        const int tx = t2 % g.Th;
+        const int i = t2 / g.Th;
+        const int x0 = M * tx - g.pad, y0 = M * ty - g.pad;
+        const T *src = D + ((size_t)i * g.C + c) * g.H * g.W;
+#pragma unroll
+        for (int p = 0; p < A; ++p) {
+            const int x = x0 + p;
+            if (x >= 0 && x < g.H) {
+#pragma unroll
+                for (int q = 0; q < A; ++q) {
+                    const int y = y0 + q;
+                    if (y >= 0 && y < g.W) d[p][q] = ld_in<T>(src + (size_t)x * g.W + y);
+                }
+            }
+        }
+    }
+    // t = B^T d (columns), v = t B (rows)
+    float t[A][A], v[A][A];
+#pragma unroll
+    for (int q = 0; q < A; ++q) {
+        float col[A], o[A];
+#pragma unroll
+        for (int p = 0; p < A; ++p) col[p] = d[p][q];
+        bt_mul<M>(col, o);
+#pragma unroll
+        for (int p = 0; p < A; ++p) t[p][q] = o[p];
+    }
+#pragma unroll
+    for (int p = 0; p < A; ++p) bt_mul<M>(t[p], v[p]);
+#pragma unroll
+    for (int xi = 0; xi < A; ++xi)
+#pragma unroll
+        for (int nu = 0; nu < A; ++nu) {
+            const int e = xi * A + nu;
+            if constexpr (sizeof(T) == 4) {
+                V[((size_t)e * g.Cp + c) * g.Pp + b] = v[xi][nu];
+            } else {
+                V[(((size_t)e * (g.Cp / 8) + c / 8) * g.Pp + b) * 8 + (c % 8)] = __float2half_rn(v[xi][nu]);
+            }
+        }
+}
+
+hipError_t launch_input_transform(const Geo &g, const void *D, void *V, hipStream_t s)
+{
+    dim3 grid((g.Pp + 255) / 256, g.Cp), block(256);
+    if (g.dt == WINO_F32) {
+        if (g.m == 2)
+            input_transform_kernel<2, float><<<grid, block, 0, s>>>((const float *)D, (float *)V, g);
+        else
+            input_transform_kernel<4, float><<<grid, block, 0, s>>>((const float *)D, (float *)V, g);
+    } else {
+        if (g.m == 2)
+            input_transform_kernel<2, __half><<<grid, block, 0, s>>>((const __half *)D, (__half *)V, g);
+        else
+            input_transform_kernel<4, __half><<<grid, block, 0, s>>>((const __half *)D, (__half *)V, g);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace wino

@@ -1,0 +1,37 @@
+// Internal declarations shared by the kernels and the C-ABI layer of libwino (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/wino.h"
+
+namespace wino {
+
+// Problem geometry and the padded extents of the transform-domain buffers.
+struct Geo {
+    int m, alpha, a2;      // output tile, input tile (m + 2), number of components alpha^2
+    int N, C, H, W, K, pad;
+    int Ho, Wo, Th, Tw;    // output extent and tiles per image
+    int P;                 // number of tiles N*Th*Tw
+    int Kp, Cp, Pp;        // padded extents of U, V, M
+    int dt;                // storage type of D, G, U, V
+};
+
+inline int round_up(long long x, int q) { return (int)(((x + q - 1) / q) * q); }
+
+// Padding rules: K to the MFMA tile edge, C to the reduction chunk, P to the MFMA tile edge.
+inline int pad_k(int K) { return round_up(K, 32); }
+inline int pad_c(int C, int dt) { return round_up(C, dt == WINO_F16 ? 32 : 16); }
+inline int pad_p(long long P) { return round_up(P, 32); }
+
+// Kernel launchers (each enqueues on `s` and returns the launch status).
+hipError_t launch_filter_transform(const Geo &g, const void *G, void *U, hipStream_t s);
+hipError_t launch_input_transform(const Geo &g, const void *D, void *V, hipStream_t s);
+hipError_t launch_batched_gemm(const Geo &g, const void *U, const void *V, float *M, hipStream_t s);
+hipError_t launch_output_transform(const Geo &g, int y_dt, const float *M, void *Y, hipStream_t s);
+hipError_t launch_direct_conv(int N, int C, int H, int W, int K, int R, int S, int pad, int stride, int dt,
+                              const void *D, const void *G, void *Y, hipStream_t s);
+
+}  // namespace wino

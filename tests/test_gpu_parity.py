@@ -1,0 +1,104 @@
+"""GPU parity: the HIP path through the C ABI against the fp64 direct-convolution oracle on the
+same seeded inputs.  Metric: normwise relative error ||Y^ - Y||_F / ||Y||_F; bounds: 1e-5 for
+fp32 F(2x2,3x3), 1e-4 for fp32 F(4x4,3x3), 5e-3 for fp16 storage with fp32 accumulation."""
+import numpy as np
+import pytest
+
+from oracle import direct
+from paper_1509_09308_amd import synth
+from gpu_util import TOL, require_gpu, rel_err, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_full(w, D, G, pad, m, pre_transform=True):
+    d, g = to_gpu(D), to_gpu(G)
+    if pre_transform:
+        U = w.wino_filter_transform(g, m)
+        return w.wino_conv2d_fwd_ex(d, U=U, K=G.shape[0], pad=pad, m=m).cpu().numpy()
+    return w.wino_conv2d_fwd_ex(d, G=g, pad=pad, m=m).cpu().numpy()
+
+
+def test_config1_small_layer():
+    """N=1, C=K=32, 56x56, fp32, F(2x2,3x3) only."""
+    torch, w = require_gpu()
+    D, G = synth.make_layer(1, 32, 56, 56, 32, synth.layer_seed(1, 0))
+    ref = direct.conv2d_fwd(D, G, pad=1)
+    for pre in (True, False):
+        Y = _run_full(w, D, G, 1, 2, pre)
+        assert rel_err(Y, ref) <= TOL[("f32", 2)]
+    Y = w.wino_conv2d_fwd(to_gpu(D), to_gpu(G), pad=1, m=2).cpu().numpy()
+    assert rel_err(Y, ref) <= TOL[("f32", 2)]
+
+
+@pytest.mark.parametrize("m", [2, 4])
+def test_config2_vgg_layer(m):
+    """N=8, C=K=512, 28x28, fp32, both algorithms."""
+    torch, w = require_gpu()
+    D, G = synth.make_layer(8, 512, 28, 28, 512, synth.layer_seed(2, 0))
+    ref = direct.conv2d_fwd(D, G, pad=1)
+    Y = _run_full(w, D, G, 1, m)
+    e = rel_err(Y, ref)
+    print("config2 m=%d rel err %.3e" % (m, e))
+    assert e <= TOL[("f32", m)]
+
+
+@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("shape", [(1, 1, 3, 3, 1, 1), (1, 1, 4, 4, 1, 0), (2, 3, 5, 7, 4, 1), (1, 19, 13, 29, 70, 1),
+                                   (3, 33, 14, 14, 65, 1), (2, 16, 31, 18, 130, 0), (5, 130, 9, 9, 40, 1),
+                                   (1, 7, 67, 131, 9, 1)])
+def test_ragged_and_degenerate_shapes(m, shape):
+    """Odd extents, single-tile images, pad 0, channel and filter counts that do not fill a tile."""
+    torch, w = require_gpu()
+    N, C, H, W, K, pad = shape
+    D, G = synth.make_layer(N, C, H, W, K, seed=sum(shape) + m)
+    ref = direct.conv2d_fwd(D, G, pad=pad)
+    Y = _run_full(w, D, G, pad, m)
+    assert Y.shape == ref.shape
+    assert rel_err(Y, ref) <= TOL[("f32", m)]
+
+
+@pytest.mark.parametrize("layer", range(1, 13))
+def test_config3_vgg16_stack_n1(layer):
+    """Every Winograd-eligible VGG-16 layer at N=1, fp32, both algorithms, whole output."""
+    torch, w = require_gpu()
+    name, C, HW, K = synth.VGG16_LAYERS[layer]
+    D, G = synth.make_layer(1, C, HW, HW, K, synth.layer_seed(3, layer))
+    ref = direct.conv2d_fwd(D, G, pad=1)
+    for m in (2, 4):
+        e = rel_err(_run_full(w, D, G, 1, m), ref)
+        print("%s m=%d rel err %.3e" % (name, m, e))
+        assert e <= TOL[("f32", m)]
+
+
+def test_config3_first_layer_direct():
+    torch, w = require_gpu()
+    name, C, HW, K = synth.VGG16_LAYERS[0]
+    D, G = synth.make_layer(1, C, HW, HW, K, synth.layer_seed(3, 0))
+    ref = direct.conv2d_fwd(D, G, pad=1)
+    Y = w.direct_conv2d_fwd(to_gpu(D), to_gpu(G), pad=1).cpu().numpy()
+    assert rel_err(Y, ref) <= 1e-5
+
+
+@pytest.mark.parametrize("layer", [1, 3, 6, 9, 12])
+def test_config4_full_size_sampled(layer):
+    """N=64 fp32 at the benchmark's launch configuration (pre-transformed filters, caller
+    workspace; F(4x4) where 4 divides the image, F(2x2) for 14x14): outputs sampled at random
+    and at the tensor corners are recomputed one by one by the oracle."""
+    torch, w = require_gpu()
+    name, C, HW, K = synth.VGG16_LAYERS[layer]
+    N = 64
+    m = 4 if HW % 4 == 0 else 2
+    D, G = synth.make_layer(N, C, HW, HW, K, synth.layer_seed(4, layer))
+    d, g = to_gpu(D), to_gpu(G)
+    U = w.wino_filter_transform(g, m)
+    ws = w.alloc_workspace(N, C, HW, HW, K, 1, m)
+    Y = w.wino_conv2d_fwd_ex(d, U=U, K=K, pad=1, m=m, workspace=ws)
+    pts = synth.sample_points((N, K, HW, HW), 4000, seed=layer)
+    idx = torch.from_numpy(pts.astype(np.int64)).cuda()
+    got = Y[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy()
+    ref = direct.conv2d_points(D, G, pts, pad=1)
+    e = rel_err(got, ref)
+    print("%s N=64 m=%d sampled rel err %.3e" % (name, m, e))
+    assert e <= TOL[("f32", m)]
+    assert bool(torch.isfinite(Y).all())

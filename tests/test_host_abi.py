@@ -1,0 +1,150 @@
+"""Host-side checks of libwino.so that need no GPU: the library loads, exports what wino.h
+declares, rejects bad arguments with status codes, and its integer bookkeeping (tile maps,
+padded extents, buffer offsets) agrees bit for bit with the oracle's."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1509_09308_amd as w
+from paper_1509_09308_amd import binding, build
+from oracle import winograd as wg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    build.ensure_built()
+    return binding.lib()
+
+
+def test_exports_every_declared_symbol(L):
+    text = open(os.path.join(ROOT, "include", "wino.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = re.findall(r"\b(wino_\w+|direct_conv2d_fwd)\s*\(", text)
+    declared = sorted(set(declared))
+    assert len(declared) >= 20
+    assert sorted(binding.EXPORTS) == declared
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_status_strings(L):
+    seen = {L.wino_status_string(s) for s in range(5)}
+    assert len(seen) == 5 and all(seen)
+    assert L.wino_status_string(99) == b"unknown status"
+
+
+def test_argument_validation_without_gpu(L):
+    null = None
+    fake = ctypes.c_void_p(0x1000)       # aligned, never dereferenced: checks fail first
+    odd = ctypes.c_void_p(0x1004)
+    # unsupported algorithm / padding
+    assert L.wino_conv2d_fwd(1, 4, 8, 8, 4, 1, 3, fake, fake, fake, null) == w.WINO_EUNSUPPORTED
+    assert L.wino_conv2d_fwd(1, 4, 8, 8, 4, 2, 4, fake, fake, fake, null) == w.WINO_EUNSUPPORTED
+    assert L.wino_conv2d_fwd(1, 4, 2, 2, 4, 0, 2, fake, fake, fake, null) == w.WINO_EUNSUPPORTED  # empty output
+    # non-positive extents, null and misaligned pointers
+    assert L.wino_conv2d_fwd(0, 4, 8, 8, 4, 1, 2, fake, fake, fake, null) == w.WINO_EINVAL
+    assert L.wino_conv2d_fwd(1, 4, 8, 8, -1, 1, 2, fake, fake, fake, null) == w.WINO_EINVAL
+    assert L.wino_conv2d_fwd(1, 4, 8, 8, 4, 1, 2, null, fake, fake, null) == w.WINO_EINVAL
+    assert L.wino_conv2d_fwd(1, 4, 8, 8, 4, 1, 2, fake, odd, fake, null) == w.WINO_EINVAL
+    assert L.wino_filter_transform(4, 4, 2, null, fake, null) == w.WINO_EINVAL
+    assert L.wino_filter_transform(4, 4, 5, fake, fake, null) == w.WINO_EUNSUPPORTED
+    assert L.wino_filter_transform_ex(4, 4, 2, 7, fake, fake, null) == w.WINO_EINVAL
+    assert L.wino_input_transform(1, 4, 8, 8, 1, 2, 0, fake, null, null) == w.WINO_EINVAL
+    assert L.wino_batched_gemm(4, 4, 0, 2, 0, fake, fake, fake, null) == w.WINO_EINVAL
+    assert L.wino_output_transform(1, 4, 8, 8, 1, 2, 0, fake, odd, null) == w.WINO_EINVAL
+    assert L.direct_conv2d_fwd(1, 3, 8, 8, 4, 3, 3, 1, 0, 0, fake, fake, fake, null) == w.WINO_EINVAL
+    assert L.direct_conv2d_fwd(1, 3, 2, 2, 4, 5, 5, 0, 1, 0, fake, fake, fake, null) == w.WINO_EUNSUPPORTED
+    # workspace too small / both G and U missing
+    need = L.wino_workspace_bytes(1, 4, 8, 8, 4, 1, 2, 0)
+    assert need > 0
+    assert L.wino_conv2d_fwd_ex(1, 4, 8, 8, 4, 1, 2, 0, 0, fake, fake, null, fake, fake, need - 1, 0,
+                                null) == w.WINO_EWORKSPACE
+    assert L.wino_conv2d_fwd_ex(1, 4, 8, 8, 4, 1, 2, 0, 0, fake, null, null, fake, fake, need, 0,
+                                null) == w.WINO_EINVAL
+    assert L.wino_conv2d_fwd_ex(1, 4, 8, 8, 4, 1, 2, 0, 0, fake, fake, null, fake, fake, need, 99,
+                                null) == w.WINO_EINVAL
+    # size queries on bad input
+    assert L.wino_workspace_bytes(1, 4, 8, 8, 4, 1, 3, 0) == 0
+    assert L.wino_filter_bytes(0, 4, 2, 0) == 0
+    assert L.wino_num_tiles(1, 8, 8, 3, 2) == -1
+
+
+SHAPES = [(1, 56, 56, 1, 2), (8, 28, 28, 1, 2), (8, 28, 28, 1, 4), (1, 224, 224, 1, 4), (2, 112, 112, 1, 4),
+          (3, 14, 14, 1, 4), (3, 14, 14, 1, 2), (2, 7, 9, 1, 4), (2, 7, 9, 0, 2), (1, 5, 5, 0, 4), (64, 14, 14, 1, 4)]
+
+
+@pytest.mark.parametrize("N,H,W,pad,m", SHAPES)
+def test_tile_bookkeeping_matches_oracle_exhaustively(L, N, H, W, pad, m):
+    P = w.wino_num_tiles(N, H, W, pad, m)
+    assert P == wg.num_tiles(N, H, W, pad, m)
+    step = 1 if P <= 20000 else 7
+    for b in list(range(0, P, step)) + [P - 1]:
+        assert w.wino_tile_coords(N, H, W, pad, m, b) == wg.tile_of(b, H, W, pad, m)
+    out = (ctypes.c_int * 5)()
+    assert L.wino_tile_coords(N, H, W, pad, m, P, out) == w.WINO_EINVAL
+    assert L.wino_tile_coords(N, H, W, pad, m, -1, out) == w.WINO_EINVAL
+
+
+@pytest.mark.parametrize("K,C,P,m,dt", [(64, 64, 3136, 4, 0), (32, 32, 784, 2, 0), (512, 512, 49, 2, 0),
+                                         (5, 3, 17, 4, 0), (70, 33, 100, 2, 1), (512, 512, 16, 4, 1)])
+def test_padded_dims_offsets_and_sizes(L, K, C, P, m, dt):
+    a = m + 2
+    Kp, Cp, Pp = w.wino_padded_dims(K, C, P, m, dt)
+    assert Kp >= K and Cp >= C and Pp >= P and Kp % 32 == 0 and Pp % 32 == 0 and Cp % (32 if dt else 16) == 0
+    assert Kp - K < 32 and Pp - P < 32
+    es = 2 if dt else 4
+    assert w.wino_filter_bytes(K, C, m, dt) == a * a * Kp * Cp * es
+    assert w.wino_v_bytes(C, P, m, dt) == a * a * Cp * Pp * es
+    assert w.wino_m_bytes(K, P, m) == a * a * Kp * Pp * 4
+    rng = np.random.default_rng(K + C)
+    seen_u, seen_v, seen_m = set(), set(), set()
+    for _ in range(300):
+        xi, nu = int(rng.integers(a)), int(rng.integers(a))
+        k, c, b = int(rng.integers(Kp)), int(rng.integers(Cp)), int(rng.integers(Pp))
+        e = xi * a + nu
+        ou, ov, om = (w.wino_u_offset(K, C, m, dt, xi, nu, k, c), w.wino_v_offset(C, P, m, dt, xi, nu, c, b),
+                      w.wino_m_offset(K, P, m, xi, nu, k, b))
+        if dt == 0:
+            assert ou == (e * Cp + c) * Kp + k and ov == (e * Cp + c) * Pp + b
+        else:
+            assert ou == ((e * (Cp // 8) + c // 8) * Kp + k) * 8 + c % 8
+            assert ov == ((e * (Cp // 8) + c // 8) * Pp + b) * 8 + c % 8
+        assert om == (e * Kp + k) * Pp + b
+        assert 0 <= ou < a * a * Kp * Cp and 0 <= ov < a * a * Cp * Pp and 0 <= om < a * a * Kp * Pp
+        seen_u.add(ou), seen_v.add(ov), seen_m.add(om)
+    assert w.wino_u_offset(K, C, m, dt, a, 0, 0, 0) == -1
+    assert w.wino_v_offset(C, P, m, dt, 0, 0, Cp, 0) == -1
+    assert w.wino_m_offset(K, P, m, 0, 0, 0, Pp) == -1
+
+
+def test_pack_unpack_round_trip_host_only():
+    """The binding's layout helpers invert each other (checked on CPU tensors)."""
+    rng = np.random.default_rng(0)
+    for dt, npdt in ((0, np.float32), (1, np.float16)):
+        for m in (2, 4):
+            a = m + 2
+            u = rng.standard_normal((a, a, 5, 19)).astype(npdt)
+            v = rng.standard_normal((a, a, 19, 45)).astype(npdt)
+            mm = rng.standard_normal((a, a, 5, 45)).astype(np.float32)
+            assert np.array_equal(w.unpack_u(w.pack_u(u, m, dt, "cpu"), 5, 19, m, dt), u)
+            assert np.array_equal(w.unpack_v(w.pack_v(v, m, dt, "cpu"), 19, 45, m, dt), v)
+            assert np.array_equal(w.unpack_m(w.pack_m(mm, m, "cpu"), 5, 45, m), mm)
+            # a spot check of the packed position against the C offset function
+            flat = w.pack_u(u, m, dt, "cpu").numpy()
+            assert flat[w.wino_u_offset(5, 19, m, dt, 1, 2, 3, 17)] == u[1, 2, 3, 17]
+            flat = w.pack_v(v, m, dt, "cpu").numpy()
+            assert flat[w.wino_v_offset(19, 45, m, dt, 2, 1, 18, 44)] == v[2, 1, 18, 44]
+
+
+def test_flop_accounting_matches_table3(golden):
+    """bench.py's direct-convolution flop formula reproduces Table 3 of the paper."""
+    import bench
+    for name, depth, C, HW, K, gf in golden("table3_vgg_e_gflops.txt"):
+        if name != "total":
+            got = int(depth) * bench.direct_flops(1, int(C), int(HW), int(HW), int(K)) / 1e9
+            assert abs(got - float(gf)) < 0.0051
