@@ -124,6 +124,139 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
         }
 }
 
+// fp16 operands, fp32 accumulation, v_mfma_f32_32x32x16_f16.  Operands are stored as
+// [e][c/8][row][c%8]: the 8 reduction values a lane feeds to one MFMA are one 16-byte word, a
+// BK=32 slab is 4 contiguous runs of 16-byte words per operand, and LDS keeps the same order.
+// Lanes 0-31 take the even 8-channel group of a 16-deep MFMA step, lanes 32-63 the odd one,
+// for both operands alike, so every product pairs equal channels.
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void gemm_f16_kernel(const uint4 *__restrict__ U, const uint4 *__restrict__ V,
+                                                       float *__restrict__ Mo, int Kp, int Cp, int Pp, int tiles_m,
+                                                       int tiles_n)
+{
+    constexpr int BK = 32, G8 = BK / 8;
+    constexpr int TM = BM / 64, TN = BN / 64;
+    constexpr int A4 = G8 * BM, B4 = G8 * BN;                  // 16-byte words per slab
+    constexpr int AL = (A4 + 255) / 256, BL = (B4 + 255) / 256;
+    __shared__ uint4 As[2][A4];
+    __shared__ uint4 Bs[2][B4];
+
+    int bid = blockIdx.x;
+    const int tm_i = bid % tiles_m;
+    bid /= tiles_m;
+    const int tn_i = bid % tiles_n;
+    const int e = bid / tiles_n;
+    const int k0 = tm_i * BM, p0 = tn_i * BN;
+    const int C8 = Cp / 8;
+
+    const uint4 *Ue = U + (size_t)e * C8 * Kp;
+    const uint4 *Ve = V + (size_t)e * C8 * Pp;
+    float *Me = Mo + (size_t)e * Kp * Pp;
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int li = lane & 31, lg = lane >> 5;
+
+    uint4 ra[AL], rb[BL];
+    auto load_global = [&](int g0) {
+#pragma unroll
+        for (int j = 0; j < AL; ++j) {
+            const int idx = tid + j * 256;
+            const int grp = idx / BM, col = idx % BM;
+            ra[j] = make_uint4(0, 0, 0, 0);
+            if (idx < A4 && k0 + col < Kp) ra[j] = Ue[(size_t)(g0 + grp) * Kp + k0 + col];
+        }
+#pragma unroll
+        for (int j = 0; j < BL; ++j) {
+            const int idx = tid + j * 256;
+            const int grp = idx / BN, col = idx % BN;
+            rb[j] = make_uint4(0, 0, 0, 0);
+            if (idx < B4 && p0 + col < Pp) rb[j] = Ve[(size_t)(g0 + grp) * Pp + p0 + col];
+        }
+    };
+    auto store_lds = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < AL; ++j) {
+            const int idx = tid + j * 256;
+            if (idx < A4) As[buf][idx] = ra[j];
+        }
+#pragma unroll
+        for (int j = 0; j < BL; ++j) {
+            const int idx = tid + j * 256;
+            if (idx < B4) Bs[buf][idx] = rb[j];
+        }
+    };
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int nk = Cp / BK;
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) load_global((kt + 1) * G8);
+        const uint4 *as = &As[cur][wm * (BM / 2) + li];
+        const uint4 *bs = &Bs[cur][wn * (BN / 2) + li];
+#pragma unroll
+        for (int kk = 0; kk < G8 / 2; ++kk) {
+            halfx8 a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const uint4 t = as[(2 * kk + lg) * BM + i * 32];
+                a[i] = *reinterpret_cast<const halfx8 *>(&t);
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const uint4 t = bs[(2 * kk + lg) * BN + j * 32];
+                b[j] = *reinterpret_cast<const halfx8 *>(&t);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) store_lds(cur ^ 1);
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = p0 + wn * (BN / 2) + j * 32 + li;
+            const int rbase = k0 + wm * (BM / 2) + i * 32 + 4 * lg;
+            if (col < Pp) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = rbase + 8 * (r / 4) + (r % 4);
+                    if (row < Kp) Me[(size_t)row * Pp + col] = acc[i][j][r];
+                }
+            }
+        }
+}
+
+template <int BM, int BN>
+static hipError_t launch_f16(const Geo &g, const void *U, const void *V, float *M, hipStream_t s)
+{
+    const int tiles_m = (g.Kp + BM - 1) / BM, tiles_n = (g.Pp + BN - 1) / BN;
+    const long long blocks = (long long)tiles_m * tiles_n * g.a2;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    gemm_f16_kernel<BM, BN><<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const uint4 *)U, (const uint4 *)V, M, g.Kp,
+                                                                         g.Cp, g.Pp, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
 template <int BM, int BN>
 static hipError_t launch_f32(const Geo &g, const float *U, const float *V, float *M, hipStream_t s)
 {
@@ -136,9 +269,14 @@ static hipError_t launch_f32(const Geo &g, const float *U, const float *V, float
 
 hipError_t launch_batched_gemm(const Geo &g, const void *U, const void *V, float *M, hipStream_t s)
 {
-    if (g.dt != WINO_F32) return hipErrorNotSupported;
-    const float *u = (const float *)U, *v = (const float *)V;
     const bool wide_m = g.Kp >= 128, wide_n = g.Pp >= 128;
+    if (g.dt == WINO_F16) {
+        if (wide_m && wide_n) return launch_f16<128, 128>(g, U, V, M, s);
+        if (wide_m) return launch_f16<128, 64>(g, U, V, M, s);
+        if (wide_n) return launch_f16<64, 128>(g, U, V, M, s);
+        return launch_f16<64, 64>(g, U, V, M, s);
+    }
+    const float *u = (const float *)U, *v = (const float *)V;
     if (wide_m && wide_n) return launch_f32<128, 128>(g, u, v, M, s);
     if (wide_m) return launch_f32<128, 64>(g, u, v, M, s);
     if (wide_n) return launch_f32<64, 128>(g, u, v, M, s);

@@ -102,3 +102,41 @@ def test_config4_full_size_sampled(layer):
     print("%s N=64 m=%d sampled rel err %.3e" % (name, m, e))
     assert e <= TOL[("f32", m)]
     assert bool(torch.isfinite(Y).all())
+
+
+# ---- fp16 storage of D, G, U, V; fp32 accumulation; fp32 Y (config 5) ----------------------------
+
+@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("shape", [(2, 32, 28, 28, 48, 1), (1, 19, 13, 29, 70, 1), (3, 130, 14, 14, 65, 1),
+                                   (2, 16, 31, 18, 130, 0), (1, 512, 14, 14, 512, 1)])
+def test_f16_storage_layers(m, shape):
+    torch, w = require_gpu()
+    N, C, H, W, K, pad = shape
+    D, G = synth.make_layer(N, C, H, W, K, seed=sum(shape) + m, dtype=np.float16)
+    ref = direct.conv2d_fwd(D, G, pad=pad)            # the oracle reads the same stored fp16 values
+    d, g = to_gpu(D), to_gpu(G)
+    Y = w.wino_conv2d_fwd_ex(d, G=g, pad=pad, m=m)
+    assert Y.dtype == torch.float32
+    e = rel_err(Y.cpu().numpy(), ref)
+    print("fp16 %s m=%d rel err %.3e" % (shape, m, e))
+    assert e <= TOL[("f16", m)]
+
+
+@pytest.mark.parametrize("layer", [1, 4, 9, 12])
+def test_config5_full_size_sampled(layer):
+    """N=32, fp16 storage, F(4x4,3x3) on every layer (ragged at 14x14), benchmark launch shape."""
+    torch, w = require_gpu()
+    name, C, HW, K = synth.VGG16_LAYERS[layer]
+    N, m = 32, 4
+    D, G = synth.make_layer(N, C, HW, HW, K, synth.layer_seed(5, layer), dtype=np.float16)
+    d, g = to_gpu(D), to_gpu(G)
+    ws = w.alloc_workspace(N, C, HW, HW, K, 1, m, w.WINO_F16)
+    Y = w.wino_conv2d_fwd_ex(d, G=g, pad=1, m=m, workspace=ws)
+    pts = synth.sample_points((N, K, HW, HW), 4000, seed=layer)
+    idx = torch.from_numpy(pts.astype(np.int64)).cuda()
+    got = Y[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy()
+    ref = direct.conv2d_points(D.astype(np.float32), G.astype(np.float32), pts, pad=1)
+    e = rel_err(got, ref)
+    print("%s N=32 fp16 m=4 sampled rel err %.3e" % (name, e))
+    assert e <= TOL[("f16", 4)]
+    assert bool(torch.isfinite(Y).all())

@@ -144,3 +144,52 @@ def test_direct_fallback(shape):
     Gi = np.round(G * 16).astype(np.float32)
     Yi = w.direct_conv2d_fwd(to_gpu(Di), to_gpu(Gi), pad=pad, stride=stride).cpu().numpy()
     assert np.array_equal(Yi.astype(np.float64), direct.conv2d_fwd(Di, Gi, pad=pad, stride=stride))
+
+
+# ---- fp16 storage (D, G, U, V in fp16; fp32 accumulation; M and Y in fp32) -----------------------
+
+@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("K,C", [(32, 32), (70, 19), (256, 128)])
+def test_filter_transform_f16(m, K, C):
+    torch, w = require_gpu()
+    rng = np.random.default_rng(K + C + m)
+    G = (rng.integers(-8, 9, (K, C, 3, 3)) * 4).astype(np.float16)
+    U = w.wino_filter_transform(to_gpu(G), m)
+    torch.cuda.synchronize()
+    ref = wg.filter_transform(G.astype(np.float64), m)
+    got = w.unpack_u(U, K, C, m, w.WINO_F16).astype(np.float64)
+    if m == 2:
+        assert np.array_equal(got, ref)                       # exact: entries are halves of small integers
+    else:
+        assert np.abs(got - ref).max() <= 2.0 ** -10 * np.abs(ref).max()   # one fp16 rounding
+    full = w.unpack_u(U, K, C, m, w.WINO_F16, padded=True)
+    assert not full[:, :, K:, :].any() and not full[:, :, :, C:].any()
+
+
+@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("N,C,H,W,pad", [(2, 3, 14, 14, 1), (1, 2, 7, 9, 1), (2, 37, 9, 6, 0), (1, 17, 56, 56, 1)])
+def test_input_transform_f16_bit_exact(m, N, C, H, W, pad):
+    torch, w = require_gpu()
+    rng = np.random.default_rng(H + W + m)
+    D = rng.integers(-3, 4, (N, C, H, W)).astype(np.float16)    # |B^T d B| <= 300: exact in fp16
+    V = w.wino_input_transform(to_gpu(D), pad, m)
+    torch.cuda.synchronize()
+    P = wg.num_tiles(N, H, W, pad, m)
+    ref = wg.data_transform(D.astype(np.float64), pad, m)
+    assert np.array_equal(w.unpack_v(V, C, P, m, w.WINO_F16).astype(np.float64), ref)
+    full = w.unpack_v(V, C, P, m, w.WINO_F16, padded=True)
+    assert not full[:, :, C:, :].any() and not full[:, :, :, P:].any()
+
+
+@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("K,C,P", [(32, 32, 784), (70, 19, 100), (128, 48, 300), (256, 256, 130), (5, 3, 17)])
+def test_batched_gemm_f16_exact_on_integers(m, K, C, P):
+    torch, w = require_gpu()
+    a = m + 2
+    rng = np.random.default_rng(K + C + P + m)
+    u = rng.integers(-4, 5, (a, a, K, C)).astype(np.float16)
+    v = rng.integers(-4, 5, (a, a, C, P)).astype(np.float16)
+    M = w.wino_batched_gemm(w.pack_u(u, m, w.WINO_F16), w.pack_v(v, m, w.WINO_F16), K, C, P, m)
+    torch.cuda.synchronize()
+    ref = wg.multiply(u.astype(np.float64), v.astype(np.float64))
+    assert np.array_equal(w.unpack_m(M, K, P, m).astype(np.float64), ref)
