@@ -264,6 +264,8 @@ def main():
             out["transform_roofline"] = {"bound": "hbm", "achieved": tb / tms / 1e6, "peak": PEAK["hbm_GBs"],
                                          "unit": "GB/s", "frac": tb / tms / 1e6 / PEAK["hbm_GBs"]}
 
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(layers)
     if not args.no_n1 and args.batch != 1:
         del layers, ws
         torch.cuda.empty_cache()
@@ -272,9 +274,6 @@ def main():
         s1 = time_steps(torch, w, l1, ws1, max(args.steps, 20), max(args.warmup, 5))
         f1 = sum(L.flops for L in l1)
         out["n1"] = {"eff_tflops": f1 / s1 / 1e12, "ms_per_step": s1 * 1e3, "images_per_sec": 1.0 / s1}
-        layers = l1
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(layers)
     print(json.dumps(out))
 
 

@@ -56,7 +56,8 @@ typedef enum { WINO_F32 = 0, WINO_F16 = 1 } wino_dtype_t;
 /* Variant selection for wino_conv2d_fwd_ex (`flags`). 0 lets the library choose. */
 #define WINO_FLAG_AUTO 0u
 #define WINO_FLAG_UNFUSED 1u      /* four separate stages exactly as in Algorithm 1 */
-#define WINO_FLAG_FUSED_OUTPUT 2u /* inverse transform applied in the multiply kernel's epilogue */
+#define WINO_FLAG_FUSED 2u        /* loops 2-4 of Algorithm 1 in one kernel: V and M never reach memory
+                                   * (fp32 F(4x4,3x3) only; WINO_EUNSUPPORTED otherwise) */
 
 const char *wino_status_string(int status);
 /* hipError_t of the most recent failing HIP call made by the calling thread (0 if none). */

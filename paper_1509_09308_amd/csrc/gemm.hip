@@ -1,31 +1,54 @@
 // Loop 3 of Algorithm 1 (Lavin & Gray): the alpha^2 independent products
 // M^(xi,nu) = U^(xi,nu) V^(xi,nu) (Eq. (13)), K x C by C x P each, on the MFMA units.
+#include <stdlib.h>
+
 #include "wino_internal.h"
 
 namespace wino {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-// fp32 operands, v_mfma_f32_32x32x2_f32.  A workgroup of 4 wavefronts (2 x 2) owns a BM x BN
-// block of one M^(e); every wavefront owns (BM/2) x (BN/2) of it as TM x TN MFMA tiles of
-// 32 x 32.  Both operands are stored reduction-index-major (U[e][c][k], V[e][c][b]), so a
-// BK-deep slab is BK contiguous row segments: loaded with 16-byte accesses, kept in LDS as
-// [c][k] / [c][b], and read by the MFMA lanes (lane = column + 32 * (c & 1)) without bank
-// conflicts.  LDS slabs are double buffered: the next slab's global loads are in flight
-// while the current one feeds the MFMAs.
-template <int BM, int BN>
-__global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__ U, const float *__restrict__ V,
-                                                       float *__restrict__ Mo, int Kp, int Cp, int Pp, int tiles_m,
-                                                       int tiles_n)
+// Maps the hardware workgroup id to a logical block id so that logically consecutive blocks run
+// on the same XCD.  Workgroups are dealt to the 8 XCDs round-robin (id % 8) and each XCD has
+// its own L2; consecutive logical blocks share an operand panel, so they should share an L2.
+__device__ __forceinline__ int xcd_remap(int bid, int nblocks)
 {
-    constexpr int BK = 16;
-    constexpr int TM = BM / 64, TN = BN / 64;
-    constexpr int A4 = BK * BM / 4, B4 = BK * BN / 4;          // float4s per slab
-    constexpr int AL = (A4 + 255) / 256, BL = (B4 + 255) / 256; // float4 loads per thread
+    constexpr int XCDS = 8;
+    const int per = nblocks / XCDS;            // blocks in the evenly divisible part
+    if (bid >= per * XCDS) return bid;         // ragged remainder keeps its id
+    return (bid % XCDS) * per + bid / XCDS;
+}
+
+// fp32 operands, v_mfma_f32_32x32x2_f32.  A workgroup of WM x WN wavefronts owns a BM x BN
+// block of one M^(e); every wavefront owns TM x TN MFMA tiles of 32 x 32.  Both operands are
+// stored reduction-index-major (U[e][c][k], V[e][c][b]), so a BK-deep slab is BK contiguous row
+// segments: loaded with 16-byte accesses, kept in LDS as [c][k] / [c][b], and read by the MFMA
+// lanes (lane = column + 32 * (c & 1)) without bank conflicts.
+//
+// Pipeline: two LDS slabs (the global loads of slab t+1 are in flight while slab t is
+// multiplied) and two register sets per wavefront holding half a slab of MFMA operands each,
+// so LDS reads for the next half overlap the MFMAs of the current one; one barrier per slab.
+//
+// Blocks that overhang Kp or Pp load from clamped (valid) addresses: rows/columns of a product
+// are independent, so whatever is loaded there only reaches outputs that are never stored.
+template <int BM, int BN, int WM, int WN, int BK>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_f32_kernel(const float *__restrict__ U,
+                                                                 const float *__restrict__ V,
+                                                                 float *__restrict__ Mo, int Kp, int Cp, int Pp,
+                                                                 int tiles_m, int tiles_n)
+{
+    constexpr int NT = 64 * WM * WN;
+    constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);
+    constexpr int A4 = BK * BM / 4, B4 = BK * BN / 4;  // float4s per slab
+    static_assert(A4 % NT == 0 && B4 % NT == 0, "slab must divide evenly among the threads");
+    static_assert(BK % 8 == 0, "two half-slabs of whole MFMA steps");
+    constexpr int AL = A4 / NT, BL = B4 / NT;
+    constexpr int HS = BK / 4;                          // MFMA steps (2 channels each) per half slab
     __shared__ float As[2][BK * BM];
     __shared__ float Bs[2][BK * BN];
 
-    int bid = blockIdx.x;
+    int bid = xcd_remap(blockIdx.x, gridDim.x);
     const int tm_i = bid % tiles_m;
     bid /= tiles_m;
     const int tn_i = bid % tiles_n;
@@ -38,38 +61,50 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, lg = lane >> 5;
 
-    float4 ra[AL], rb[BL];
-    auto load_global = [&](int c0) {
+    const float *pa[AL], *pb[BL];
+#pragma unroll
+    for (int j = 0; j < AL; ++j) {
+        const int idx = tid + j * NT;
+        const int row = idx / (BM / 4), col = min(k0 + (idx % (BM / 4)) * 4, Kp - 4);
+        pa[j] = Ue + (size_t)row * Kp + col;
+    }
+#pragma unroll
+    for (int j = 0; j < BL; ++j) {
+        const int idx = tid + j * NT;
+        const int row = idx / (BN / 4), col = min(p0 + (idx % (BN / 4)) * 4, Pp - 4);
+        pb[j] = Ve + (size_t)row * Pp + col;
+    }
+    floatx4 ra[AL], rb[BL];
+    auto load_global = [&]() {
 #pragma unroll
         for (int j = 0; j < AL; ++j) {
-            const int idx = tid + j * 256;
-            const int row = idx / (BM / 4), col = (idx % (BM / 4)) * 4;
-            ra[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (idx < A4 && k0 + col < Kp)
-                ra[j] = *reinterpret_cast<const float4 *>(Ue + (size_t)(c0 + row) * Kp + k0 + col);
+            ra[j] = *reinterpret_cast<const floatx4 *>(pa[j]);
+            pa[j] += (size_t)BK * Kp;
         }
 #pragma unroll
         for (int j = 0; j < BL; ++j) {
-            const int idx = tid + j * 256;
-            const int row = idx / (BN / 4), col = (idx % (BN / 4)) * 4;
-            rb[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (idx < B4 && p0 + col < Pp)
-                rb[j] = *reinterpret_cast<const float4 *>(Ve + (size_t)(c0 + row) * Pp + p0 + col);
+            rb[j] = *reinterpret_cast<const floatx4 *>(pb[j]);
+            pb[j] += (size_t)BK * Pp;
         }
     };
     auto store_lds = [&](int buf) {
 #pragma unroll
-        for (int j = 0; j < AL; ++j) {
-            const int idx = tid + j * 256;
-            if (idx < A4) *reinterpret_cast<float4 *>(&As[buf][idx * 4]) = ra[j];
-        }
+        for (int j = 0; j < AL; ++j) *reinterpret_cast<floatx4 *>(&As[buf][(tid + j * NT) * 4]) = ra[j];
 #pragma unroll
-        for (int j = 0; j < BL; ++j) {
-            const int idx = tid + j * 256;
-            if (idx < B4) *reinterpret_cast<float4 *>(&Bs[buf][idx * 4]) = rb[j];
+        for (int j = 0; j < BL; ++j) *reinterpret_cast<floatx4 *>(&Bs[buf][(tid + j * NT) * 4]) = rb[j];
+    };
+    const int a_off = wm * (TM * 32) + li, b_off = wn * (TN * 32) + li;
+    auto lds_load = [&](int buf, int half, float (&a)[HS][TM], float (&b)[HS][TN]) {
+#pragma unroll
+        for (int s = 0; s < HS; ++s) {
+            const int c = 2 * (half * HS + s) + lg;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[s][i] = As[buf][c * BM + a_off + i * 32];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[s][j] = Bs[buf][c * BN + b_off + j * 32];
         }
     };
 
@@ -80,48 +115,61 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-    const int nk = Cp / BK;
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) load_global((kt + 1) * BK);
-        const float *as = &As[cur][wm * (BM / 2) + li];
-        const float *bs = &Bs[cur][wn * (BN / 2) + li];
+    auto mma = [&](const float (&a)[HS][TM], const float (&b)[HS][TN]) {
 #pragma unroll
-        for (int kk = 0; kk < BK / 2; ++kk) {
-            float a[TM], b[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = as[(2 * kk + lg) * BM + i * 32];
-#pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = bs[(2 * kk + lg) * BN + j * 32];
+        for (int s = 0; s < HS; ++s)
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
-        }
-        if (kt + 1 < nk) store_lds(cur ^ 1);
-        __syncthreads();
-    }
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s][i], b[s][j], acc[i][j], 0, 0, 0);
+    };
 
-    // accumulator register r of lane (li, lg) is row 8*(r/4) + 4*lg + r%4, column li of its tile
+    float a0[HS][TM], b0[HS][TN], a1[HS][TM], b1[HS][TN];
+    const int nk = Cp / BK;
+    load_global();
+    store_lds(0);
+    __syncthreads();
+    lds_load(0, 0, a0, b0);
+    // all slabs but the last: fetch the next slab while multiplying the current one
+    for (int kt = 0; kt + 1 < nk; ++kt) {
+        const int cur = kt & 1;
+        load_global();
+        lds_load(cur, 1, a1, b1);
+        mma(a0, b0);
+        store_lds(cur ^ 1);
+        __syncthreads();
+        lds_load(cur ^ 1, 0, a0, b0);
+        mma(a1, b1);
+    }
+    lds_load((nk - 1) & 1, 1, a1, b1);
+    mma(a0, b0);
+    mma(a1, b1);
+
+    // accumulator register r of lane (li, lg) is row 8*(r/4) + 4*lg + r%4, column li of its tile;
+    // Kp and Pp are multiples of 32, so a 32 x 32 tile is entirely inside or entirely outside
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            const int col = p0 + wn * (BN / 2) + j * 32 + li;
-            const int rbase = k0 + wm * (BM / 2) + i * 32 + 4 * lg;
-            if (col < Pp) {
+            const int ct = p0 + wn * (TN * 32) + j * 32, rt = k0 + wm * (TM * 32) + i * 32;
+            if (ct < Pp && rt < Kp) {
+                float *dst = Me + (size_t)(rt + 4 * lg) * Pp + ct + li;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = rbase + 8 * (r / 4) + (r % 4);
-                    if (row < Kp) Me[(size_t)row * Pp + col] = acc[i][j][r];
-                }
+                for (int r = 0; r < 16; ++r) dst[(size_t)(8 * (r / 4) + (r % 4)) * Pp] = acc[i][j][r];
             }
         }
+}
+
+template <int BM, int BN, int WM, int WN, int BK>
+static hipError_t launch_f32(const Geo &g, const float *U, const float *V, float *M, hipStream_t s)
+{
+    const int tiles_m = (g.Kp + BM - 1) / BM, tiles_n = (g.Pp + BN - 1) / BN;
+    const long long blocks = (long long)tiles_m * tiles_n * g.a2;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    gemm_f32_kernel<BM, BN, WM, WN, BK><<<dim3((unsigned)blocks), dim3(64 * WM * WN), 0, s>>>(
+        U, V, M, g.Kp, g.Cp, g.Pp, tiles_m, tiles_n);
+    return hipGetLastError();
 }
 
 // fp16 operands, fp32 accumulation, v_mfma_f32_32x32x16_f16.  Operands are stored as
@@ -257,16 +305,6 @@ static hipError_t launch_f16(const Geo &g, const void *U, const void *V, float *
     return hipGetLastError();
 }
 
-template <int BM, int BN>
-static hipError_t launch_f32(const Geo &g, const float *U, const float *V, float *M, hipStream_t s)
-{
-    const int tiles_m = (g.Kp + BM - 1) / BM, tiles_n = (g.Pp + BN - 1) / BN;
-    const long long blocks = (long long)tiles_m * tiles_n * g.a2;
-    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    gemm_f32_kernel<BM, BN><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(U, V, M, g.Kp, g.Cp, g.Pp, tiles_m, tiles_n);
-    return hipGetLastError();
-}
-
 hipError_t launch_batched_gemm(const Geo &g, const void *U, const void *V, float *M, hipStream_t s)
 {
     const bool wide_m = g.Kp >= 128, wide_n = g.Pp >= 128;
@@ -277,10 +315,24 @@ hipError_t launch_batched_gemm(const Geo &g, const void *U, const void *V, float
         return launch_f16<64, 64>(g, U, V, M, s);
     }
     const float *u = (const float *)U, *v = (const float *)V;
-    if (wide_m && wide_n) return launch_f32<128, 128>(g, u, v, M, s);
-    if (wide_m) return launch_f32<128, 64>(g, u, v, M, s);
-    if (wide_n) return launch_f32<64, 128>(g, u, v, M, s);
-    return launch_f32<64, 64>(g, u, v, M, s);
+    const char *tune = getenv("WINO_GEMM_TILE");   // tuning sweeps only
+    const int forced = tune ? atoi(tune) : 0;
+    switch (forced) {
+    case 1: return launch_f32<128, 128, 2, 2, 16>(g, u, v, M, s);
+    case 2: return launch_f32<128, 128, 2, 2, 32>(g, u, v, M, s);
+    case 3: return launch_f32<256, 128, 2, 2, 16>(g, u, v, M, s);
+    case 4: return launch_f32<128, 256, 2, 2, 16>(g, u, v, M, s);
+    case 5: return launch_f32<256, 128, 4, 2, 16>(g, u, v, M, s);
+    case 6: return launch_f32<128, 256, 2, 4, 16>(g, u, v, M, s);
+    case 7: return launch_f32<256, 256, 4, 2, 16>(g, u, v, M, s);
+    case 8: return launch_f32<64, 128, 1, 4, 16>(g, u, v, M, s);
+    case 9: return launch_f32<64, 256, 1, 4, 16>(g, u, v, M, s);
+    default: break;
+    }
+    if (wide_m && wide_n) return launch_f32<128, 128, 2, 2, 16>(g, u, v, M, s);
+    if (wide_m) return launch_f32<128, 64, 2, 2, 16>(g, u, v, M, s);
+    if (wide_n) return launch_f32<64, 128, 2, 2, 16>(g, u, v, M, s);
+    return launch_f32<64, 64, 2, 2, 16>(g, u, v, M, s);
 }
 
 }  // namespace wino

@@ -234,7 +234,8 @@ int wino_conv2d_fwd_ex(int N, int C, int H, int W, int K, int pad, int m, int dt
     const int st = make_geo(N, C, H, W, K, pad, m, dt, &g);
     if (st != WINO_OK) return st;
     if (bad_dtype(y_dt)) return WINO_EINVAL;
-    if (flags > WINO_FLAG_FUSED_OUTPUT) return WINO_EINVAL;
+    if (flags > WINO_FLAG_FUSED) return WINO_EINVAL;
+    if (flags == WINO_FLAG_FUSED && (!fused_eligible(g) || y_dt != WINO_F32)) return WINO_EUNSUPPORTED;
     if (bad_ptr(D) || bad_ptr(Y) || bad_ptr(workspace)) return WINO_EINVAL;
     if (U == nullptr ? bad_ptr(G) : !aligned16(U)) return WINO_EINVAL;
     const size_t ub = align256(u_bytes(g)), vb = align256(v_bytes(g)), mb = align256(m_bytes(g));
@@ -247,6 +248,11 @@ int wino_conv2d_fwd_ex(int N, int C, int H, int W, int K, int pad, int m, int dt
     if (U == nullptr) {
         if ((e = launch_filter_transform(g, G, Uw, s)) != hipSuccess) return hip_fail(e);
         U = Uw;
+    }
+    if (flags == WINO_FLAG_AUTO && y_dt == WINO_F32 && fused_preferred(g)) flags = WINO_FLAG_FUSED;
+    if (flags == WINO_FLAG_FUSED) {
+        if ((e = launch_fused(g, (const float *)D, (const float *)U, (float *)Y, s)) != hipSuccess) return hip_fail(e);
+        return WINO_OK;
     }
     if ((e = launch_input_transform(g, D, Vw, s)) != hipSuccess) return hip_fail(e);
     if ((e = launch_batched_gemm(g, U, Vw, Mw, s)) != hipSuccess)

@@ -31,6 +31,9 @@ hipError_t launch_filter_transform(const Geo &g, const void *G, void *U, hipStre
 hipError_t launch_input_transform(const Geo &g, const void *D, void *V, hipStream_t s);
 hipError_t launch_batched_gemm(const Geo &g, const void *U, const void *V, float *M, hipStream_t s);
 hipError_t launch_output_transform(const Geo &g, int y_dt, const float *M, void *Y, hipStream_t s);
+bool fused_eligible(const Geo &g);
+bool fused_preferred(const Geo &g);
+hipError_t launch_fused(const Geo &g, const float *D, const float *U, float *Y, hipStream_t s);
 hipError_t launch_direct_conv(int N, int C, int H, int W, int K, int R, int S, int pad, int stride, int dt,
                               const void *D, const void *G, void *Y, hipStream_t s);
 

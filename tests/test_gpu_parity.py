@@ -140,3 +140,47 @@ def test_config5_full_size_sampled(layer):
     print("%s N=32 fp16 m=4 sampled rel err %.3e" % (name, e))
     assert e <= TOL[("f16", 4)]
     assert bool(torch.isfinite(Y).all())
+
+
+# ---- the one-kernel path (gather + data transform + multiply + inverse transform fused) ----------
+
+@pytest.mark.parametrize("shape", [(2, 16, 8, 8, 16, 1), (1, 4, 12, 12, 8, 1), (2, 64, 28, 28, 64, 1),
+                                   (1, 19, 13, 29, 70, 1), (3, 33, 14, 14, 65, 1), (2, 16, 31, 18, 130, 0),
+                                   (1, 7, 67, 131, 9, 1), (1, 1, 3, 3, 1, 1), (1, 1, 4, 4, 1, 0), (5, 130, 9, 9, 40, 1),
+                                   (8, 512, 28, 28, 512, 1)])
+def test_fused_path_matches_oracle(shape):
+    """F(4x4,3x3) with V and M kept on chip: whole output against the oracle, including ragged
+    edges, pad 0, channel counts that are not multiples of 4 and filter counts below a block."""
+    torch, w = require_gpu()
+    N, C, H, W, K, pad = shape
+    D, G = synth.make_layer(N, C, H, W, K, seed=sum(shape) + 40)
+    ref = direct.conv2d_fwd(D, G, pad=pad)
+    Y = w.wino_conv2d_fwd_ex(to_gpu(D), G=to_gpu(G), pad=pad, m=4, flags=w.FLAG_FUSED).cpu().numpy()
+    assert Y.shape == ref.shape
+    e = rel_err(Y, ref)
+    print("fused %s rel err %.3e" % (shape, e))
+    assert e <= TOL[("f32", 4)]
+
+
+def test_fused_path_exact_on_integers_and_equals_unfused_bookkeeping():
+    """Integer data and filters scaled by 576: the only roundings are those of the 1/6-type
+    constants, and every output position must be the right one (distinct values per pixel)."""
+    torch, w = require_gpu()
+    D, G = synth.make_integer_layer(3, 8, 22, 26, 70, seed=9, gscale=576.0)
+    ref = direct.conv2d_fwd(D, G, pad=1)
+    d, g = to_gpu(D), to_gpu(G)
+    Yf = w.wino_conv2d_fwd_ex(d, G=g, pad=1, m=4, flags=w.FLAG_FUSED).cpu().numpy()
+    Yu = w.wino_conv2d_fwd_ex(d, G=g, pad=1, m=4, flags=w.FLAG_UNFUSED).cpu().numpy()
+    assert rel_err(Yf, ref) < 1e-6 and rel_err(Yu, ref) < 1e-6
+    assert np.abs(Yf - Yu).max() <= 1e-5 * np.abs(ref).max()
+
+
+def test_fused_flag_rejected_where_unsupported():
+    torch, w = require_gpu()
+    D, G = synth.make_layer(1, 8, 8, 8, 8, seed=1)
+    with pytest.raises(w.WinoError) as ei:
+        w.wino_conv2d_fwd_ex(to_gpu(D), G=to_gpu(G), pad=1, m=2, flags=w.FLAG_FUSED)
+    assert ei.value.status == w.WINO_EUNSUPPORTED
+    with pytest.raises(w.WinoError):
+        w.wino_conv2d_fwd_ex(to_gpu(D.astype(np.float16)), G=to_gpu(G.astype(np.float16)), pad=1, m=4,
+                             flags=w.FLAG_FUSED)
