@@ -104,34 +104,39 @@ __device__ __forceinline__ void fused_body(const float *__restrict__ D, const fl
     const unsigned step_bytes = (unsigned)(FC * HW) * 4u;
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)D, 0, d_bytes, 0x00020000);
 
-    // ---- raw taps: the 18 loads (6 rows x {q=0, q=1..4, q=5}) of a tile group are dealt to its
-    //      four wavefronts; load n of this wavefront is number idx4 + 4n -------------------------
+    // ---- raw taps: a tile row is fetched as {q=0 (4 B), q=1..4 (16 B), q=5 (4 B)} per lane.  The
+    //      four wavefronts of a tile group each fetch two rows: rows 0-1, 2-3, 4-4, 5-5 (the last
+    //      two fetch their row twice, which keeps the loop free of wave-dependent branches). ------
     const int idx4 = L.wm * 2 + L.h;
-    unsigned rvoff[5];
-    int rdst[5], rpart[5];
+    const int rrow[2] = {(idx4 < 2) ? 2 * idx4 : idx4 + 2, (idx4 < 2) ? 2 * idx4 + 1 : idx4 + 2};
+    unsigned rvoff[2][3];
 #pragma unroll
-    for (int n = 0; n < 5; ++n) {
-        const int d = idx4 + 4 * n;
-        const int p = (d < 18) ? d / 3 : 0, part = (d < 18) ? d % 3 : 3;
-        const int x = x0 + p;
-        const int y = (part == 0) ? y0 : (part == 1) ? y0 + 1 : y0 + 5;
-        const bool ok = L.tile_ok && x >= 0 && x < g.H && y >= 0 && y < g.W;
-        rvoff[n] = ok ? (unsigned)((L.img * g.C + cs) * HW + x * g.W + y) * 4u : OOB;
-        rdst[n] = p * RROW + ((part == 0) ? 0 : (part == 1) ? 64 : 64 + 256);
-        rpart[n] = part;
-    }
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int part = 0; part < 3; ++part) {
+            const int x = x0 + rrow[i];
+            const int y = (part == 0) ? y0 : (part == 1) ? y0 + 1 : y0 + 5;
+            const bool ok = L.tile_ok && x >= 0 && x < g.H && y >= 0 && y < g.W;
+            rvoff[i][part] = ok ? (unsigned)((L.img * g.C + cs) * HW + x * g.W + y) * 4u : OOB;
+        }
     auto load_raw = [&](int st, int s) {
-        unsigned so = (unsigned)s * step_bytes;
+        const unsigned so = (unsigned)s * step_bytes;
         const bool ch_ok = !CPAD || (s * FC + cs < g.C);
 #pragma unroll
-        for (int n = 0; n < 5; ++n) {
-            unsigned vo = rvoff[n];
-            if (CPAD) vo = (ch_ok && vo != OOB) ? vo + so : OOB;  // bounds check sees the whole address
-            float *dst = rlds + st * RSTAGE + rdst[n];
-            if (rpart[n] == 1)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, WINO_LDS_PTR(dst), 16, vo, CPAD ? 0u : so, 0, 0);
-            else if (rpart[n] != 3)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, WINO_LDS_PTR(dst), 4, vo, CPAD ? 0u : so, 0, 0);
+        for (int i = 0; i < 2; ++i) {
+            float *dst = rlds + st * RSTAGE + rrow[i] * RROW;
+#pragma unroll
+            for (int part = 0; part < 3; ++part) {
+                unsigned vo = rvoff[i][part];
+                if (CPAD) vo = (ch_ok && vo != OOB) ? vo + so : OOB;  // bounds check sees the whole address
+                if (part == 0)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, WINO_LDS_PTR(dst), 4, vo, CPAD ? 0u : so, 0, 0);
+                else if (part == 1)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, WINO_LDS_PTR(dst + 64), 16, vo, CPAD ? 0u : so, 0, 0);
+                else
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, WINO_LDS_PTR(dst + 64 + 256), 4, vo, CPAD ? 0u : so, 0,
+                                                             0);
+            }
         }
     };
     // columns that may lie outside the image when the 4-wide run overhangs the row (RAGGED only)
@@ -139,30 +144,34 @@ __device__ __forceinline__ void fused_body(const float *__restrict__ D, const fl
 #pragma unroll
     for (int q = 0; q < A; ++q) cv[q] = (y0 + q >= 0) && (y0 + q < g.W);
 
-    // LDS stage -> registers -> this wavefront's three rows of v = B^T d B
-    auto transform = [&](float (&v)[HC], int st) {
+    // LDS stage -> registers (the 36 raw taps of this lane's tile and channel)
+    auto load_taps = [&](float (&d)[A2], int st) {
         const float *src = rlds + st * RSTAGE;
-        float t[3][A];
-        float d[A][A];
 #pragma unroll
         for (int p = 0; p < A; ++p) {
             const floatx4 mid = *reinterpret_cast<const floatx4 *>(src + p * RROW + 64 + lane * 4);
-            d[p][0] = src[p * RROW + lane];
-            d[p][1] = mid[0];
-            d[p][2] = mid[1];
-            d[p][3] = mid[2];
-            d[p][4] = mid[3];
-            d[p][5] = src[p * RROW + 64 + 256 + lane];
-            if (RAGGED) {
+            d[p * A + 0] = src[p * RROW + lane];
+            d[p * A + 1] = mid[0];
+            d[p * A + 2] = mid[1];
+            d[p * A + 3] = mid[2];
+            d[p * A + 4] = mid[3];
+            d[p * A + 5] = src[p * RROW + 64 + 256 + lane];
+        }
+    };
+    // this wavefront's three rows of v = B^T d B
+    auto transform = [&](float (&v)[HC], float (&d)[A2]) {
+        float t[3][A];
+        if (RAGGED) {
 #pragma unroll
-                for (int q = 1; q < 5; ++q) d[p][q] = cv[q] ? d[p][q] : 0.0f;
-            }
+            for (int p = 0; p < A; ++p)
+#pragma unroll
+                for (int q = 1; q < 5; ++q) d[p * A + q] = cv[q] ? d[p * A + q] : 0.0f;
         }
 #pragma unroll
         for (int q = 0; q < A; ++q) {
             float col[A], o[3];
 #pragma unroll
-            for (int p = 0; p < A; ++p) col[p] = d[p][q];
+            for (int p = 0; p < A; ++p) col[p] = d[p * A + q];
             bt_half<HALF>(col, o);
             t[0][q] = o[0];
             t[1][q] = o[1];
@@ -179,17 +188,22 @@ __device__ __forceinline__ void fused_body(const float *__restrict__ D, const fl
     const int ucol = min(L.kb * FK + (((f4 >> 2) ^ (cs & 1)) << 4) + ((f4 & 3) << 2), g.Kp - 4);
     const size_t e_stride = (size_t)g.Cp * g.Kp;
     const size_t s_stride = (size_t)FC * g.Kp;
+    // component of load n: wave + 8n, the last one clamped to 35 (waves 4..7 fetch it redundantly)
+    const int e_last = min(L.wave + 32, A2 - 1);
     const float *usrc = U + (size_t)cs * g.Kp + ucol + (size_t)L.wave * e_stride;
+    const float *usrc_last = U + (size_t)cs * g.Kp + ucol + (size_t)e_last * e_stride;
     float *const udst = ulds + L.wave * (FC * FK);
+    float *const udst_last = ulds + e_last * (FC * FK);
     auto load_u = [&](int buf, int s) {
         const float *src = usrc + (size_t)s * s_stride;
 #pragma unroll
-        for (int n = 0; n < 5; ++n) {
-            if (L.wave + 8 * n < A2)
-                __builtin_amdgcn_global_load_lds(WINO_GLB_PTR(src), WINO_LDS_PTR(udst + buf * SLAB + n * 8 * (FC * FK)),
-                                                 16, 0, 0);
+        for (int n = 0; n < 4; ++n) {
+            __builtin_amdgcn_global_load_lds(WINO_GLB_PTR(src), WINO_LDS_PTR(udst + buf * SLAB + n * 8 * (FC * FK)), 16, 0,
+                                             0);
             src += 8 * e_stride;
         }
+        __builtin_amdgcn_global_load_lds(WINO_GLB_PTR(usrc_last + (size_t)s * s_stride),
+                                         WINO_LDS_PTR(udst_last + buf * SLAB), 16, 0, 0);
     };
     // A operand of lane (cs, t16): filter row t16 of 16-filter group wm*2 + j, channel cs
     const int a_lane0 = HALF * HC * (FC * FK) + cs * FK + (((L.wm * 2 + 0) ^ (cs & 1)) << 4) + t16;
@@ -201,14 +215,19 @@ __device__ __forceinline__ void fused_body(const float *__restrict__ D, const fl
         acc[e][0] = floatx4{0.f, 0.f, 0.f, 0.f};
         acc[e][1] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
-    auto mma_step = [&](const float (&v)[HC], int buf) {
+    auto load_a = [&](float (&a0)[HC], float (&a1)[HC], int buf) {
         const float *as = ulds + buf * SLAB;
 #pragma unroll
         for (int e = 0; e < HC; ++e) {
-            const float a0 = as[e * (FC * FK) + a_lane0];
-            const float a1 = as[e * (FC * FK) + a_lane1];
-            acc[e][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, v[e], acc[e][0], 0, 0, 0);
-            acc[e][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, v[e], acc[e][1], 0, 0, 0);
+            a0[e] = as[e * (FC * FK) + a_lane0];
+            a1[e] = as[e * (FC * FK) + a_lane1];
+        }
+    };
+    auto mma_step = [&](const float (&v)[HC], const float (&a0)[HC], const float (&a1)[HC]) {
+#pragma unroll
+        for (int e = 0; e < HC; ++e) {
+            acc[e][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0[e], v[e], acc[e][0], 0, 0, 0);
+            acc[e][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[e], v[e], acc[e][1], 0, 0, 0);
         }
     };
 
@@ -217,13 +236,7 @@ __device__ __forceinline__ void fused_body(const float *__restrict__ D, const fl
     //      step everything but the taps issued in that step must have landed.  The two wavefronts
     //      that share a SIMD (same wn and h, different wm) run the MFMA block and the transform
     //      block in opposite order, so that one's MFMAs overlap the other's VALU work. -----------
-    const bool five_raw = idx4 + 16 < 18;  // this wavefront issues 5 (else 4) tap loads per step
-    auto wait_all_but_new_taps = [&]() {
-        if (five_raw)
-            __builtin_amdgcn_s_waitcnt(0x0f75);  // vmcnt(5)
-        else
-            __builtin_amdgcn_s_waitcnt(0x0f74);  // vmcnt(4)
-    };
+    auto wait_all_but_new_taps = [&]() { __builtin_amdgcn_s_waitcnt(0x0f76); };  // vmcnt(6)
     float va[HC], vb[HC];
     load_u(0, 0);
     load_raw(0, 0);
@@ -231,25 +244,41 @@ __device__ __forceinline__ void fused_body(const float *__restrict__ D, const fl
     load_raw(2, min(2, S - 1));
     __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's loads have landed in LDS
     __syncthreads();
-    transform(va, 0);
+    {
+        float d[A2];
+        load_taps(d, 0);
+        transform(va, d);
+    }
     __syncthreads();  // stage 0 is free for the loads of step 0
     int st_w = 0, st_r = 1;  // raw stage written (s % 3) and read ((s + 1) % 3) in step s
 
-#define WINO_FUSED_STEP(CUR, NXT, s)                        \
-    {                                                       \
-        load_u(((s) + 1) & 1, min((s) + 1, S - 1));         \
-        load_raw(st_w, min((s) + 3, S - 1));                \
-        if constexpr (PHASE == 0) {                         \
-            mma_step(CUR, (s) & 1);                         \
-            transform(NXT, st_r);                           \
-        } else {                                            \
-            transform(NXT, st_r);                           \
-            mma_step(CUR, (s) & 1);                         \
-        }                                                   \
-        wait_all_but_new_taps();                            \
-        __syncthreads();                                    \
-        st_w = st_r;                                        \
-        st_r = (st_r == 2) ? 0 : st_r + 1;                  \
+    // All LDS reads of a block are issued before its arithmetic (the scheduling barriers keep
+    // the compiler from sinking them next to their uses, which would expose the LDS latency
+    // once per group of MFMAs instead of once per step).
+#define WINO_FUSED_STEP(CUR, NXT, s)                                \
+    {                                                               \
+        float d[A2], a0[HC], a1[HC];                                \
+        load_u(((s) + 1) & 1, min((s) + 1, S - 1));                 \
+        load_raw(st_w, min((s) + 3, S - 1));                        \
+        if constexpr (PHASE == 0) {                                 \
+            load_a(a0, a1, (s) & 1);                                \
+            load_taps(d, st_r);                                     \
+            __builtin_amdgcn_sched_barrier(0);                      \
+            mma_step(CUR, a0, a1);                                  \
+            __builtin_amdgcn_sched_barrier(0);                      \
+            transform(NXT, d);                                      \
+        } else {                                                    \
+            load_taps(d, st_r);                                     \
+            __builtin_amdgcn_sched_barrier(0);                      \
+            transform(NXT, d);                                      \
+            load_a(a0, a1, (s) & 1);                                \
+            __builtin_amdgcn_sched_barrier(0);                      \
+            mma_step(CUR, a0, a1);                                  \
+        }                                                           \
+        wait_all_but_new_taps();                                    \
+        __syncthreads();                                            \
+        st_w = st_r;                                                \
+        st_r = (st_r == 2) ? 0 : st_r + 1;                          \
     }
     for (int s = 0; s < S; s += 2) {  // S is a multiple of 4
         WINO_FUSED_STEP(va, vb, s)
