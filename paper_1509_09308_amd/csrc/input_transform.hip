@@ -72,9 +72,84 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const T *__restric
         }
 }
 
+// fp32, pad 1, W a multiple of 4 (every VGG layer): two tiles per thread.  Columns 1..4 of a
+// tile row are then one aligned 16-byte load (columns 0 and 5 are single loads, absent on the
+// image border), and the two results go out as one 8-byte store per component, so a wavefront
+// writes 512 contiguous bytes per store instruction.
+typedef float floatx4_it __attribute__((ext_vector_type(4)));
+typedef float floatx2_it __attribute__((ext_vector_type(2)));
+
+template <int M>
+__global__ __launch_bounds__(256) void input_transform_pair_kernel(const float *__restrict__ D, float *__restrict__ V,
+                                                                   Geo g)
+{
+    constexpr int A = M + 2;
+    static_assert(M == 4, "the 16-byte middle run is columns 1..4 of a 6-wide tile");
+    const int b0 = (blockIdx.x * 256 + threadIdx.x) * 2;
+    const int c = blockIdx.y;
+    if (b0 >= g.Pp) return;
+    float v[2][A][A];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int b = b0 + t;
+        float d[A][A];
+#pragma unroll
+        for (int p = 0; p < A; ++p)
+#pragma unroll
+            for (int q = 0; q < A; ++q) d[p][q] = 0.0f;
+        if (c < g.C && b < g.P) {
+            const int ty = b % g.Tw;
+            const int t2 = b / g.Tw;
+            const int tx = t2 % g.Th;
+            const int i = t2 / g.Th;
+            const int x0 = M * tx - 1, y0 = M * ty - 1;
+            const float *src = D + ((size_t)i * g.C + c) * g.H * g.W;
+#pragma unroll
+            for (int p = 0; p < A; ++p) {
+                const int x = x0 + p;
+                if (x >= 0 && x < g.H) {
+                    const float *row = src + (size_t)x * g.W + y0;
+                    const floatx4_it mid = *reinterpret_cast<const floatx4_it *>(row + 1);
+                    d[p][1] = mid[0];
+                    d[p][2] = mid[1];
+                    d[p][3] = mid[2];
+                    d[p][4] = mid[3];
+                    if (y0 >= 0) d[p][0] = row[0];
+                    if (y0 + 5 < g.W) d[p][5] = row[5];
+                }
+            }
+        }
+        float tt[A][A];
+#pragma unroll
+        for (int q = 0; q < A; ++q) {
+            float col[A], o[A];
+#pragma unroll
+            for (int p = 0; p < A; ++p) col[p] = d[p][q];
+            bt_mul<M>(col, o);
+#pragma unroll
+            for (int p = 0; p < A; ++p) tt[p][q] = o[p];
+        }
+#pragma unroll
+        for (int p = 0; p < A; ++p) bt_mul<M>(tt[p], v[t][p]);
+    }
+#pragma unroll
+    for (int xi = 0; xi < A; ++xi)
+#pragma unroll
+        for (int nu = 0; nu < A; ++nu) {
+            const int e = xi * A + nu;
+            *reinterpret_cast<floatx2_it *>(V + ((size_t)e * g.Cp + c) * g.Pp + b0) =
+                floatx2_it{v[0][xi][nu], v[1][xi][nu]};
+        }
+}
+
 hipError_t launch_input_transform(const Geo &g, const void *D, void *V, hipStream_t s)
 {
     dim3 grid((g.Pp + 255) / 256, g.Cp), block(256);
+    if (g.dt == WINO_F32 && g.m == 4 && g.pad == 1 && g.W % 4 == 0) {
+        dim3 grid2((g.Pp / 2 + 255) / 256, g.Cp);
+        input_transform_pair_kernel<4><<<grid2, block, 0, s>>>((const float *)D, (float *)V, g);
+        return hipGetLastError();
+    }
     if (g.dt == WINO_F32) {
         if (g.m == 2)
             input_transform_kernel<2, float><<<grid, block, 0, s>>>((const float *)D, (float *)V, g);
