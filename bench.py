@@ -27,6 +27,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK = {"hbm_GBs": 8000.0, "mfma_f32_TFs": 157.3, "mfma_f16_TFs": 2500.0}
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see
+# profiles/); keyed by (workload, kernel).  None until measured for a workload.
+MEASURED_TRAFFIC = {}
 # Titan X (Maxwell) numbers of the paper, F(2x2,3x3), VGG network E (Tables 5 and 6): context only.
 PAPER_TITANX = {"fp32": {1: 7.03, 64: 9.37}, "fp16": {1: 7.06, 64: 10.28}}
 
@@ -66,6 +69,7 @@ def make_layers(N, np_dtype, policy, config_idx):
             L.dt = w.WINO_F32 if L.D.dtype == torch.float32 else w.WINO_F16
             L.P = w.wino_num_tiles(N, HW, HW, 1, L.m)
             L.ws_bytes = w.wino_workspace_bytes(N, C, HW, HW, K, 1, L.m, L.dt)
+            L.variant = w.wino_conv2d_variant(N, C, HW, HW, K, 1, L.m, L.dt)
         layers.append(L)
     return layers
 
@@ -106,8 +110,10 @@ def time_layers(torch, w, layers, ws, steps):
 
 
 def time_stages(torch, w, layers, ws, steps):
-    """Second pass over the same launches, one stage entry point at a time, each bracketed by
-    HIP events on the stream the kernels run on.  Returns per-layer stage times in ms."""
+    """Second pass over the same launches, one kernel at a time, each bracketed by HIP events on
+    the stream the kernels run on.  A layer that wino_conv2d_fwd_ex runs through the one-kernel
+    path is timed as {filter transform, fused kernel}; the others as the four stage kernels.
+    Returns per-layer dictionaries (times in ms)."""
     res = []
     es = lambda: torch.cuda.Event(enable_timing=True)
     for L in layers:
@@ -115,38 +121,57 @@ def time_stages(torch, w, layers, ws, steps):
             res.append(None)
             continue
         a2 = (L.m + 2) ** 2
-        U = w.alloc_u(L.K, L.C, L.m, L.dt)
-        V = w.alloc_v(L.C, L.P, L.m, L.dt)
-        M = w.alloc_m(L.K, L.P, L.m)
-        acc = {"filter": 0.0, "input": 0.0, "gemm": 0.0, "output": 0.0}
-        for it in range(steps + 1):
-            e = [es() for _ in range(5)]
-            e[0].record()
-            w.wino_filter_transform(L.G, L.m, U=U)
-            e[1].record()
-            w.wino_input_transform(L.D, 1, L.m, V=V)
-            e[2].record()
-            w.wino_batched_gemm(U, V, L.K, L.C, L.P, L.m, M=M)
-            e[3].record()
-            w.wino_output_transform(M, L.N, L.K, L.HW, L.HW, 1, L.m, Y=L.Y)
-            e[4].record()
-            torch.cuda.synchronize()
-            if it == 0:
-                continue  # warm-up
-            for j, k in enumerate(("filter", "input", "gemm", "output")):
-                acc[k] += e[j].elapsed_time(e[j + 1]) / steps
         s = 4 if L.dt == w.WINO_F32 else 2
         Kp, Cp, Pp = w.wino_padded_dims(L.K, L.C, L.P, L.m, L.dt)
-        st = dict(acc)
-        st["gemm_flops"] = 2 * a2 * L.K * L.C * L.P
-        st["bytes"] = {
-            "filter": 9 * L.K * L.C * s + a2 * L.K * L.C * s,
-            "input": L.N * L.C * L.HW * L.HW * s + a2 * L.C * L.P * s,
-            "output": a2 * L.K * L.P * 4 + L.N * L.K * L.HW * L.HW * 4,
-        }
-        st["gemm_variant"] = "%dx%d" % (128 if Kp >= 128 else 64, 128 if Pp >= 128 else 64)
+        U = w.alloc_u(L.K, L.C, L.m, L.dt)
+        st = {"variant": L.variant, "gemm_flops": 2 * a2 * L.K * L.C * L.P}
+        if L.variant == w.FLAG_FUSED:
+            acc = {"filter": 0.0, "fused": 0.0}
+            for it in range(steps + 1):
+                e = [es() for _ in range(3)]
+                e[0].record()
+                w.wino_filter_transform(L.G, L.m, U=U)
+                e[1].record()
+                w.wino_conv2d_fwd_ex(L.D, U=U, K=L.K, pad=1, m=L.m, Y=L.Y, workspace=ws, flags=w.FLAG_FUSED)
+                e[2].record()
+                torch.cuda.synchronize()
+                if it:
+                    for j, k in enumerate(("filter", "fused")):
+                        acc[k] += e[j].elapsed_time(e[j + 1]) / steps
+            st.update(acc)
+            st["kernel"] = "fused_f4_kernel<false, false>"
+            st["bytes"] = {"filter": 9 * L.K * L.C * s + a2 * L.K * L.C * s,
+                           "fused": L.N * L.C * L.HW * L.HW * 4 + a2 * L.K * L.C * 4 + L.N * L.K * L.HW * L.HW * 4}
+        else:
+            V = w.alloc_v(L.C, L.P, L.m, L.dt)
+            M = w.alloc_m(L.K, L.P, L.m)
+            acc = {"filter": 0.0, "input": 0.0, "gemm": 0.0, "output": 0.0}
+            for it in range(steps + 1):
+                e = [es() for _ in range(5)]
+                e[0].record()
+                w.wino_filter_transform(L.G, L.m, U=U)
+                e[1].record()
+                w.wino_input_transform(L.D, 1, L.m, V=V)
+                e[2].record()
+                w.wino_batched_gemm(U, V, L.K, L.C, L.P, L.m, M=M)
+                e[3].record()
+                w.wino_output_transform(M, L.N, L.K, L.HW, L.HW, 1, L.m, Y=L.Y)
+                e[4].record()
+                torch.cuda.synchronize()
+                if it:
+                    for j, k in enumerate(("filter", "input", "gemm", "output")):
+                        acc[k] += e[j].elapsed_time(e[j + 1]) / steps
+            st.update(acc)
+            st["bytes"] = {
+                "filter": 9 * L.K * L.C * s + a2 * L.K * L.C * s,
+                "input": L.N * L.C * L.HW * L.HW * s + a2 * L.C * L.P * s,
+                "output": a2 * L.K * L.P * 4 + L.N * L.K * L.HW * L.HW * 4,
+            }
+            tile = "%d, %d" % (128 if Kp >= 128 else 64, 128 if Pp >= 128 else 64)
+            st["kernel"] = ("gemm_f32_kernel<%s, 2, 2, 16>" % tile) if L.dt == w.WINO_F32 else ("gemm_f16_kernel<%s>" % tile)
+            del V, M
         res.append(st)
-        del U, V, M
+        del U
     return res
 
 
@@ -181,6 +206,9 @@ def main():
     ap.add_argument("--no-n1", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stages", action="store_true")
+    ap.add_argument("--probe", action="store_true",
+                    help="for rocprofv3 --pmc runs: one 1 GiB device copy (counter calibration), then every "
+                         "kernel of one step once; prints the algorithmic bytes per kernel and exits")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (batch sharding across GPUs is a design note, "
@@ -203,6 +231,18 @@ def main():
     ws = torch.empty(max(L.ws_bytes for L in layers if not L.direct), dtype=torch.uint8, device="cuda")
     total_flops = sum(L.flops for L in layers)
 
+    if args.probe:
+        a = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)                                                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del a, b
+        st = time_stages(torch, w, layers, ws, 1)
+        print(json.dumps({"probe": "1 GiB copy, then each kernel of one step twice (warm-up + timed)",
+                          "layers": [{"layer": L.name, "kernel": x["kernel"], "flops": x["gemm_flops"],
+                                      "bytes": x["bytes"]} for L, x in zip(layers, st) if x]}))
+        return
     sec = time_steps(torch, w, layers, ws, args.steps, args.warmup)
     value = total_flops / sec / 1e12
 
@@ -237,32 +277,41 @@ def main():
     if not args.no_stages:
         stages = time_stages(torch, w, layers, ws, max(3, args.steps))
         rows, dom = [], {}
+        hb, hms = 0.0, 0.0
         for L, st in zip(layers, stages):
             if st is None:
                 continue
-            row = {"layer": L.name, "m": L.m, "gemm_variant": st["gemm_variant"],
-                   "gemm_ms": st["gemm"], "gemm_tflops": st["gemm_flops"] / st["gemm"] / 1e9}
+            main = "fused" if st["variant"] == w.FLAG_FUSED else "gemm"
+            row = {"layer": L.name, "m": L.m, "variant": "fused" if main == "fused" else "unfused",
+                   "kernel": st["kernel"], "kernel_ms": st[main], "kernel_tflops": st["gemm_flops"] / st[main] / 1e9}
             for k in ("filter", "input", "output"):
-                row[k + "_ms"] = st[k]
-                row[k + "_GBs"] = st["bytes"][k] / st[k] / 1e6
+                if k in st:
+                    row[k + "_ms"] = st[k]
+                    row[k + "_GBs"] = st["bytes"][k] / st[k] / 1e6
+                    if k != "filter":
+                        hb += st["bytes"][k]
+                        hms += st[k]
             rows.append(row)
-            d = dom.setdefault(st["gemm_variant"], {"flops": 0.0, "ms": 0.0, "launches": 0})
+            d = dom.setdefault(st["kernel"], {"flops": 0.0, "ms": 0.0, "launches": 0})
             d["flops"] += st["gemm_flops"]
-            d["ms"] += st["gemm"]
+            d["ms"] += st[main]
             d["launches"] += 1
         out["stages"] = rows
+        peak = PEAK["mfma_f32_TFs"] if args.dtype == "f32" else PEAK["mfma_f16_TFs"]
+        out["kernels"] = {k: {"launches_per_step": d["launches"], "avg_launch_ms": d["ms"] / d["launches"],
+                              "tflops": d["flops"] / d["ms"] / 1e9, "frac_of_mfma_peak": d["flops"] / d["ms"] / 1e9 / peak}
+                          for k, d in dom.items()}
         if dom:
             name, d = max(dom.items(), key=lambda kv: kv[1]["ms"])
-            peak = PEAK["mfma_f32_TFs"] if args.dtype == "f32" else PEAK["mfma_f16_TFs"]
             ach = d["flops"] / d["ms"] / 1e9
             out["roofline"] = {"bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
-                               "traffic": None, "kernel": "gemm_%s_kernel<%s>" % (args.dtype, name.replace("x", ", ")),
+                               "traffic": MEASURED_TRAFFIC.get((out["config"]["workload"], name)), "kernel": name,
                                "launches_per_step": d["launches"], "avg_launch_ms": d["ms"] / d["launches"],
                                "flops_per_launch": d["flops"] / d["launches"]}
-            tb = sum(st["bytes"]["input"] + st["bytes"]["output"] for st in stages if st)
-            tms = sum(st["input"] + st["output"] for st in stages if st)
-            out["transform_roofline"] = {"bound": "hbm", "achieved": tb / tms / 1e6, "peak": PEAK["hbm_GBs"],
-                                         "unit": "GB/s", "frac": tb / tms / 1e6 / PEAK["hbm_GBs"]}
+        if hms > 0:
+            out["transform_roofline"] = {"bound": "hbm", "achieved": hb / hms / 1e6, "peak": PEAK["hbm_GBs"],
+                                         "unit": "GB/s", "frac": hb / hms / 1e6 / PEAK["hbm_GBs"],
+                                         "kernels": "input_transform + output_transform of the unfused layers"}
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers)

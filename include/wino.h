@@ -116,6 +116,10 @@ int wino_conv2d_fwd(int N, int C, int H, int W, int K, int pad, int m, const voi
 int wino_conv2d_fwd_ex(int N, int C, int H, int W, int K, int pad, int m, int dt, int y_dt, const void *D,
                        const void *G, const void *U, void *Y, void *workspace, size_t workspace_bytes,
                        unsigned flags, void *stream);
+/* Host-side query: the variant wino_conv2d_fwd_ex runs for these arguments -- WINO_FLAG_UNFUSED or
+ * WINO_FLAG_FUSED -- when called with `flags` (WINO_FLAG_AUTO resolves to one of the two); a negative
+ * wino_status_t (e.g. -WINO_EUNSUPPORTED) if the call would be rejected. */
+int wino_conv2d_variant(int N, int C, int H, int W, int K, int pad, int m, int dt, int y_dt, unsigned flags);
 /* Eq. (1) evaluated directly on the GPU: any R x S filter, stride and padding; for layers the
  * fast algorithm does not cover (e.g. the 3-channel first layer of Table 3). */
 int direct_conv2d_fwd(int N, int C, int H, int W, int K, int R, int S, int pad, int stride, int dt,

@@ -58,6 +58,7 @@ def lib():
             "wino_output_transform": (i, [i] * 7 + [p, p, p]),
             "wino_conv2d_fwd": (i, [i] * 7 + [p, p, p, p]),
             "wino_conv2d_fwd_ex": (i, [i] * 9 + [p, p, p, p, p, sz, u, p]),
+            "wino_conv2d_variant": (i, [i] * 9 + [u]),
             "direct_conv2d_fwd": (i, [i] * 10 + [p, p, p, p]),
             "wino_shutdown": (i, []),
         }
@@ -72,7 +73,7 @@ EXPORTS = ["wino_status_string", "wino_last_hip_error", "wino_num_tiles", "wino_
            "wino_padded_dims", "wino_u_offset", "wino_v_offset", "wino_m_offset", "wino_filter_bytes",
            "wino_v_bytes", "wino_m_bytes", "wino_workspace_bytes", "wino_filter_transform",
            "wino_filter_transform_ex", "wino_input_transform", "wino_batched_gemm",
-           "wino_output_transform", "wino_conv2d_fwd", "wino_conv2d_fwd_ex", "direct_conv2d_fwd",
+           "wino_output_transform", "wino_conv2d_fwd", "wino_conv2d_fwd_ex", "wino_conv2d_variant", "direct_conv2d_fwd",
            "wino_shutdown"]
 
 
@@ -333,6 +334,14 @@ def wino_conv2d_fwd_ex(D, G=None, U=None, pad=1, m=4, Y=None, y_dtype=None, work
                                     _ptr(workspace), workspace.numel() * workspace.element_size(), flags,
                                     _stream(stream)), "wino_conv2d_fwd_ex")
     return Y
+
+
+def wino_conv2d_variant(N, C, H, W, K, pad, m, dt=WINO_F32, y_dt=WINO_F32, flags=FLAG_AUTO):
+    """FLAG_UNFUSED or FLAG_FUSED: the path wino_conv2d_fwd_ex takes; raises if it would be rejected."""
+    v = int(lib().wino_conv2d_variant(N, C, H, W, K, pad, m, dt, y_dt, flags))
+    if v < 0:
+        raise WinoError(-v, "wino_conv2d_variant")
+    return v
 
 
 def direct_conv2d_fwd(D, G, pad=1, stride=1, Y=None, stream=None):

@@ -226,6 +226,17 @@ int wino_output_transform(int N, int K, int H, int W, int pad, int m, int y_dt, 
     return e == hipSuccess ? WINO_OK : hip_fail(e);
 }
 
+int wino_conv2d_variant(int N, int C, int H, int W, int K, int pad, int m, int dt, int y_dt, unsigned flags)
+{
+    Geo g;
+    const int st = make_geo(N, C, H, W, K, pad, m, dt, &g);
+    if (st != WINO_OK) return -st;
+    if (bad_dtype(y_dt) || flags > WINO_FLAG_FUSED) return -WINO_EINVAL;
+    if (flags == WINO_FLAG_FUSED) return (fused_eligible(g) && y_dt == WINO_F32) ? (int)WINO_FLAG_FUSED : -WINO_EUNSUPPORTED;
+    if (flags == WINO_FLAG_AUTO && y_dt == WINO_F32 && fused_preferred(g)) return WINO_FLAG_FUSED;
+    return WINO_FLAG_UNFUSED;
+}
+
 int wino_conv2d_fwd_ex(int N, int C, int H, int W, int K, int pad, int m, int dt, int y_dt, const void *D,
                        const void *G, const void *U, void *Y, void *workspace, size_t workspace_bytes, unsigned flags,
                        void *stream)

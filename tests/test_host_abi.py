@@ -148,3 +148,21 @@ def test_flop_accounting_matches_table3(golden):
         if name != "total":
             got = int(depth) * bench.direct_flops(1, int(C), int(HW), int(HW), int(K)) / 1e9
             assert abs(got - float(gf)) < 0.0051
+
+
+def test_variant_query_host_only(L):
+    """Which path a call takes is decided on the host and can be asked without a GPU."""
+    # the VGG layers with few filters and many tiles go to the one-kernel path, the rest do not
+    assert w.wino_conv2d_variant(64, 64, 224, 224, 64, 1, 4) == w.FLAG_FUSED
+    assert w.wino_conv2d_variant(64, 128, 112, 112, 128, 1, 4) == w.FLAG_FUSED
+    assert w.wino_conv2d_variant(64, 512, 28, 28, 512, 1, 4) == w.FLAG_UNFUSED
+    assert w.wino_conv2d_variant(1, 64, 224, 224, 64, 1, 4) == w.FLAG_UNFUSED      # too few workgroups
+    assert w.wino_conv2d_variant(64, 64, 224, 224, 64, 1, 2) == w.FLAG_UNFUSED      # F(2x2) has no fused kernel
+    assert w.wino_conv2d_variant(64, 64, 224, 224, 64, 1, 4, flags=w.FLAG_UNFUSED) == w.FLAG_UNFUSED
+    assert w.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 4, flags=w.FLAG_FUSED) == w.FLAG_FUSED
+    assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 2, 0, 0, w.FLAG_FUSED) == -w.WINO_EUNSUPPORTED
+    assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 4, 1, 0, w.FLAG_FUSED) == -w.WINO_EUNSUPPORTED   # fp16
+    assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 3, 0, 0, 0) == -w.WINO_EUNSUPPORTED
+    assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 4, 0, 0, 7) == -w.WINO_EINVAL
+    # inputs of 2 GiB or more need 64-bit tap offsets: not eligible
+    assert L.wino_conv2d_variant(256, 64, 224, 224, 64, 1, 4, 0, 0, w.FLAG_FUSED) == -w.WINO_EUNSUPPORTED
