@@ -82,7 +82,8 @@ long long wino_m_offset(int K, long long P, int m, int xi, int nu, int k, long l
 size_t wino_filter_bytes(int K, int C, int m, int dt);           /* U */
 size_t wino_v_bytes(int C, long long P, int m, int dt);          /* V */
 size_t wino_m_bytes(int K, long long P, int m);                  /* M */
-/* Workspace wino_conv2d_fwd_ex needs: room for U, V and M of this problem. */
+/* Workspace wino_conv2d_fwd_ex needs: room for U, V and M of this problem (M several times over
+ * when the library splits the channel reduction of a small problem across workgroups). */
 size_t wino_workspace_bytes(int N, int C, int H, int W, int K, int pad, int m, int dt);
 
 /* ---- the four stages of Algorithm 1, one entry point each ------------------------------- */

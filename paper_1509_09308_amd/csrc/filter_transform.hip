@@ -10,14 +10,15 @@ template <typename T> __device__ __forceinline__ float ld_f(const T *p);
 template <> __device__ __forceinline__ float ld_f<float>(const float *p) { return *p; }
 template <> __device__ __forceinline__ float ld_f<__half>(const __half *p) { return __half2float(*p); }
 
-// One thread per (k, c) of the padded Kp x Cp grid, k fastest so that the alpha^2 stores of a
-// wavefront are contiguous.  A workgroup covers KT filters x CT channels; the 9*CT source
-// values of one filter are contiguous in G and are staged through LDS with coalesced loads.
+// One thread per (k, c) of the padded Kp x Cp grid, k fastest: a wavefront is 64 consecutive
+// filters of one channel, so each of its alpha^2 stores is 256 contiguous bytes.  A workgroup
+// covers KT filters x CT channels; the 9*CT source values of one filter are contiguous in G and
+// are staged through LDS with coalesced loads.
 template <int M, typename T>
 __global__ __launch_bounds__(256) void filter_transform_kernel(const T *__restrict__ G, T *__restrict__ U, int K,
                                                                int C, int Kp, int Cp)
 {
-    constexpr int A = M + 2, KT = 32, CT = 8, ROW = CT * 9 + 1;
+    constexpr int A = M + 2, KT = 64, CT = 4, ROW = CT * 9 + 1;
     __shared__ float gs[KT * ROW];
     const int k0 = blockIdx.x * KT, c0 = blockIdx.y * CT;
     for (int idx = threadIdx.x; idx < KT * CT * 9; idx += 256) {
@@ -63,7 +64,7 @@ __global__ __launch_bounds__(256) void filter_transform_kernel(const T *__restri
 
 hipError_t launch_filter_transform(const Geo &g, const void *G, void *U, hipStream_t s)
 {
-    dim3 grid((g.Kp + 31) / 32, (g.Cp + 7) / 8), block(256);
+    dim3 grid((g.Kp + 63) / 64, (g.Cp + 3) / 4), block(256);
     if (g.dt == WINO_F32) {
         if (g.m == 2)
             filter_transform_kernel<2, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, g.K, g.C, g.Kp, g.Cp);

@@ -36,7 +36,7 @@ template <int BM, int BN, int WM, int WN, int BK>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_f32_kernel(const float *__restrict__ U,
                                                                  const float *__restrict__ V,
                                                                  float *__restrict__ Mo, int Kp, int Cp, int Pp,
-                                                                 int tiles_m, int tiles_n)
+                                                                 int tiles_m, int tiles_n, int a2, int nk_split)
 {
     constexpr int NT = 64 * WM * WN;
     constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);
@@ -52,12 +52,15 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_f32_kernel(const float *__r
     const int tm_i = bid % tiles_m;
     bid /= tiles_m;
     const int tn_i = bid % tiles_n;
-    const int e = bid / tiles_n;
+    bid /= tiles_n;
+    const int e = bid % a2;
+    const int z = bid / a2;   // which share of the channel loop (layers with few blocks split it)
     const int k0 = tm_i * BM, p0 = tn_i * BN;
+    const int c_first = z * nk_split * BK;
 
-    const float *Ue = U + (size_t)e * Cp * Kp;
-    const float *Ve = V + (size_t)e * Cp * Pp;
-    float *Me = Mo + (size_t)e * Kp * Pp;
+    const float *Ue = U + ((size_t)e * Cp + c_first) * Kp;
+    const float *Ve = V + ((size_t)e * Cp + c_first) * Pp;
+    float *Me = Mo + ((size_t)z * a2 + e) * Kp * Pp;
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
@@ -126,7 +129,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_f32_kernel(const float *__r
     };
 
     float a0[HS][TM], b0[HS][TN], a1[HS][TM], b1[HS][TN];
-    const int nk = Cp / BK;
+    const int nk = min(nk_split, Cp / BK - z * nk_split);   // >= 1 by construction of the launch
     load_global();
     store_lds(0);
     __syncthreads();
@@ -162,13 +165,17 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_f32_kernel(const float *__r
 }
 
 template <int BM, int BN, int WM, int WN, int BK>
-static hipError_t launch_f32(const Geo &g, const float *U, const float *V, float *M, hipStream_t s)
+static hipError_t launch_f32(const Geo &g, const float *U, const float *V, float *M, int splits, hipStream_t s)
 {
     const int tiles_m = (g.Kp + BM - 1) / BM, tiles_n = (g.Pp + BN - 1) / BN;
-    const long long blocks = (long long)tiles_m * tiles_n * g.a2;
+    const int nk = g.Cp / BK;
+    const int nk_split = (nk + splits - 1) / splits;
+    const int used = (nk + nk_split - 1) / nk_split;   // every share gets at least one slab
+    if (used != splits) return hipErrorInvalidValue;
+    const long long blocks = (long long)tiles_m * tiles_n * g.a2 * splits;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     gemm_f32_kernel<BM, BN, WM, WN, BK><<<dim3((unsigned)blocks), dim3(64 * WM * WN), 0, s>>>(
-        U, V, M, g.Kp, g.Cp, g.Pp, tiles_m, tiles_n);
+        U, V, M, g.Kp, g.Cp, g.Pp, tiles_m, tiles_n, g.a2, nk_split);
     return hipGetLastError();
 }
 
@@ -305,34 +312,66 @@ static hipError_t launch_f16(const Geo &g, const void *U, const void *V, float *
     return hipGetLastError();
 }
 
-hipError_t launch_batched_gemm(const Geo &g, const void *U, const void *V, float *M, hipStream_t s)
+// Launch shape of the fp32 multiply: block tile and number of shares of the channel loop.
+// Large problems use 128 x 128 blocks and no split.  A problem with few blocks (small batch,
+// small images) would leave most of the 256 CUs idle while each block runs a long serial loop,
+// so it gets 64-wide blocks and, if that is still short of one block per CU, its reduction over
+// C is spread over 2, 4 or 8 groups of blocks, each writing its own partial M (the inverse
+// transform adds the partials while gathering).  More than one round of blocks per CU does not
+// pay: every block has a fixed prologue and epilogue.
+struct GemmShape { int bm, bn, splits; };
+
+static GemmShape gemm_shape(const Geo &g)
 {
-    const bool wide_m = g.Kp >= 128, wide_n = g.Pp >= 128;
+    GemmShape sh;
+    sh.bm = g.Kp >= 128 ? 128 : 64;
+    sh.bn = g.Pp >= 128 ? 128 : 64;
+    sh.splits = 1;
+    if (g.dt != WINO_F32) return sh;
+    auto blocks = [&](int bm, int bn) {
+        return (long long)((g.Kp + bm - 1) / bm) * ((g.Pp + bn - 1) / bn) * g.a2;
+    };
+    const char *tile = getenv("WINO_GEMM_TILE");   // tuning sweeps only: 1 = 64x64, 2 = 128x64, 3 = 64x128
+    if (tile) {
+        const int t = atoi(tile);
+        if (t == 1) { sh.bm = 64; sh.bn = 64; }
+        if (t == 2) { sh.bm = 128; sh.bn = 64; }
+        if (t == 3) { sh.bm = 64; sh.bn = 128; }
+    } else {
+        if (blocks(sh.bm, sh.bn) < 512 && sh.bn == 128) sh.bn = 64;
+        if (blocks(sh.bm, sh.bn) < 512 && sh.bm == 128) sh.bm = 64;
+    }
+    const int nk = g.Cp / 16;
+    const char *tune = getenv("WINO_GEMM_SPLITS");   // tuning sweeps only
+    if (tune) {
+        const int want = atoi(tune);
+        while (sh.splits < want && nk % (sh.splits * 2) == 0) sh.splits *= 2;
+        return sh;
+    }
+    const long long b = blocks(sh.bm, sh.bn);
+    while (sh.splits < 8 && b * sh.splits * 2 <= 256 && nk % (sh.splits * 2) == 0 && nk / (sh.splits * 2) >= 2)
+        sh.splits *= 2;
+    return sh;
+}
+
+int gemm_splits(const Geo &g) { return gemm_shape(g).splits; }
+
+hipError_t launch_batched_gemm(const Geo &g, const void *U, const void *V, float *M, int splits, hipStream_t s)
+{
     if (g.dt == WINO_F16) {
+        const bool wide_m = g.Kp >= 128, wide_n = g.Pp >= 128;
+        if (splits != 1) return hipErrorInvalidValue;
         if (wide_m && wide_n) return launch_f16<128, 128>(g, U, V, M, s);
         if (wide_m) return launch_f16<128, 64>(g, U, V, M, s);
         if (wide_n) return launch_f16<64, 128>(g, U, V, M, s);
         return launch_f16<64, 64>(g, U, V, M, s);
     }
     const float *u = (const float *)U, *v = (const float *)V;
-    const char *tune = getenv("WINO_GEMM_TILE");   // tuning sweeps only
-    const int forced = tune ? atoi(tune) : 0;
-    switch (forced) {
-    case 1: return launch_f32<128, 128, 2, 2, 16>(g, u, v, M, s);
-    case 2: return launch_f32<128, 128, 2, 2, 32>(g, u, v, M, s);
-    case 3: return launch_f32<256, 128, 2, 2, 16>(g, u, v, M, s);
-    case 4: return launch_f32<128, 256, 2, 2, 16>(g, u, v, M, s);
-    case 5: return launch_f32<256, 128, 4, 2, 16>(g, u, v, M, s);
-    case 6: return launch_f32<128, 256, 2, 4, 16>(g, u, v, M, s);
-    case 7: return launch_f32<256, 256, 4, 2, 16>(g, u, v, M, s);
-    case 8: return launch_f32<64, 128, 1, 4, 16>(g, u, v, M, s);
-    case 9: return launch_f32<64, 256, 1, 4, 16>(g, u, v, M, s);
-    default: break;
-    }
-    if (wide_m && wide_n) return launch_f32<128, 128, 2, 2, 16>(g, u, v, M, s);
-    if (wide_m) return launch_f32<128, 64, 2, 2, 16>(g, u, v, M, s);
-    if (wide_n) return launch_f32<64, 128, 2, 2, 16>(g, u, v, M, s);
-    return launch_f32<64, 64, 2, 2, 16>(g, u, v, M, s);
+    const GemmShape sh = gemm_shape(g);
+    if (sh.bm == 128 && sh.bn == 128) return launch_f32<128, 128, 2, 2, 16>(g, u, v, M, splits, s);
+    if (sh.bm == 128) return launch_f32<128, 64, 2, 2, 16>(g, u, v, M, splits, s);
+    if (sh.bn == 128) return launch_f32<64, 128, 2, 2, 16>(g, u, v, M, splits, s);
+    return launch_f32<64, 64, 2, 2, 16>(g, u, v, M, splits, s);
 }
 
 }  // namespace wino

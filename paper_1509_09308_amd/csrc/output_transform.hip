@@ -13,7 +13,8 @@ template <> __device__ __forceinline__ void st_out<__half>(__half *p, float v) {
 // One thread per (k, b), b fastest: loads from every M^(xi,nu) row are contiguous across a
 // wavefront, and neighbouring threads write neighbouring m-wide output segments.
 template <int M, typename T>
-__global__ __launch_bounds__(256) void output_transform_kernel(const float *__restrict__ Min, T *__restrict__ Y, Geo g)
+__global__ __launch_bounds__(256) void output_transform_kernel(const float *__restrict__ Min, T *__restrict__ Y, Geo g,
+                                                               int splits)
 {
     constexpr int A = M + 2;
     const int b = blockIdx.x * 256 + threadIdx.x;
@@ -25,6 +26,14 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float *__re
 #pragma unroll
         for (int nu = 0; nu < A; ++nu)
             mm[xi][nu] = Min[((size_t)(xi * A + nu) * g.Kp + k) * g.Pp + b];
+    // partial products of a split channel loop are added here, in the order of the shares
+    const size_t zstride = (size_t)A * A * g.Kp * g.Pp;
+    for (int z = 1; z < splits; ++z)
+#pragma unroll
+        for (int xi = 0; xi < A; ++xi)
+#pragma unroll
+            for (int nu = 0; nu < A; ++nu)
+                mm[xi][nu] += Min[z * zstride + ((size_t)(xi * A + nu) * g.Kp + k) * g.Pp + b];
     // t = A^T m (columns), y = t A (rows)
     float t[M][A], y[M][M];
 #pragma unroll
@@ -64,19 +73,19 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float *__re
     }
 }
 
-hipError_t launch_output_transform(const Geo &g, int y_dt, const float *M, void *Y, hipStream_t s)
+hipError_t launch_output_transform(const Geo &g, int y_dt, const float *M, void *Y, int splits, hipStream_t s)
 {
     dim3 grid((g.P + 255) / 256, g.K), block(256);
     if (y_dt == WINO_F32) {
         if (g.m == 2)
-            output_transform_kernel<2, float><<<grid, block, 0, s>>>(M, (float *)Y, g);
+            output_transform_kernel<2, float><<<grid, block, 0, s>>>(M, (float *)Y, g, splits);
         else
-            output_transform_kernel<4, float><<<grid, block, 0, s>>>(M, (float *)Y, g);
+            output_transform_kernel<4, float><<<grid, block, 0, s>>>(M, (float *)Y, g, splits);
     } else {
         if (g.m == 2)
-            output_transform_kernel<2, __half><<<grid, block, 0, s>>>(M, (__half *)Y, g);
+            output_transform_kernel<2, __half><<<grid, block, 0, s>>>(M, (__half *)Y, g, splits);
         else
-            output_transform_kernel<4, __half><<<grid, block, 0, s>>>(M, (__half *)Y, g);
+            output_transform_kernel<4, __half><<<grid, block, 0, s>>>(M, (__half *)Y, g, splits);
     }
     return hipGetLastError();
 }

@@ -176,7 +176,7 @@ size_t wino_workspace_bytes(int N, int C, int H, int W, int K, int pad, int m, i
 {
     Geo g;
     if (make_geo(N, C, H, W, K, pad, m, dt, &g) != WINO_OK) return 0;
-    return align256(u_bytes(g)) + align256(v_bytes(g)) + align256(m_bytes(g));
+    return align256(u_bytes(g)) + align256(v_bytes(g)) + align256(m_bytes(g) * gemm_splits(g));
 }
 
 int wino_filter_transform_ex(int K, int C, int m, int dt, const void *G, void *U, void *stream)
@@ -210,7 +210,7 @@ int wino_batched_gemm(int K, int C, long long P, int m, int dt, const void *U, c
     const int st = make_geo_kcp(K, C, P, m, dt, &g);
     if (st != WINO_OK) return st;
     if (bad_ptr(U) || bad_ptr(V) || bad_ptr(M)) return WINO_EINVAL;
-    const hipError_t e = launch_batched_gemm(g, U, V, (float *)M, (hipStream_t)stream);
+    const hipError_t e = launch_batched_gemm(g, U, V, (float *)M, 1, (hipStream_t)stream);
     if (e == hipErrorNotSupported) return WINO_EUNSUPPORTED;
     return e == hipSuccess ? WINO_OK : hip_fail(e);
 }
@@ -222,7 +222,7 @@ int wino_output_transform(int N, int K, int H, int W, int pad, int m, int y_dt, 
     if (st != WINO_OK) return st;
     if (bad_dtype(y_dt)) return WINO_EINVAL;
     if (bad_ptr(M) || bad_ptr(Y)) return WINO_EINVAL;
-    const hipError_t e = launch_output_transform(g, y_dt, (const float *)M, Y, (hipStream_t)stream);
+    const hipError_t e = launch_output_transform(g, y_dt, (const float *)M, Y, 1, (hipStream_t)stream);
     return e == hipSuccess ? WINO_OK : hip_fail(e);
 }
 
@@ -249,7 +249,8 @@ int wino_conv2d_fwd_ex(int N, int C, int H, int W, int K, int pad, int m, int dt
     if (flags == WINO_FLAG_FUSED && (!fused_eligible(g) || y_dt != WINO_F32)) return WINO_EUNSUPPORTED;
     if (bad_ptr(D) || bad_ptr(Y) || bad_ptr(workspace)) return WINO_EINVAL;
     if (U == nullptr ? bad_ptr(G) : !aligned16(U)) return WINO_EINVAL;
-    const size_t ub = align256(u_bytes(g)), vb = align256(v_bytes(g)), mb = align256(m_bytes(g));
+    const int splits = gemm_splits(g);
+    const size_t ub = align256(u_bytes(g)), vb = align256(v_bytes(g)), mb = align256(m_bytes(g) * splits);
     if (workspace_bytes < ub + vb + mb) return WINO_EWORKSPACE;
     char *ws = (char *)workspace;
     void *Uw = ws, *Vw = ws + ub;
@@ -266,9 +267,9 @@ int wino_conv2d_fwd_ex(int N, int C, int H, int W, int K, int pad, int m, int dt
         return WINO_OK;
     }
     if ((e = launch_input_transform(g, D, Vw, s)) != hipSuccess) return hip_fail(e);
-    if ((e = launch_batched_gemm(g, U, Vw, Mw, s)) != hipSuccess)
+    if ((e = launch_batched_gemm(g, U, Vw, Mw, splits, s)) != hipSuccess)
         return e == hipErrorNotSupported ? (int)WINO_EUNSUPPORTED : hip_fail(e);
-    if ((e = launch_output_transform(g, y_dt, Mw, Y, s)) != hipSuccess) return hip_fail(e);
+    if ((e = launch_output_transform(g, y_dt, Mw, Y, splits, s)) != hipSuccess) return hip_fail(e);
     return WINO_OK;
 }
 

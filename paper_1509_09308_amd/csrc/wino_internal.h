@@ -29,8 +29,9 @@ inline int pad_p(long long P) { return round_up(P, 32); }
 // Kernel launchers (each enqueues on `s` and returns the launch status).
 hipError_t launch_filter_transform(const Geo &g, const void *G, void *U, hipStream_t s);
 hipError_t launch_input_transform(const Geo &g, const void *D, void *V, hipStream_t s);
-hipError_t launch_batched_gemm(const Geo &g, const void *U, const void *V, float *M, hipStream_t s);
-hipError_t launch_output_transform(const Geo &g, int y_dt, const float *M, void *Y, hipStream_t s);
+int gemm_splits(const Geo &g);
+hipError_t launch_batched_gemm(const Geo &g, const void *U, const void *V, float *M, int splits, hipStream_t s);
+hipError_t launch_output_transform(const Geo &g, int y_dt, const float *M, void *Y, int splits, hipStream_t s);
 bool fused_eligible(const Geo &g);
 bool fused_preferred(const Geo &g);
 hipError_t launch_fused(const Geo &g, const float *D, const float *U, float *Y, hipStream_t s);
