@@ -32,8 +32,11 @@ def _load():
         lib.oracle_conv2d_fwd_f64.argtypes = [i] * 9 + [p, p, p]
         lib.oracle_conv2d_fwd_f32in.argtypes = [i] * 9 + [p, p, p]
         lib.oracle_conv2d_points_f32in.argtypes = [i] * 9 + [p, p, l, p, p]
+        lib.oracle_conv2d_bwd_data_f64.argtypes = [i] * 9 + [p, p, p]
+        lib.oracle_conv2d_bwd_data_points_f32in.argtypes = [i] * 9 + [p, p, l, p, p]
         for f in (lib.oracle_conv2d_fwd_f64, lib.oracle_conv2d_fwd_f32in,
-                  lib.oracle_conv2d_points_f32in):
+                  lib.oracle_conv2d_points_f32in, lib.oracle_conv2d_bwd_data_f64,
+                  lib.oracle_conv2d_bwd_data_points_f32in):
             f.restype = None
         _lib = lib
     return _lib
@@ -89,4 +92,39 @@ def conv2d_points(D, G, pts, pad=1, stride=1):
     out = np.empty(len(pts), dtype=np.float64)
     _load().oracle_conv2d_points_f32in(N, C, H, W, K, R, S, pad, stride, D.ctypes.data,
                                        G.ctypes.data, len(pts), pts.ctypes.data, out.ctypes.data)
+    return out
+
+
+def conv2d_bwd_data(E, G, H, W, pad=1, stride=1):
+    """Gradient of the layer with respect to its input: E[N,K,Ho,Wo], G[K,C,R,S] -> dD[N,C,H,W] (fp64).
+    Stored fp16/fp32 tensors are widened exactly."""
+    E = np.ascontiguousarray(np.asarray(E), dtype=np.float64)
+    G = np.ascontiguousarray(np.asarray(G), dtype=np.float64)
+    N, K = E.shape[0], E.shape[1]
+    K2, C, R, S = G.shape
+    Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    if K2 != K or E.shape[2:] != (Ho, Wo):
+        raise ValueError("error tensor does not match the layer geometry")
+    dD = np.empty((N, C, H, W), dtype=np.float64)
+    _load().oracle_conv2d_bwd_data_f64(N, C, H, W, K, R, S, pad, stride, E.ctypes.data, G.ctypes.data,
+                                       dD.ctypes.data)
+    return dD
+
+
+def conv2d_bwd_data_points(E, G, H, W, pts, pad=1, stride=1):
+    """Selected elements of the input gradient; ``pts`` is an (n,4) array of (i,c,x,y)."""
+    E = np.ascontiguousarray(E, dtype=np.float32)
+    G = np.ascontiguousarray(G, dtype=np.float32)
+    N, K = E.shape[0], E.shape[1]
+    K2, C, R, S = G.shape
+    Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    if K2 != K or E.shape[2:] != (Ho, Wo):
+        raise ValueError("error tensor does not match the layer geometry")
+    pts = np.ascontiguousarray(pts, dtype=np.int32).reshape(-1, 4)
+    hi = np.array([N, C, H, W])
+    if pts.size and ((pts < 0).any() or (pts >= hi).any()):
+        raise ValueError("sample point outside the gradient tensor")
+    out = np.empty(len(pts), dtype=np.float64)
+    _load().oracle_conv2d_bwd_data_points_f32in(N, C, H, W, K, R, S, pad, stride, E.ctypes.data, G.ctypes.data,
+                                                len(pts), pts.ctypes.data, out.ctypes.data)
     return out

@@ -114,3 +114,60 @@ void oracle_conv2d_points_f32in(int N, int C, int H, int W, int K, int R, int S,
         out[j] = acc;
     }
 }
+
+/* Gradient of Eq. (1) with respect to the images (Section 4.2: the backpropagated error, of
+ * dimension N x K x Ho x Wo, correlated with the flipped filters).  Written out from Eq. (1)
+ * itself: Y[i][k][x'][y'] depends on D[i][c][x'*stride+u-pad][y'*stride+v-pad] with weight
+ * G[k][c][u][v], so
+ *   dD[i][c][x][y] = sum_k sum_u sum_v E[i][k][x'][y'] * G[k][c][u][v]
+ * over the (u, v) for which x' = (x + pad - u)/stride and y' = (y + pad - v)/stride are integers
+ * inside the output.  E is the error tensor [N][K][Ho][Wo]; the result is [N][C][H][W] in fp64. */
+void oracle_conv2d_bwd_data_f64(int N, int C, int H, int W, int K, int R, int S, int pad, int stride,
+                                const double *E, const double *G, double *dD)
+{
+    const int Ho = out_extent(H, pad, R, stride), Wo = out_extent(W, pad, S, stride);
+    #pragma omp parallel for collapse(2) schedule(static)
+    for (int i = 0; i < N; ++i)
+        for (int c = 0; c < C; ++c)
+            for (int x = 0; x < H; ++x)
+                for (int y = 0; y < W; ++y) {
+                    double acc = 0.0;
+                    for (int k = 0; k < K; ++k)
+                        for (int u = 0; u < R; ++u)
+                            for (int v = 0; v < S; ++v) {
+                                const int xs = x + pad - u, ys = y + pad - v;
+                                if (xs < 0 || ys < 0 || xs % stride || ys % stride) continue;
+                                const int xo = xs / stride, yo = ys / stride;
+                                if (xo < Ho && yo < Wo)
+                                    acc += E[(((size_t)i * K + k) * Ho + xo) * Wo + yo] *
+                                           G[(((size_t)k * C + c) * R + u) * S + v];
+                            }
+                    dD[(((size_t)i * C + c) * H + x) * W + y] = acc;
+                }
+}
+
+/* The same sum for selected elements of dD: pts holds npts quadruples (i, c, x, y); inputs are the
+ * stored single-precision tensors, products and sums in double. */
+void oracle_conv2d_bwd_data_points_f32in(int N, int C, int H, int W, int K, int R, int S, int pad, int stride,
+                                         const float *E, const float *G, long npts, const int32_t *pts,
+                                         double *out)
+{
+    (void)N;
+    const int Ho = out_extent(H, pad, R, stride), Wo = out_extent(W, pad, S, stride);
+    #pragma omp parallel for schedule(static)
+    for (long j = 0; j < npts; ++j) {
+        const int i = pts[4 * j + 0], c = pts[4 * j + 1], x = pts[4 * j + 2], y = pts[4 * j + 3];
+        double acc = 0.0;
+        for (int k = 0; k < K; ++k)
+            for (int u = 0; u < R; ++u)
+                for (int v = 0; v < S; ++v) {
+                    const int xs = x + pad - u, ys = y + pad - v;
+                    if (xs < 0 || ys < 0 || xs % stride || ys % stride) continue;
+                    const int xo = xs / stride, yo = ys / stride;
+                    if (xo < Ho && yo < Wo)
+                        acc += (double)E[(((size_t)i * K + k) * Ho + xo) * Wo + yo] *
+                               (double)G[(((size_t)k * C + c) * R + u) * S + v];
+                }
+        out[j] = acc;
+    }
+}

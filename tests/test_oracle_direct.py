@@ -113,3 +113,56 @@ def test_points_equal_full_tensor():
     assert np.array_equal(got, Y[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]])
     with pytest.raises(ValueError):
         direct.conv2d_points(D, G, [[0, 0, 9, 0]])
+
+
+# ---- gradient with respect to the input (Section 4.2, first paragraph) ----------------------------
+
+@pytest.mark.parametrize("shape", [(2, 3, 7, 9, 4, 3, 3, 1, 1), (1, 2, 8, 8, 3, 3, 3, 0, 1), (2, 3, 9, 8, 2, 3, 3, 1, 2),
+                                   (1, 4, 6, 6, 5, 1, 1, 0, 1), (1, 2, 10, 7, 3, 5, 5, 2, 1)])
+def test_bwd_data_is_the_adjoint_of_the_layer(shape):
+    """<conv(D, G), E> == <D, bwd(E, G)> exactly on small integers: the defining property of
+    the input gradient, independent of how either side is computed."""
+    N, C, H, W, K, R, S, pad, stride = shape
+    rng = np.random.default_rng(sum(shape))
+    D = rng.integers(-5, 6, (N, C, H, W)).astype(np.float64)
+    G = rng.integers(-5, 6, (K, C, R, S)).astype(np.float64)
+    Y = direct.conv2d_fwd(D, G, pad=pad, stride=stride)
+    E = rng.integers(-5, 6, Y.shape).astype(np.float64)
+    dD = direct.conv2d_bwd_data(E, G, H, W, pad=pad, stride=stride)
+    assert dD.shape == D.shape
+    assert float((Y * E).sum()) == float((D * dD).sum())
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 7, 9, 4, 3, 3, 1, 1), (1, 2, 8, 8, 3, 3, 3, 0, 1), (2, 3, 9, 8, 2, 3, 3, 1, 2)])
+def test_bwd_data_against_torch_autograd_float64(shape):
+    N, C, H, W, K, R, S, pad, stride = shape
+    rng = np.random.default_rng(sum(shape) + 1)
+    D = torch.from_numpy(rng.standard_normal((N, C, H, W))).requires_grad_(True)
+    G = torch.from_numpy(rng.standard_normal((K, C, R, S)))
+    Y = torch.nn.functional.conv2d(D, G, padding=pad, stride=stride)
+    E = torch.from_numpy(rng.standard_normal(tuple(Y.shape)))
+    Y.backward(E)
+    got = direct.conv2d_bwd_data(E.numpy(), G.numpy(), H, W, pad=pad, stride=stride)
+    assert np.abs(got - D.grad.numpy()).max() < 1e-12
+
+
+def test_bwd_data_equals_forward_with_flipped_swapped_filters():
+    """Section 4.2: for 3x3, stride 1, pad 1 the input gradient is the forward layer applied to
+    the error with the filters flipped by 180 degrees and K, C exchanged."""
+    rng = np.random.default_rng(12)
+    E = rng.standard_normal((2, 5, 9, 11))
+    G = rng.standard_normal((5, 4, 3, 3))
+    Gf = np.ascontiguousarray(G[:, :, ::-1, ::-1].transpose(1, 0, 2, 3))
+    a = direct.conv2d_bwd_data(E, G, 9, 11, pad=1)
+    b = direct.conv2d_fwd(E, Gf, pad=1)
+    assert np.abs(a - b).max() < 1e-12
+
+
+def test_bwd_data_points_equal_full_tensor():
+    rng = np.random.default_rng(13)
+    E = rng.standard_normal((2, 6, 9, 11)).astype(np.float32)
+    G = rng.standard_normal((6, 4, 3, 3)).astype(np.float32)
+    full = direct.conv2d_bwd_data(E, G, 9, 11, pad=1)
+    pts = np.stack([rng.integers(0, n, 100) for n in full.shape], axis=1)
+    got = direct.conv2d_bwd_data_points(E, G, 9, 11, pts, pad=1)
+    assert np.array_equal(got, full[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]])
