@@ -14,6 +14,7 @@ Prints ONE JSON line.  Besides the contract fields it carries
                 timed per launch with HIP events in a separate pass over the same launches;
   stages        per-stage achieved GB/s (transforms) and TFLOP/s (multiply), per layer;
   n1            the same stack at batch 1 (the latency case of the paper's Table 5);
+  bwd_data      the input gradient of the same layers (Section 4.2: same algorithm, rotated filters);
   cpu_baseline  the fp64 CPU oracle timed on a bounded sample of the same workload.
 """
 import argparse
@@ -178,6 +179,33 @@ def time_stages(torch, w, layers, ws, steps):
     return res
 
 
+def time_bwd_data(torch, w, layers, ws_bytes, steps):
+    """Input gradient (Section 4.2 of the paper) of the 12 layers that need one (not the first):
+    the error tensor is the layer's output buffer, same algorithm choice as the forward pass."""
+    todo = [L for L in layers if not L.direct]
+    need = max(w.wino_workspace_bytes(L.N, L.K, L.HW, L.HW, L.C, 1, L.m, L.dt) for L in todo)
+    ws = torch.empty(max(need, ws_bytes), dtype=torch.uint8, device="cuda")
+    grads = [torch.empty_like(L.D, dtype=torch.float32) for L in todo]
+
+    def step():
+        for L, dD in zip(todo, grads):
+            w.wino_conv2d_bwd_data(L.Y.to(L.D.dtype) if L.Y.dtype != L.D.dtype else L.Y, G=L.G, pad=1, m=L.m, dD=dD,
+                                   workspace=ws)
+    if any(L.Y.dtype != L.D.dtype for L in todo):
+        return None   # fp16 storage keeps fp32 outputs: no resident fp16 error tensor to time
+    for _ in range(2):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / steps
+    flops = sum(L.flops for L in todo)
+    return {"eff_tflops": flops / sec / 1e12, "ms_per_step": sec * 1e3, "layers": len(todo),
+            "note": "conv1.1 needs no input gradient; effective flops as for the forward pass"}
+
+
 def cpu_baseline(layers, budget_s=12.0, max_images=32):
     """The fp64 oracle (Eq. (1)) on the host cores over whole images of the same workload:
     image after image through all 13 layers until about `budget_s` seconds have been spent."""
@@ -209,6 +237,7 @@ def main():
     ap.add_argument("--no-n1", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stages", action="store_true")
+    ap.add_argument("--no-bwd", action="store_true", help="skip the input-gradient line")
     ap.add_argument("--probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 1 GiB device copy (counter calibration), then every "
                          "kernel of one step once; prints the algorithmic bytes per kernel and exits")
@@ -316,6 +345,10 @@ def main():
                                          "unit": "GB/s", "frac": hb / hms / 1e6 / PEAK["hbm_GBs"],
                                          "kernels": "input_transform + output_transform of the unfused layers"}
 
+    if not args.no_bwd:
+        bd = time_bwd_data(torch, w, layers, ws.numel(), max(3, args.steps // 2))
+        if bd:
+            out["bwd_data"] = bd
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers)
     if not args.no_n1 and args.batch != 1:

@@ -117,6 +117,21 @@ int wino_conv2d_fwd(int N, int C, int H, int W, int K, int pad, int m, const voi
 int wino_conv2d_fwd_ex(int N, int C, int H, int W, int K, int pad, int m, int dt, int y_dt, const void *D,
                        const void *G, const void *U, void *Y, void *workspace, size_t workspace_bytes,
                        unsigned flags, void *stream);
+/* ---- gradient with respect to the input (Section 4.2 of the paper) --------------------------
+ * dD[i][c][x][y] = sum_k sum_u sum_v E[i][k][x+pad-u][y+pad-v] * G[k][c][u][v]: the forward algorithm
+ * applied to the error tensor E[N][K][H][W] with every filter rotated by 180 degrees and K, C
+ * exchanged.  Only pad = 1 (then E has the extent of D); other pads give WINO_EUNSUPPORTED. */
+
+/* G[K][C][3][3] -> U' for the exchanged layer: the layout is that of a forward U with C filters
+ * and K channels (sizes and offsets from wino_filter_bytes(C, K, ...), wino_u_offset(C, K, ...)). */
+int wino_filter_transform_bwd(int K, int C, int m, int dt, const void *G, void *U, void *stream);
+/* E[N][K][H][W] (type dt), G[K][C][3][3] (type dt) or its wino_filter_transform_bwd output U (then
+ * G may be NULL) -> dD[N][C][H][W] (type d_dt).  Workspace: wino_workspace_bytes(N, K, H, W, C, 1, m, dt)
+ * (the forward query with K and C exchanged).  `flags` as for wino_conv2d_fwd_ex. */
+int wino_conv2d_bwd_data(int N, int C, int H, int W, int K, int pad, int m, int dt, int d_dt, const void *E,
+                         const void *G, const void *U, void *dD, void *workspace, size_t workspace_bytes,
+                         unsigned flags, void *stream);
+
 /* Host-side query: the variant wino_conv2d_fwd_ex runs for these arguments -- WINO_FLAG_UNFUSED or
  * WINO_FLAG_FUSED -- when called with `flags` (WINO_FLAG_AUTO resolves to one of the two); a negative
  * wino_status_t (e.g. -WINO_EUNSUPPORTED) if the call would be rejected. */

@@ -59,6 +59,8 @@ def lib():
             "wino_conv2d_fwd": (i, [i] * 7 + [p, p, p, p]),
             "wino_conv2d_fwd_ex": (i, [i] * 9 + [p, p, p, p, p, sz, u, p]),
             "wino_conv2d_variant": (i, [i] * 9 + [u]),
+            "wino_filter_transform_bwd": (i, [i, i, i, i, p, p, p]),
+            "wino_conv2d_bwd_data": (i, [i] * 9 + [p, p, p, p, p, sz, u, p]),
             "direct_conv2d_fwd": (i, [i] * 10 + [p, p, p, p]),
             "wino_shutdown": (i, []),
         }
@@ -73,7 +75,8 @@ EXPORTS = ["wino_status_string", "wino_last_hip_error", "wino_num_tiles", "wino_
            "wino_padded_dims", "wino_u_offset", "wino_v_offset", "wino_m_offset", "wino_filter_bytes",
            "wino_v_bytes", "wino_m_bytes", "wino_workspace_bytes", "wino_filter_transform",
            "wino_filter_transform_ex", "wino_input_transform", "wino_batched_gemm",
-           "wino_output_transform", "wino_conv2d_fwd", "wino_conv2d_fwd_ex", "wino_conv2d_variant", "direct_conv2d_fwd",
+           "wino_output_transform", "wino_conv2d_fwd", "wino_conv2d_fwd_ex", "wino_conv2d_variant", "wino_filter_transform_bwd", "wino_conv2d_bwd_data",
+           "direct_conv2d_fwd",
            "wino_shutdown"]
 
 
@@ -342,6 +345,39 @@ def wino_conv2d_variant(N, C, H, W, K, pad, m, dt=WINO_F32, y_dt=WINO_F32, flags
     if v < 0:
         raise WinoError(-v, "wino_conv2d_variant")
     return v
+
+
+def wino_filter_transform_bwd(G, m, U=None, stream=None):
+    """G[K,C,3,3] -> U' of the exchanged layer (C filters, K channels), filters rotated by 180 degrees."""
+    _dense_cuda(G, "G")
+    K, C = G.shape[0], G.shape[1]
+    dt = _dt(G)
+    if U is None:
+        U = alloc_u(C, K, m, dt, G.device)
+    _check(lib().wino_filter_transform_bwd(K, C, m, dt, _ptr(G), _ptr(U), _stream(stream)),
+           "wino_filter_transform_bwd")
+    return U
+
+
+def wino_conv2d_bwd_data(E, G=None, U=None, C=None, pad=1, m=4, dD=None, d_dtype=None, workspace=None,
+                         flags=FLAG_AUTO, stream=None):
+    """Input gradient: E[N,K,H,W] and G[K,C,3,3] (or its bwd-transformed U plus C) -> dD[N,C,H,W]."""
+    import torch
+    _dense_cuda(E, "E")
+    N, K, H, W = E.shape
+    if G is not None:
+        C = G.shape[1]
+    if C is None:
+        raise ValueError("C is required when only U is given")
+    dt = _dt(E)
+    if dD is None:
+        dD = torch.empty((N, C, H, W), dtype=d_dtype or torch.float32, device=E.device)
+    if workspace is None:
+        workspace = alloc_workspace(N, K, H, W, C, pad, m, dt, E.device)
+    _check(lib().wino_conv2d_bwd_data(N, C, H, W, K, pad, m, dt, _dt(dD), _ptr(E), _ptr(G), _ptr(U), _ptr(dD),
+                                      _ptr(workspace), workspace.numel() * workspace.element_size(), flags,
+                                      _stream(stream)), "wino_conv2d_bwd_data")
+    return dD
 
 
 def direct_conv2d_fwd(D, G, pad=1, stride=1, Y=None, stream=None):

@@ -62,6 +62,66 @@ __global__ __launch_bounds__(256) void filter_transform_kernel(const T *__restri
         }
 }
 
+// Filter transform for the gradient with respect to the input (Section 4.2 of the paper): that
+// gradient is the forward algorithm applied to the error tensor with every filter rotated by
+// 180 degrees and the roles of filters and channels exchanged.  So the output is a U for a layer
+// with K' = C "filters" and C' = K "channels": U'[e][c' = k][k' = c] = (G g~ G^T)[e] with
+// g~[u][v] = g_{k,c}[2-u][2-v].  One thread per (k', c'), k' fastest.
+template <int M, typename T>
+__global__ __launch_bounds__(256) void filter_transform_bwd_kernel(const T *__restrict__ G, T *__restrict__ U, int K,
+                                                                   int C, int Kp2, int Cp2)
+{
+    constexpr int A = M + 2;
+    const int k2 = blockIdx.x * 64 + threadIdx.x % 64;   // = c of G
+    const int c2 = blockIdx.y * 4 + threadIdx.x / 64;    // = k of G
+    if (k2 >= Kp2 || c2 >= Cp2) return;
+    float g[3][3], t[A][3], u[A][A];
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+#pragma unroll
+        for (int j = 0; j < 3; ++j)
+            g[i][j] = (k2 < C && c2 < K) ? ld_f<T>(G + ((size_t)c2 * C + k2) * 9 + (2 - i) * 3 + (2 - j)) : 0.0f;
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+        float col[3] = {g[0][j], g[1][j], g[2][j]}, o[A];
+        g_mul<M>(col, o);
+#pragma unroll
+        for (int i = 0; i < A; ++i) t[i][j] = o[i];
+    }
+#pragma unroll
+    for (int i = 0; i < A; ++i) g_mul<M>(t[i], u[i]);
+#pragma unroll
+    for (int xi = 0; xi < A; ++xi)
+#pragma unroll
+        for (int nu = 0; nu < A; ++nu) {
+            const int e = xi * A + nu;
+            if constexpr (sizeof(T) == 4) {
+                U[((size_t)e * Cp2 + c2) * Kp2 + k2] = u[xi][nu];
+            } else {
+                U[(((size_t)e * (Cp2 / 8) + c2 / 8) * Kp2 + k2) * 8 + (c2 % 8)] = __float2half_rn(u[xi][nu]);
+            }
+        }
+}
+
+// `g` describes the swapped layer (g.K = channels of the forward layer, g.C = its filters).
+hipError_t launch_filter_transform_bwd(const Geo &g, const void *G, void *U, hipStream_t s)
+{
+    dim3 grid((g.Kp + 63) / 64, (g.Cp + 3) / 4), block(256);
+    const int K = g.C, C = g.K;   // extents of G[K][C][3][3]
+    if (g.dt == WINO_F32) {
+        if (g.m == 2)
+            filter_transform_bwd_kernel<2, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, K, C, g.Kp, g.Cp);
+        else
+            filter_transform_bwd_kernel<4, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, K, C, g.Kp, g.Cp);
+    } else {
+        if (g.m == 2)
+            filter_transform_bwd_kernel<2, __half><<<grid, block, 0, s>>>((const __half *)G, (__half *)U, K, C, g.Kp, g.Cp);
+        else
+            filter_transform_bwd_kernel<4, __half><<<grid, block, 0, s>>>((const __half *)G, (__half *)U, K, C, g.Kp, g.Cp);
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_filter_transform(const Geo &g, const void *G, void *U, hipStream_t s)
 {
     dim3 grid((g.Kp + 63) / 64, (g.Cp + 3) / 4), block(256);

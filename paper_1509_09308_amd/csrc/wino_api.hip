@@ -237,13 +237,11 @@ int wino_conv2d_variant(int N, int C, int H, int W, int K, int pad, int m, int d
     return WINO_FLAG_UNFUSED;
 }
 
-int wino_conv2d_fwd_ex(int N, int C, int H, int W, int K, int pad, int m, int dt, int y_dt, const void *D,
-                       const void *G, const void *U, void *Y, void *workspace, size_t workspace_bytes, unsigned flags,
-                       void *stream)
+// Shared driver of the forward layer and of the input gradient: `g` is the geometry the kernels see,
+// `bwd` selects the filter transform (plain, or rotated and transposed).
+static int run_layer(const Geo &g, int y_dt, const void *D, const void *G, const void *U, void *Y, void *workspace,
+                     size_t workspace_bytes, unsigned flags, bool bwd, hipStream_t s)
 {
-    Geo g;
-    const int st = make_geo(N, C, H, W, K, pad, m, dt, &g);
-    if (st != WINO_OK) return st;
     if (bad_dtype(y_dt)) return WINO_EINVAL;
     if (flags > WINO_FLAG_FUSED) return WINO_EINVAL;
     if (flags == WINO_FLAG_FUSED && (!fused_eligible(g) || y_dt != WINO_F32)) return WINO_EUNSUPPORTED;
@@ -255,10 +253,10 @@ int wino_conv2d_fwd_ex(int N, int C, int H, int W, int K, int pad, int m, int dt
     char *ws = (char *)workspace;
     void *Uw = ws, *Vw = ws + ub;
     float *Mw = (float *)(ws + ub + vb);
-    hipStream_t s = (hipStream_t)stream;
     hipError_t e;
     if (U == nullptr) {
-        if ((e = launch_filter_transform(g, G, Uw, s)) != hipSuccess) return hip_fail(e);
+        e = bwd ? launch_filter_transform_bwd(g, G, Uw, s) : launch_filter_transform(g, G, Uw, s);
+        if (e != hipSuccess) return hip_fail(e);
         U = Uw;
     }
     if (flags == WINO_FLAG_AUTO && y_dt == WINO_F32 && fused_preferred(g)) flags = WINO_FLAG_FUSED;
@@ -271,6 +269,37 @@ int wino_conv2d_fwd_ex(int N, int C, int H, int W, int K, int pad, int m, int dt
         return e == hipErrorNotSupported ? (int)WINO_EUNSUPPORTED : hip_fail(e);
     if ((e = launch_output_transform(g, y_dt, Mw, Y, splits, s)) != hipSuccess) return hip_fail(e);
     return WINO_OK;
+}
+
+int wino_conv2d_fwd_ex(int N, int C, int H, int W, int K, int pad, int m, int dt, int y_dt, const void *D,
+                       const void *G, const void *U, void *Y, void *workspace, size_t workspace_bytes, unsigned flags,
+                       void *stream)
+{
+    Geo g;
+    const int st = make_geo(N, C, H, W, K, pad, m, dt, &g);
+    if (st != WINO_OK) return st;
+    return run_layer(g, y_dt, D, G, U, Y, workspace, workspace_bytes, flags, false, (hipStream_t)stream);
+}
+
+int wino_filter_transform_bwd(int K, int C, int m, int dt, const void *G, void *U, void *stream)
+{
+    Geo g;
+    const int st = make_geo_kcp(C, K, 1, m, dt, &g);   // the swapped layer: C "filters", K "channels"
+    if (st != WINO_OK) return st;
+    if (bad_ptr(G) || bad_ptr(U)) return WINO_EINVAL;
+    const hipError_t e = launch_filter_transform_bwd(g, G, U, (hipStream_t)stream);
+    return e == hipSuccess ? WINO_OK : hip_fail(e);
+}
+
+int wino_conv2d_bwd_data(int N, int C, int H, int W, int K, int pad, int m, int dt, int d_dt, const void *E,
+                         const void *G, const void *U, void *dD, void *workspace, size_t workspace_bytes,
+                         unsigned flags, void *stream)
+{
+    if (pad != 1) return (pad == 0) ? WINO_EUNSUPPORTED : WINO_EUNSUPPORTED;   // pad 0 would need pad 2 here
+    Geo g;
+    const int st = make_geo(N, K, H, W, C, 1, m, dt, &g);   // error tensor in, K channels; C outputs
+    if (st != WINO_OK) return st;
+    return run_layer(g, d_dt, E, G, U, dD, workspace, workspace_bytes, flags, true, (hipStream_t)stream);
 }
 
 int wino_conv2d_fwd(int N, int C, int H, int W, int K, int pad, int m, const void *D, const void *G, void *Y,

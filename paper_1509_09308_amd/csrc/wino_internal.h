@@ -28,6 +28,7 @@ inline int pad_p(long long P) { return round_up(P, 32); }
 
 // Kernel launchers (each enqueues on `s` and returns the launch status).
 hipError_t launch_filter_transform(const Geo &g, const void *G, void *U, hipStream_t s);
+hipError_t launch_filter_transform_bwd(const Geo &g, const void *G, void *U, hipStream_t s);
 hipError_t launch_input_transform(const Geo &g, const void *D, void *V, hipStream_t s);
 int gemm_splits(const Geo &g);
 hipError_t launch_batched_gemm(const Geo &g, const void *U, const void *V, float *M, int splits, hipStream_t s);

@@ -1,0 +1,107 @@
+"""GPU parity of the input gradient (Section 4.2 of the paper: the forward algorithm on the error
+tensor with rotated, transposed filters) against the fp64 oracle written from Eq. (1)."""
+import numpy as np
+import pytest
+
+from oracle import direct
+from oracle import winograd as wg
+from paper_1509_09308_amd import synth
+from gpu_util import TOL, require_gpu, rel_err, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("K,C", [(32, 32), (70, 19), (5, 3), (128, 256)])
+def test_filter_transform_bwd(m, K, C):
+    """U' must be the forward transform of the filters rotated by 180 degrees with K and C exchanged."""
+    torch, w = require_gpu()
+    rng = np.random.default_rng(K + 3 * C + m)
+    G = (rng.integers(-8, 9, (K, C, 3, 3)) * 4).astype(np.float32)
+    U = w.wino_filter_transform_bwd(to_gpu(G), m)
+    torch.cuda.synchronize()
+    Gf = np.ascontiguousarray(G[:, :, ::-1, ::-1].transpose(1, 0, 2, 3))      # [C, K, 3, 3]
+    ref = wg.filter_transform(Gf, m)                                           # [a, a, C, K]
+    got = w.unpack_u(U, C, K, m)
+    if m == 2:
+        assert np.array_equal(got.astype(np.float64), ref)
+    else:
+        assert np.abs(got - ref).max() <= 4e-7 * np.abs(ref).max()
+    full = w.unpack_u(U, C, K, m, padded=True)
+    assert not full[:, :, C:, :].any() and not full[:, :, :, K:].any()
+
+
+@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("shape", [(2, 16, 12, 12, 24), (1, 19, 13, 29, 70), (3, 33, 14, 14, 65), (1, 3, 9, 9, 8),
+                                   (2, 64, 28, 28, 128)])
+def test_bwd_data_matches_oracle(m, shape):
+    torch, w = require_gpu()
+    N, C, H, W, K = shape
+    rng = np.random.default_rng(sum(shape) + m)
+    E = rng.standard_normal((N, K, H, W), dtype=np.float32)
+    _, G = synth.make_layer(1, C, 4, 4, K, seed=sum(shape))
+    ref = direct.conv2d_bwd_data(E, G, H, W, pad=1)
+    e, g = to_gpu(E), to_gpu(G)
+    for flags in ([w.FLAG_UNFUSED, w.FLAG_FUSED] if m == 4 else [w.FLAG_UNFUSED]):
+        dD = w.wino_conv2d_bwd_data(e, G=g, pad=1, m=m, flags=flags).cpu().numpy()
+        assert dD.shape == ref.shape
+        err = rel_err(dD, ref)
+        print("bwd %s m=%d flags=%d rel err %.3e" % (shape, m, flags, err))
+        assert err <= TOL[("f32", m)]
+    # pre-transformed filters give the same result
+    U = w.wino_filter_transform_bwd(g, m)
+    dD2 = w.wino_conv2d_bwd_data(e, U=U, C=C, pad=1, m=m, flags=w.FLAG_UNFUSED).cpu().numpy()
+    assert rel_err(dD2, ref) <= TOL[("f32", m)]
+
+
+def test_bwd_data_adjoint_identity_on_gpu_results():
+    """<fwd(D, G), E> == <D, bwd(E, G)> with both sides computed by the library (exact data)."""
+    torch, w = require_gpu()
+    D, G = synth.make_integer_layer(2, 8, 16, 20, 12, seed=21, gscale=4.0)
+    E = np.random.default_rng(22).integers(-6, 7, (2, 12, 16, 20)).astype(np.float32)
+    Y = w.wino_conv2d_fwd_ex(to_gpu(D), G=to_gpu(G), pad=1, m=2).cpu().numpy().astype(np.float64)
+    dD = w.wino_conv2d_bwd_data(to_gpu(E), G=to_gpu(G), pad=1, m=2).cpu().numpy().astype(np.float64)
+    assert float((Y * E).sum()) == float((D * dD).sum())     # F(2x2) is exact on these integers
+
+
+def test_bwd_data_f16_storage():
+    torch, w = require_gpu()
+    N, C, H, W, K = 2, 48, 28, 28, 64
+    rng = np.random.default_rng(5)
+    E = rng.standard_normal((N, K, H, W), dtype=np.float32).astype(np.float16)
+    _, G = synth.make_layer(1, C, 4, 4, K, seed=6, dtype=np.float16)
+    ref = direct.conv2d_bwd_data(E, G, H, W, pad=1)
+    for m in (2, 4):
+        dD = w.wino_conv2d_bwd_data(to_gpu(E), G=to_gpu(G), pad=1, m=m).cpu().numpy()
+        assert rel_err(dD, ref) <= TOL[("f16", m)]
+
+
+def test_bwd_data_rejects_pad0():
+    torch, w = require_gpu()
+    E = torch.zeros((1, 8, 6, 6), device="cuda")
+    G = torch.zeros((8, 8, 3, 3), device="cuda")
+    with pytest.raises(w.WinoError) as ei:
+        w.wino_conv2d_bwd_data(E, G=G, pad=0, m=2)
+    assert ei.value.status == w.WINO_EUNSUPPORTED
+
+
+@pytest.mark.parametrize("layer", [2, 5, 9])
+def test_bwd_data_full_size_sampled(layer):
+    """VGG-16 shapes at N=64, fp32, F(4x4,3x3): sampled elements of dD recomputed by the oracle."""
+    torch, w = require_gpu()
+    name, C, HW, K = synth.VGG16_LAYERS[layer]
+    N, m = 64, 4
+    rng = np.random.default_rng(synth.layer_seed(6, layer))
+    E = rng.standard_normal((N, K, HW, HW), dtype=np.float32)
+    _, G = synth.make_layer(1, C, 4, 4, K, seed=synth.layer_seed(6, layer) + 1)
+    e, g = to_gpu(E), to_gpu(G)
+    ws = w.alloc_workspace(N, K, HW, HW, C, 1, m)
+    dD = w.wino_conv2d_bwd_data(e, G=g, pad=1, m=m, workspace=ws)
+    pts = synth.sample_points((N, C, HW, HW), 3000, seed=layer)
+    idx = torch.from_numpy(pts.astype(np.int64)).cuda()
+    got = dD[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy()
+    ref = direct.conv2d_bwd_data_points(E, G, HW, HW, pts, pad=1)
+    err = rel_err(got, ref)
+    print("%s N=64 bwd-data sampled rel err %.3e" % (name, err))
+    assert err <= TOL[("f32", 4)]
+    assert bool(torch.isfinite(dD).all())
