@@ -34,9 +34,10 @@ def _load():
         lib.oracle_conv2d_points_f32in.argtypes = [i] * 9 + [p, p, l, p, p]
         lib.oracle_conv2d_bwd_data_f64.argtypes = [i] * 9 + [p, p, p]
         lib.oracle_conv2d_bwd_data_points_f32in.argtypes = [i] * 9 + [p, p, l, p, p]
+        lib.oracle_conv2d_bwd_filter_f64.argtypes = [i] * 9 + [p, p, p]
         for f in (lib.oracle_conv2d_fwd_f64, lib.oracle_conv2d_fwd_f32in,
                   lib.oracle_conv2d_points_f32in, lib.oracle_conv2d_bwd_data_f64,
-                  lib.oracle_conv2d_bwd_data_points_f32in):
+                  lib.oracle_conv2d_bwd_data_points_f32in, lib.oracle_conv2d_bwd_filter_f64):
             f.restype = None
         _lib = lib
     return _lib
@@ -128,3 +129,18 @@ def conv2d_bwd_data_points(E, G, H, W, pts, pad=1, stride=1):
     _load().oracle_conv2d_bwd_data_points_f32in(N, C, H, W, K, R, S, pad, stride, E.ctypes.data, G.ctypes.data,
                                                 len(pts), pts.ctypes.data, out.ctypes.data)
     return out
+
+
+def conv2d_bwd_filter(D, E, R=3, S=3, pad=1, stride=1):
+    """Gradient of the layer with respect to its filters: D[N,C,H,W], E[N,K,Ho,Wo] -> dG[K,C,R,S] (fp64)."""
+    D = np.ascontiguousarray(np.asarray(D), dtype=np.float64)
+    E = np.ascontiguousarray(np.asarray(E), dtype=np.float64)
+    N, C, H, W = D.shape
+    K = E.shape[1]
+    Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    if E.shape[0] != N or E.shape[2:] != (Ho, Wo):
+        raise ValueError("error tensor does not match the layer geometry")
+    dG = np.empty((K, C, R, S), dtype=np.float64)
+    _load().oracle_conv2d_bwd_filter_f64(N, C, H, W, K, R, S, pad, stride, D.ctypes.data, E.ctypes.data,
+                                         dG.ctypes.data)
+    return dG

@@ -171,3 +171,30 @@ void oracle_conv2d_bwd_data_points_f32in(int N, int C, int H, int W, int K, int 
         out[j] = acc;
     }
 }
+
+/* Gradient of Eq. (1) with respect to the filters (Section 4.2, second paragraph: a convolution of
+ * the layer inputs with the backpropagated errors, R x S outputs per filter and channel).  From
+ * Eq. (1): Y[i][k][x][y] contains D[i][c][x*stride+u-pad][y*stride+v-pad] * G[k][c][u][v], so
+ *   dG[k][c][u][v] = sum_i sum_x sum_y D[i][c][x*stride+u-pad][y*stride+v-pad] * E[i][k][x][y]
+ * with out-of-image taps contributing zero.  Inputs widened to double by the caller. */
+void oracle_conv2d_bwd_filter_f64(int N, int C, int H, int W, int K, int R, int S, int pad, int stride,
+                                  const double *D, const double *E, double *dG)
+{
+    const int Ho = out_extent(H, pad, R, stride), Wo = out_extent(W, pad, S, stride);
+    #pragma omp parallel for collapse(2) schedule(static)
+    for (int k = 0; k < K; ++k)
+        for (int c = 0; c < C; ++c)
+            for (int u = 0; u < R; ++u)
+                for (int v = 0; v < S; ++v) {
+                    double acc = 0.0;
+                    for (int i = 0; i < N; ++i)
+                        for (int x = 0; x < Ho; ++x)
+                            for (int y = 0; y < Wo; ++y) {
+                                const int xx = x * stride + u - pad, yy = y * stride + v - pad;
+                                if (xx >= 0 && xx < H && yy >= 0 && yy < W)
+                                    acc += D[(((size_t)i * C + c) * H + xx) * W + yy] *
+                                           E[(((size_t)i * K + k) * Ho + x) * Wo + y];
+                            }
+                    dG[(((size_t)k * C + c) * R + u) * S + v] = acc;
+                }
+}

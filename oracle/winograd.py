@@ -222,3 +222,74 @@ def conv2d_fwd(D4, G4, pad, m):
     V = data_transform(D4, pad, m)
     M = multiply(U, V)
     return inverse_transform(M, N, H, W, pad, m), U, V, M
+
+
+# ---- weight gradient with F(3x3, 2x2) (Section 4.2, Eq. (14)), loop by loop, float64 ---------------
+#
+# The error tensor is cut into 2 x 2 blocks e_{k,b}; block (bx, by) of image i pairs with the
+# 4 x 4 input tile whose origin is (2*bx - pad, 2*by - pad) (tiles overlap by 2).  Each pair
+# yields the 3 x 3 correlation of the tile with the block; the filter gradient is their sum
+# over all blocks and images.  In transform space: w = G e G^T, v = B^T d B, M = sum_b w . v,
+# dG = A^T M A, with the matrices of Eq. (14).  Readings where the paper is silent: blocks per
+# image are ceil(H/2) x ceil(W/2); block index b = (i*Bh + bx)*Bw + by; error entries and
+# input taps outside the tensors are zero.
+
+def wgrad_block_counts(H, W):
+    return -(-H // 2), -(-W // 2)
+
+
+def wgrad_error_transform(E4):
+    """W[xi,nu,k,b] = (G e_{k,b} G^T)[xi,nu] for every 2 x 2 block of the error tensor."""
+    _, Gm, _ = matrices_f64(3, 2)
+    E = np.asarray(E4, dtype=np.float64)
+    N, K, H, W = E.shape
+    Bh, Bw = wgrad_block_counts(H, W)
+    Ep = np.zeros((N, K, 2 * Bh, 2 * Bw))
+    Ep[:, :, :H, :W] = E
+    blocks = Ep.reshape(N, K, Bh, 2, Bw, 2).transpose(1, 0, 2, 4, 3, 5).reshape(K, N * Bh * Bw, 2, 2)
+    w = np.einsum("ai,kbij,ej->kbae", Gm, blocks, Gm)
+    return np.ascontiguousarray(w.transpose(2, 3, 0, 1))
+
+
+def wgrad_data_transform(D4, pad=1):
+    """V[xi,nu,c,b] = (B^T d_{c,b} B)[xi,nu] for the 4 x 4 input tile of every error block."""
+    BT, _, _ = matrices_f64(3, 2)
+    D = np.asarray(D4, dtype=np.float64)
+    N, C, H, W = D.shape
+    Bh, Bw = wgrad_block_counts(H + 2 * pad - 2, W + 2 * pad - 2)
+    tiles = np.zeros((C, N * Bh * Bw, 4, 4))
+    for i in range(N):
+        for bx in range(Bh):
+            for by in range(Bw):
+                b = (i * Bh + bx) * Bw + by
+                for p in range(4):
+                    for q in range(4):
+                        x, y = 2 * bx - pad + p, 2 * by - pad + q
+                        if 0 <= x < H and 0 <= y < W:
+                            tiles[:, b, p, q] = D[i, :, x, y]
+    v = np.einsum("ai,cbij,ej->cbae", BT, tiles, BT)
+    return np.ascontiguousarray(v.transpose(2, 3, 0, 1))
+
+
+def wgrad_multiply(Wt, V):
+    """M^(xi,nu) = W^(xi,nu) (V^(xi,nu))^T: K x P by P x C, the reduction runs over blocks and images."""
+    a = Wt.shape[0]
+    M = np.empty((a, a, Wt.shape[2], V.shape[2]))
+    for xi in range(a):
+        for nu in range(a):
+            M[xi, nu] = Wt[xi, nu] @ V[xi, nu].T
+    return M
+
+
+def wgrad_inverse_transform(M):
+    """dG[k,c] = A^T m_{k,c} A (3 x 3 from 4 x 4)."""
+    _, _, AT = matrices_f64(3, 2)
+    return np.einsum("pa,abkc,qb->kcpq", AT, M, AT)
+
+
+def conv2d_bwd_filter(D4, E4, pad=1):
+    """The whole weight-gradient algorithm; returns dG[K,C,3,3] and the intermediates W, V, M."""
+    Wt = wgrad_error_transform(E4)
+    V = wgrad_data_transform(D4, pad)
+    M = wgrad_multiply(Wt, V)
+    return wgrad_inverse_transform(M), Wt, V, M

@@ -166,3 +166,33 @@ def test_bwd_data_points_equal_full_tensor():
     pts = np.stack([rng.integers(0, n, 100) for n in full.shape], axis=1)
     got = direct.conv2d_bwd_data_points(E, G, 9, 11, pts, pad=1)
     assert np.array_equal(got, full[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]])
+
+
+# ---- gradient with respect to the filters (Section 4.2, second paragraph) -------------------------
+
+@pytest.mark.parametrize("shape", [(2, 3, 7, 9, 4, 3, 3, 1, 1), (1, 2, 8, 8, 3, 3, 3, 0, 1), (2, 3, 9, 8, 2, 3, 3, 1, 2),
+                                   (1, 2, 10, 7, 3, 5, 5, 2, 1)])
+def test_bwd_filter_is_the_adjoint_in_the_filters(shape):
+    """<conv(D, G), E> == <G, bwd_filter(D, E)> exactly on small integers."""
+    N, C, H, W, K, R, S, pad, stride = shape
+    rng = np.random.default_rng(sum(shape) + 7)
+    D = rng.integers(-5, 6, (N, C, H, W)).astype(np.float64)
+    G = rng.integers(-5, 6, (K, C, R, S)).astype(np.float64)
+    Y = direct.conv2d_fwd(D, G, pad=pad, stride=stride)
+    E = rng.integers(-5, 6, Y.shape).astype(np.float64)
+    dG = direct.conv2d_bwd_filter(D, E, R=R, S=S, pad=pad, stride=stride)
+    assert dG.shape == G.shape
+    assert float((Y * E).sum()) == float((G * dG).sum())
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 7, 9, 4, 3, 3, 1, 1), (1, 2, 8, 8, 3, 3, 3, 0, 1), (2, 3, 9, 8, 2, 3, 3, 1, 2)])
+def test_bwd_filter_against_torch_autograd_float64(shape):
+    N, C, H, W, K, R, S, pad, stride = shape
+    rng = np.random.default_rng(sum(shape) + 8)
+    D = torch.from_numpy(rng.standard_normal((N, C, H, W)))
+    G = torch.from_numpy(rng.standard_normal((K, C, R, S))).requires_grad_(True)
+    Y = torch.nn.functional.conv2d(D, G, padding=pad, stride=stride)
+    E = torch.from_numpy(rng.standard_normal(tuple(Y.shape)))
+    Y.backward(E)
+    got = direct.conv2d_bwd_filter(D.numpy(), E.numpy(), R=R, S=S, pad=pad, stride=stride)
+    assert np.abs(got - G.grad.numpy()).max() < 1e-11

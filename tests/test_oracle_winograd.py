@@ -171,3 +171,26 @@ def test_stage_values_against_hand_computed_tile():
     assert wg.filter_transform_tile(2, g) == [[x * y for y in gg] for x in gg]
     # outputs: sum of a 3x3 window of the outer product = (sum rows)(sum cols)
     assert wg.fir_2d(2, 3, d, g)[0] == [[Fr(36), Fr(54)], [Fr(54), Fr(81)]]
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 8, 8, 4), (1, 2, 7, 9, 3), (3, 1, 5, 6, 2), (1, 4, 14, 14, 5)])
+def test_wgrad_f3x3_2x2_matches_direct_oracle(shape):
+    """Section 4.2 / Eq. (14): 4 x 4 tiles overlapped by 2, 3 x 3 outputs summed over all tiles,
+    reproduce the filter gradient of Eq. (1) (odd extents use zero-filled edge blocks)."""
+    N, C, H, W, K = shape
+    rng = np.random.default_rng(sum(shape))
+    D = rng.standard_normal((N, C, H, W))
+    E = rng.standard_normal((N, K, H, W))
+    dG, Wt, V, M = wg.conv2d_bwd_filter(D, E, pad=1)
+    ref = direct.conv2d_bwd_filter(D, E, pad=1)
+    Bh, Bw = wg.wgrad_block_counts(H, W)
+    assert Wt.shape == (4, 4, K, N * Bh * Bw) and V.shape == (4, 4, C, N * Bh * Bw) and M.shape == (4, 4, K, C)
+    assert np.abs(dG - ref).max() <= 1e-12 * max(1.0, np.abs(ref).max())
+
+
+def test_wgrad_exact_on_integers():
+    rng = np.random.default_rng(3)
+    D = rng.integers(-8, 9, (2, 3, 10, 12)).astype(np.float64)
+    E = (rng.integers(-4, 5, (2, 4, 10, 12)) * 4).astype(np.float64)   # G of F(3,2) has halves
+    dG, _, _, _ = wg.conv2d_bwd_filter(D, E, pad=1)
+    assert np.array_equal(dG, direct.conv2d_bwd_filter(D, E, pad=1))
