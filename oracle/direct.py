@@ -35,9 +35,11 @@ def _load():
         lib.oracle_conv2d_bwd_data_f64.argtypes = [i] * 9 + [p, p, p]
         lib.oracle_conv2d_bwd_data_points_f32in.argtypes = [i] * 9 + [p, p, l, p, p]
         lib.oracle_conv2d_bwd_filter_f64.argtypes = [i] * 9 + [p, p, p]
+        lib.oracle_conv2d_bwd_filter_points_f32in.argtypes = [i] * 9 + [p, p, l, p, p]
         for f in (lib.oracle_conv2d_fwd_f64, lib.oracle_conv2d_fwd_f32in,
                   lib.oracle_conv2d_points_f32in, lib.oracle_conv2d_bwd_data_f64,
-                  lib.oracle_conv2d_bwd_data_points_f32in, lib.oracle_conv2d_bwd_filter_f64):
+                  lib.oracle_conv2d_bwd_data_points_f32in, lib.oracle_conv2d_bwd_filter_f64,
+                  lib.oracle_conv2d_bwd_filter_points_f32in):
             f.restype = None
         _lib = lib
     return _lib
@@ -144,3 +146,22 @@ def conv2d_bwd_filter(D, E, R=3, S=3, pad=1, stride=1):
     _load().oracle_conv2d_bwd_filter_f64(N, C, H, W, K, R, S, pad, stride, D.ctypes.data, E.ctypes.data,
                                          dG.ctypes.data)
     return dG
+
+
+def conv2d_bwd_filter_points(D, E, pts, R=3, S=3, pad=1, stride=1):
+    """Selected elements of the filter gradient; ``pts`` is an (n,4) array of (k,c,u,v)."""
+    D = np.ascontiguousarray(D, dtype=np.float32)
+    E = np.ascontiguousarray(E, dtype=np.float32)
+    N, C, H, W = D.shape
+    K = E.shape[1]
+    Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    if E.shape[0] != N or E.shape[2:] != (Ho, Wo):
+        raise ValueError("error tensor does not match the layer geometry")
+    pts = np.ascontiguousarray(pts, dtype=np.int32).reshape(-1, 4)
+    hi = np.array([K, C, R, S])
+    if pts.size and ((pts < 0).any() or (pts >= hi).any()):
+        raise ValueError("sample point outside the gradient tensor")
+    out = np.empty(len(pts), dtype=np.float64)
+    _load().oracle_conv2d_bwd_filter_points_f32in(N, C, H, W, K, R, S, pad, stride, D.ctypes.data, E.ctypes.data,
+                                                  len(pts), pts.ctypes.data, out.ctypes.data)
+    return out

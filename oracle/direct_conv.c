@@ -198,3 +198,29 @@ void oracle_conv2d_bwd_filter_f64(int N, int C, int H, int W, int K, int R, int 
                     dG[(((size_t)k * C + c) * R + u) * S + v] = acc;
                 }
 }
+
+/* Selected elements of the filter gradient above on float inputs widened exactly to double:
+ * pts[j] = (k, c, u, v).  Same sum as oracle_conv2d_bwd_filter_f64, one element at a time. */
+void oracle_conv2d_bwd_filter_points_f32in(int N, int C, int H, int W, int K, int R, int S, int pad, int stride,
+                                           const float *D, const float *E, long npts, const int32_t *pts,
+                                           double *out)
+{
+    const int Ho = out_extent(H, pad, R, stride), Wo = out_extent(W, pad, S, stride);
+    #pragma omp parallel for schedule(dynamic, 1)
+    for (long j = 0; j < npts; ++j) {
+        const int k = pts[4 * j + 0], c = pts[4 * j + 1], u = pts[4 * j + 2], v = pts[4 * j + 3];
+        double acc = 0.0;
+        for (int i = 0; i < N; ++i)
+            for (int x = 0; x < Ho; ++x) {
+                const int xx = x * stride + u - pad;
+                if (xx < 0 || xx >= H) continue;
+                for (int y = 0; y < Wo; ++y) {
+                    const int yy = y * stride + v - pad;
+                    if (yy >= 0 && yy < W)
+                        acc += (double)D[(((size_t)i * C + c) * H + xx) * W + yy] *
+                               (double)E[(((size_t)i * K + k) * Ho + x) * Wo + y];
+                }
+            }
+        out[j] = acc;
+    }
+}

@@ -196,3 +196,19 @@ def test_bwd_filter_against_torch_autograd_float64(shape):
     Y.backward(E)
     got = direct.conv2d_bwd_filter(D.numpy(), E.numpy(), R=R, S=S, pad=pad, stride=stride)
     assert np.abs(got - G.grad.numpy()).max() < 1e-11
+
+
+@pytest.mark.parametrize("pad,stride", [(1, 1), (0, 1), (1, 2)])
+def test_bwd_filter_points_equal_the_full_gradient(pad, stride):
+    """The one-element-at-a-time form must reproduce every element of the full gradient (exact integers)."""
+    rng = np.random.default_rng(77 + pad + stride)
+    N, C, H, W, K = 2, 3, 9, 11, 4
+    D = rng.integers(-5, 6, (N, C, H, W)).astype(np.float32)
+    Ho, Wo = (H + 2 * pad - 3) // stride + 1, (W + 2 * pad - 3) // stride + 1
+    E = rng.integers(-5, 6, (N, K, Ho, Wo)).astype(np.float32)
+    full = direct.conv2d_bwd_filter(D, E, pad=pad, stride=stride)
+    pts = np.array([(k, c, u, v) for k in range(K) for c in range(C) for u in range(3) for v in range(3)])
+    got = direct.conv2d_bwd_filter_points(D, E, pts, pad=pad, stride=stride)
+    assert np.array_equal(got.reshape(K, C, 3, 3), full)
+    with pytest.raises(ValueError):
+        direct.conv2d_bwd_filter_points(D, E, np.array([[K, 0, 0, 0]]), pad=pad, stride=stride)
