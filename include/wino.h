@@ -132,6 +132,16 @@ int wino_conv2d_bwd_data(int N, int C, int H, int W, int K, int pad, int m, int 
                          const void *G, const void *U, void *dD, void *workspace, size_t workspace_bytes,
                          unsigned flags, void *stream);
 
+/* ---- gradient with respect to the filters (Section 4.2, Eq. (14): F(3x3, 2x2)) ---------------
+ * dG[k][c][u][v] = sum_i sum_x sum_y D[i][c][x+u-pad][y+v-pad] * E[i][k][x][y].  The error tensor is
+ * cut into 2 x 2 blocks, each paired with the 4 x 4 input tile around it (tiles overlap by 2);
+ * w = G e G^T, v = B^T d B, M = sum over blocks and images of w . v, dG = A^T M A.
+ * fp32 only, pad = 1, stride 1 (else WINO_EUNSUPPORTED). */
+size_t wino_bwd_filter_workspace_bytes(int N, int C, int H, int W, int K);   /* 0 on bad input */
+/* D[N][C][H][W], E[N][K][H][W] -> dG[K][C][3][3]; overwrites dG; never allocates. */
+int wino_conv2d_bwd_filter(int N, int C, int H, int W, int K, int pad, int dt, const void *D, const void *E, void *dG,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
 /* Host-side query: the variant wino_conv2d_fwd_ex runs for these arguments -- WINO_FLAG_UNFUSED or
  * WINO_FLAG_FUSED -- when called with `flags` (WINO_FLAG_AUTO resolves to one of the two); a negative
  * wino_status_t (e.g. -WINO_EUNSUPPORTED) if the call would be rejected. */

@@ -60,6 +60,8 @@ def lib():
             "wino_conv2d_fwd_ex": (i, [i] * 9 + [p, p, p, p, p, sz, u, p]),
             "wino_conv2d_variant": (i, [i] * 9 + [u]),
             "wino_filter_transform_bwd": (i, [i, i, i, i, p, p, p]),
+            "wino_bwd_filter_workspace_bytes": (sz, [i] * 5),
+            "wino_conv2d_bwd_filter": (i, [i] * 7 + [p, p, p, p, sz, p]),
             "wino_conv2d_bwd_data": (i, [i] * 9 + [p, p, p, p, p, sz, u, p]),
             "direct_conv2d_fwd": (i, [i] * 10 + [p, p, p, p]),
             "wino_shutdown": (i, []),
@@ -76,6 +78,7 @@ EXPORTS = ["wino_status_string", "wino_last_hip_error", "wino_num_tiles", "wino_
            "wino_v_bytes", "wino_m_bytes", "wino_workspace_bytes", "wino_filter_transform",
            "wino_filter_transform_ex", "wino_input_transform", "wino_batched_gemm",
            "wino_output_transform", "wino_conv2d_fwd", "wino_conv2d_fwd_ex", "wino_conv2d_variant", "wino_filter_transform_bwd", "wino_conv2d_bwd_data",
+           "wino_bwd_filter_workspace_bytes", "wino_conv2d_bwd_filter",
            "direct_conv2d_fwd",
            "wino_shutdown"]
 
@@ -378,6 +381,26 @@ def wino_conv2d_bwd_data(E, G=None, U=None, C=None, pad=1, m=4, dD=None, d_dtype
                                       _ptr(workspace), workspace.numel() * workspace.element_size(), flags,
                                       _stream(stream)), "wino_conv2d_bwd_data")
     return dD
+
+
+def wino_bwd_filter_workspace_bytes(N, C, H, W, K):
+    return int(lib().wino_bwd_filter_workspace_bytes(N, C, H, W, K))
+
+
+def wino_conv2d_bwd_filter(D, E, pad=1, dG=None, workspace=None, stream=None):
+    """Filter gradient with F(3x3,2x2): D[N,C,H,W], E[N,K,H,W] -> dG[K,C,3,3] (fp32)."""
+    import torch
+    _dense_cuda(D, "D"), _dense_cuda(E, "E")
+    N, C, H, W = D.shape
+    K = E.shape[1]
+    if dG is None:
+        dG = torch.empty((K, C, 3, 3), dtype=torch.float32, device=D.device)
+    if workspace is None:
+        workspace = torch.empty(wino_bwd_filter_workspace_bytes(N, C, H, W, K), dtype=torch.uint8, device=D.device)
+    _check(lib().wino_conv2d_bwd_filter(N, C, H, W, K, pad, _dt(D), _ptr(D), _ptr(E), _ptr(dG), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream(stream)),
+           "wino_conv2d_bwd_filter")
+    return dG
 
 
 def direct_conv2d_fwd(D, G, pad=1, stride=1, Y=None, stream=None):

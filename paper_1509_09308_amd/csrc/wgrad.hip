@@ -1,0 +1,352 @@
+// Gradient with respect to the filters with F(3x3, 2x2) (Lavin & Gray, Section 4.2, Eq. (14)):
+// the error tensor is cut into 2 x 2 blocks, each paired with the 4 x 4 input tile around it
+// (tiles overlap by 2); in transform space  w = G e G^T,  v = B^T d B,  M = sum over all blocks and
+// images of w . v,  dG = A^T M A.  The sum over blocks is 16 matrix products
+// M^(e)[K x C] = W^(e)[K x Pb] V^(e)[C x Pb]^T whose reduction index is the block index b.
+//
+// Stages, each its own kernel: error transform (E -> W[e][k][b]), data transform (D -> V[e][c][b]),
+// the 16 products on fp32 MFMAs with the reduction split over workgroups, and the inverse
+// transform that also adds the partial products.  fp32, stride 1, pad 1.
+#include "wino_internal.h"
+
+namespace wino {
+
+typedef float floatx16_w __attribute__((ext_vector_type(16)));
+typedef float floatx4_w __attribute__((ext_vector_type(4)));
+typedef float floatx2_w __attribute__((ext_vector_type(2)));
+
+// rows of B^T of F(3,2): (1,0,-1,0) (0,1,1,0) (0,-1,1,0) (0,-1,0,1)
+__device__ __forceinline__ void bt32_mul(const float *d, float *o)
+{
+    o[0] = d[0] - d[2];
+    o[1] = d[1] + d[2];
+    o[2] = d[2] - d[1];
+    o[3] = d[3] - d[1];
+}
+// rows of G of F(3,2): (1,0) (1/2,1/2) (1/2,-1/2) (0,1)
+__device__ __forceinline__ void g32_mul(const float *e, float *o)
+{
+    o[0] = e[0];
+    o[1] = 0.5f * (e[0] + e[1]);
+    o[2] = 0.5f * (e[0] - e[1]);
+    o[3] = e[1];
+}
+// rows of A^T of F(3,2): (1,1,1,0) (0,1,-1,0) (0,1,1,1)
+__device__ __forceinline__ void at32_mul(const float *x, float *o)
+{
+    o[0] = x[0] + x[1] + x[2];
+    o[1] = x[1] - x[2];
+    o[2] = x[1] + x[2] + x[3];
+}
+
+struct WgradGeo {
+    int N, C, H, W, K;
+    int Bh, Bw;       // 2 x 2 error blocks per image
+    int Pb, Pbp;      // blocks in all, padded to the reduction slab
+    int Kp, Cq;       // padded rows of W and V (and extents of M)
+};
+
+// One thread per (row, b), b fastest: row is a filter k (IS_ERR) or a channel c.  Rows and blocks
+// in the padding are written as zeros.
+template <bool IS_ERR>
+__global__ __launch_bounds__(256) void wgrad_transform_kernel(const float *__restrict__ X, float *__restrict__ T,
+                                                              WgradGeo g)
+{
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    const int r = blockIdx.y;
+    const int rows = IS_ERR ? g.K : g.C, rows_p = IS_ERR ? g.Kp : g.Cq;
+    if (b >= g.Pbp) return;
+    float out[4][4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) out[p][q] = 0.0f;
+    if (r < rows && b < g.Pb) {
+        const int by = b % g.Bw;
+        const int t2 = b / g.Bw;
+        const int bx = t2 % g.Bh;
+        const int i = t2 / g.Bh;
+        const float *src = X + ((size_t)i * rows + r) * g.H * g.W;
+        if (IS_ERR) {
+            float e[2][2], t[4][2];
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const int x = 2 * bx + p, y = 2 * by + q;
+                    e[p][q] = (x < g.H && y < g.W) ? src[(size_t)x * g.W + y] : 0.0f;
+                }
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                float col[2] = {e[0][q], e[1][q]}, o[4];
+                g32_mul(col, o);
+#pragma unroll
+                for (int p = 0; p < 4; ++p) t[p][q] = o[p];
+            }
+#pragma unroll
+            for (int p = 0; p < 4; ++p) g32_mul(t[p], out[p]);
+        } else {
+            float d[4][4], t[4][4];
+#pragma unroll
+            for (int p = 0; p < 4; ++p)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int x = 2 * bx - 1 + p, y = 2 * by - 1 + q;
+                    d[p][q] = (x >= 0 && x < g.H && y >= 0 && y < g.W) ? src[(size_t)x * g.W + y] : 0.0f;
+                }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float col[4] = {d[0][q], d[1][q], d[2][q], d[3][q]}, o[4];
+                bt32_mul(col, o);
+#pragma unroll
+                for (int p = 0; p < 4; ++p) t[p][q] = o[p];
+            }
+#pragma unroll
+            for (int p = 0; p < 4; ++p) bt32_mul(t[p], out[p]);
+        }
+    }
+#pragma unroll
+    for (int xi = 0; xi < 4; ++xi)
+#pragma unroll
+        for (int nu = 0; nu < 4; ++nu) T[((size_t)(xi * 4 + nu) * rows_p + r) * g.Pbp + b] = out[xi][nu];
+    (void)rows_p;
+}
+
+// M^(e) = W^(e) V^(e)^T on v_mfma_f32_32x32x2_f32.  Both operands are stored with the reduction
+// index b contiguous.  A BK-deep slab is kept in LDS as [row][BK + 2]; lane (i, h) of an MFMA
+// reads rows i of its tiles at columns 4t + 2h, 4t + 2h + 1 with one 8-byte read and uses them in
+// two consecutive MFMAs (the order of the reduction is free as long as both operands agree).
+// The row stride of 18 floats makes those reads conflict-free.  Two LDS slabs: the next slab's
+// global loads are in flight during the MFMAs of the current one.  The reduction is split over
+// `gridDim` shares z, each writing its own partial M.
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void wgrad_gemm_kernel(const float *__restrict__ Wt, const float *__restrict__ Vt,
+                                                         float *__restrict__ Mo, int Kp, int Cq, int Pbp, int tiles_m,
+                                                         int tiles_n, int nk_split)
+{
+    constexpr int BK = 16, LS = BK + 2;
+    constexpr int TM = BM / 64, TN = BN / 64;
+    constexpr int A4 = BM * BK / 4, B4 = BN * BK / 4;
+    static_assert(A4 % 256 == 0 && B4 % 256 == 0, "slab must divide evenly among the threads");
+    constexpr int AL = A4 / 256, BL = B4 / 256;
+    __shared__ float As[2][BM * LS];
+    __shared__ float Bs[2][BN * LS];
+
+    int bid = blockIdx.x;
+    const int tm_i = bid % tiles_m;
+    bid /= tiles_m;
+    const int tn_i = bid % tiles_n;
+    bid /= tiles_n;
+    const int e = bid % 16;
+    const int z = bid / 16;
+    const int k0 = tm_i * BM, c0 = tn_i * BN;
+    const int b_first = z * nk_split * BK;
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int li = lane & 31, lh = lane >> 5;
+
+    const float *pa[AL], *pb[BL];
+    int sa[AL], sb[BL];
+#pragma unroll
+    for (int j = 0; j < AL; ++j) {
+        const int idx = tid + j * 256;
+        const int row = idx / (BK / 4), q = idx % (BK / 4);
+        pa[j] = Wt + ((size_t)e * Kp + min(k0 + row, Kp - 1)) * Pbp + b_first + 4 * q;
+        sa[j] = row * LS + 4 * q;
+    }
+#pragma unroll
+    for (int j = 0; j < BL; ++j) {
+        const int idx = tid + j * 256;
+        const int row = idx / (BK / 4), q = idx % (BK / 4);
+        pb[j] = Vt + ((size_t)e * Cq + min(c0 + row, Cq - 1)) * Pbp + b_first + 4 * q;
+        sb[j] = row * LS + 4 * q;
+    }
+    floatx4_w ra[AL], rb[BL];
+    auto load_global = [&]() {
+#pragma unroll
+        for (int j = 0; j < AL; ++j) {
+            ra[j] = *reinterpret_cast<const floatx4_w *>(pa[j]);
+            pa[j] += BK;
+        }
+#pragma unroll
+        for (int j = 0; j < BL; ++j) {
+            rb[j] = *reinterpret_cast<const floatx4_w *>(pb[j]);
+            pb[j] += BK;
+        }
+    };
+    auto store_lds = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < AL; ++j) {
+            *reinterpret_cast<floatx2_w *>(&As[buf][sa[j]]) = floatx2_w{ra[j][0], ra[j][1]};
+            *reinterpret_cast<floatx2_w *>(&As[buf][sa[j] + 2]) = floatx2_w{ra[j][2], ra[j][3]};
+        }
+#pragma unroll
+        for (int j = 0; j < BL; ++j) {
+            *reinterpret_cast<floatx2_w *>(&Bs[buf][sb[j]]) = floatx2_w{rb[j][0], rb[j][1]};
+            *reinterpret_cast<floatx2_w *>(&Bs[buf][sb[j] + 2]) = floatx2_w{rb[j][2], rb[j][3]};
+        }
+    };
+
+    floatx16_w acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int a_off = (wm * (TM * 32) + li) * LS + 2 * lh, b_off = (wn * (TN * 32) + li) * LS + 2 * lh;
+    auto compute = [&](int buf) {
+#pragma unroll
+        for (int t = 0; t < BK / 4; ++t) {
+            floatx2_w a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const floatx2_w *>(&As[buf][a_off + i * 32 * LS + 4 * t]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const floatx2_w *>(&Bs[buf][b_off + j * 32 * LS + 4 * t]);
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][s], b[j][s], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    const int nk = min(nk_split, Pbp / BK - z * nk_split);   // >= 1 by construction of the launch
+    load_global();
+    store_lds(0);
+    __syncthreads();
+    for (int kt = 0; kt + 1 < nk; ++kt) {
+        const int cur = kt & 1;
+        load_global();
+        compute(cur);
+        store_lds(cur ^ 1);
+        __syncthreads();
+    }
+    compute((nk - 1) & 1);
+
+    float *Me = Mo + ((size_t)z * 16 + e) * Kp * Cq;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int ct = c0 + wn * (TN * 32) + j * 32, rt = k0 + wm * (TM * 32) + i * 32;
+            if (ct < Cq && rt < Kp) {
+                float *dst = Me + (size_t)(rt + 4 * lh) * Cq + ct + li;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) dst[(size_t)(8 * (r / 4) + (r % 4)) * Cq] = acc[i][j][r];
+            }
+        }
+}
+
+// dG[k][c] = A^T (sum over shares of M[e][k][c]) A; one thread per (k, c), c fastest.
+__global__ __launch_bounds__(256) void wgrad_output_kernel(const float *__restrict__ Mi, float *__restrict__ dG,
+                                                           WgradGeo g, int shares)
+{
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    const int k = blockIdx.y;
+    if (c >= g.C) return;
+    float m[4][4];
+#pragma unroll
+    for (int xi = 0; xi < 4; ++xi)
+#pragma unroll
+        for (int nu = 0; nu < 4; ++nu) m[xi][nu] = 0.0f;
+    const size_t plane = (size_t)g.Kp * g.Cq;
+    for (int z = 0; z < shares; ++z)
+#pragma unroll
+        for (int xi = 0; xi < 4; ++xi)
+#pragma unroll
+            for (int nu = 0; nu < 4; ++nu) m[xi][nu] += Mi[((size_t)z * 16 + xi * 4 + nu) * plane + (size_t)k * g.Cq + c];
+    float t[3][4], y[3][3];
+#pragma unroll
+    for (int nu = 0; nu < 4; ++nu) {
+        float col[4] = {m[0][nu], m[1][nu], m[2][nu], m[3][nu]}, o[3];
+        at32_mul(col, o);
+#pragma unroll
+        for (int p = 0; p < 3; ++p) t[p][nu] = o[p];
+    }
+#pragma unroll
+    for (int p = 0; p < 3; ++p) at32_mul(t[p], y[p]);
+    float *dst = dG + ((size_t)k * g.C + c) * 9;
+#pragma unroll
+    for (int p = 0; p < 3; ++p)
+#pragma unroll
+        for (int q = 0; q < 3; ++q) dst[p * 3 + q] = y[p][q];
+}
+
+static WgradGeo make_wgeo(int N, int C, int H, int W, int K)
+{
+    WgradGeo g;
+    g.N = N; g.C = C; g.H = H; g.W = W; g.K = K;
+    g.Bh = (H + 1) / 2; g.Bw = (W + 1) / 2;
+    g.Pb = N * g.Bh * g.Bw;
+    g.Pbp = round_up(g.Pb, 16);
+    g.Kp = round_up(K, 32);
+    g.Cq = round_up(C, 32);
+    return g;
+}
+
+static void wgrad_shape(const WgradGeo &g, int *bm, int *bn, int *shares, int *nk_split)
+{
+    *bm = g.Kp >= 128 ? 128 : 64;
+    *bn = g.Cq >= 128 ? 128 : 64;
+    const long long blocks = (long long)((g.Kp + *bm - 1) / *bm) * ((g.Cq + *bn - 1) / *bn) * 16;
+    const int nk = g.Pbp / 16;
+    int want = (int)((768 + blocks - 1) / blocks);   // about three blocks per CU in all
+    if (want > 256) want = 256;
+    if (want > nk / 8) want = nk / 8 > 0 ? nk / 8 : 1;   // at least 8 slabs per share
+    if (want < 1) want = 1;
+    *nk_split = (nk + want - 1) / want;
+    *shares = (nk + *nk_split - 1) / *nk_split;
+}
+
+bool wgrad_supported(long long N, long long C, long long H, long long W, long long K)
+{
+    const long long Pb = N * ((H + 1) / 2) * ((W + 1) / 2);
+    return Pb < (1LL << 30) && C <= 65000 && K <= 65000;
+}
+
+size_t wgrad_workspace_bytes(int N, int C, int H, int W, int K)
+{
+    const WgradGeo g = make_wgeo(N, C, H, W, K);
+    int bm, bn, shares, nk_split;
+    wgrad_shape(g, &bm, &bn, &shares, &nk_split);
+    auto al = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    return al((size_t)16 * g.Kp * g.Pbp * 4) + al((size_t)16 * g.Cq * g.Pbp * 4) + al((size_t)shares * 16 * g.Kp * g.Cq * 4);
+}
+
+hipError_t launch_wgrad(int N, int C, int H, int W, int K, const float *D, const float *E, float *dG, void *workspace,
+                        hipStream_t s)
+{
+    const WgradGeo g = make_wgeo(N, C, H, W, K);
+    int bm, bn, shares, nk_split;
+    wgrad_shape(g, &bm, &bn, &shares, &nk_split);
+    auto al = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    char *ws = (char *)workspace;
+    float *Wt = (float *)ws;
+    float *Vt = (float *)(ws + al((size_t)16 * g.Kp * g.Pbp * 4));
+    float *Mw = (float *)(ws + al((size_t)16 * g.Kp * g.Pbp * 4) + al((size_t)16 * g.Cq * g.Pbp * 4));
+    dim3 block(256);
+    wgrad_transform_kernel<true><<<dim3((g.Pbp + 255) / 256, g.Kp), block, 0, s>>>(E, Wt, g);
+    wgrad_transform_kernel<false><<<dim3((g.Pbp + 255) / 256, g.Cq), block, 0, s>>>(D, Vt, g);
+    const int tiles_m = (g.Kp + bm - 1) / bm, tiles_n = (g.Cq + bn - 1) / bn;
+    const long long blocks = (long long)tiles_m * tiles_n * 16 * shares;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)blocks);
+    if (bm == 128 && bn == 128)
+        wgrad_gemm_kernel<128, 128><<<grid, block, 0, s>>>(Wt, Vt, Mw, g.Kp, g.Cq, g.Pbp, tiles_m, tiles_n, nk_split);
+    else if (bm == 128)
+        wgrad_gemm_kernel<128, 64><<<grid, block, 0, s>>>(Wt, Vt, Mw, g.Kp, g.Cq, g.Pbp, tiles_m, tiles_n, nk_split);
+    else if (bn == 128)
+        wgrad_gemm_kernel<64, 128><<<grid, block, 0, s>>>(Wt, Vt, Mw, g.Kp, g.Cq, g.Pbp, tiles_m, tiles_n, nk_split);
+    else
+        wgrad_gemm_kernel<64, 64><<<grid, block, 0, s>>>(Wt, Vt, Mw, g.Kp, g.Cq, g.Pbp, tiles_m, tiles_n, nk_split);
+    wgrad_output_kernel<<<dim3((C + 255) / 256, K), block, 0, s>>>(Mw, dG, g, shares);
+    return hipGetLastError();
+}
+
+}  // namespace wino

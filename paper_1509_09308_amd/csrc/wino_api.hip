@@ -302,6 +302,25 @@ int wino_conv2d_bwd_data(int N, int C, int H, int W, int K, int pad, int m, int 
     return run_layer(g, d_dt, E, G, U, dD, workspace, workspace_bytes, flags, true, (hipStream_t)stream);
 }
 
+size_t wino_bwd_filter_workspace_bytes(int N, int C, int H, int W, int K)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0 || !wgrad_supported(N, C, H, W, K)) return 0;
+    return wgrad_workspace_bytes(N, C, H, W, K);
+}
+
+int wino_conv2d_bwd_filter(int N, int C, int H, int W, int K, int pad, int dt, const void *D, const void *E, void *dG,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0) return WINO_EINVAL;
+    if (bad_dtype(dt)) return WINO_EINVAL;
+    if (dt != WINO_F32 || pad != 1 || !wgrad_supported(N, C, H, W, K)) return WINO_EUNSUPPORTED;
+    if (bad_ptr(D) || bad_ptr(E) || bad_ptr(dG) || bad_ptr(workspace)) return WINO_EINVAL;
+    if (workspace_bytes < wgrad_workspace_bytes(N, C, H, W, K)) return WINO_EWORKSPACE;
+    const hipError_t e = launch_wgrad(N, C, H, W, K, (const float *)D, (const float *)E, (float *)dG, workspace,
+                                      (hipStream_t)stream);
+    return e == hipSuccess ? WINO_OK : hip_fail(e);
+}
+
 int wino_conv2d_fwd(int N, int C, int H, int W, int K, int pad, int m, const void *D, const void *G, void *Y,
                     void *stream)
 {

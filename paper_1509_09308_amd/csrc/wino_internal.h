@@ -36,6 +36,10 @@ hipError_t launch_output_transform(const Geo &g, int y_dt, const float *M, void 
 bool fused_eligible(const Geo &g);
 bool fused_preferred(const Geo &g);
 hipError_t launch_fused(const Geo &g, const float *D, const float *U, float *Y, hipStream_t s);
+bool wgrad_supported(long long N, long long C, long long H, long long W, long long K);
+size_t wgrad_workspace_bytes(int N, int C, int H, int W, int K);
+hipError_t launch_wgrad(int N, int C, int H, int W, int K, const float *D, const float *E, float *dG, void *workspace,
+                        hipStream_t s);
 hipError_t launch_direct_conv(int N, int C, int H, int W, int K, int R, int S, int pad, int stride, int dt,
                               const void *D, const void *G, void *Y, hipStream_t s);
 

@@ -68,6 +68,16 @@ def test_argument_validation_without_gpu(L):
                                 null) == w.WINO_EINVAL
     assert L.wino_conv2d_fwd_ex(1, 4, 8, 8, 4, 1, 2, 0, 0, fake, fake, null, fake, fake, need, 99,
                                 null) == w.WINO_EINVAL
+    # filter gradient: fp32 and pad 1 only, workspace and pointers checked
+    need = L.wino_bwd_filter_workspace_bytes(2, 4, 8, 8, 4)
+    assert need >= 16 * 32 * 32 * 4 * 3          # W, V (Pb = 32 blocks, 32 padded rows) and one M
+    assert L.wino_conv2d_bwd_filter(2, 4, 8, 8, 4, 1, 0, fake, fake, fake, fake, need - 1, null) == w.WINO_EWORKSPACE
+    assert L.wino_conv2d_bwd_filter(2, 4, 8, 8, 4, 0, 0, fake, fake, fake, fake, need, null) == w.WINO_EUNSUPPORTED
+    assert L.wino_conv2d_bwd_filter(2, 4, 8, 8, 4, 1, 1, fake, fake, fake, fake, need, null) == w.WINO_EUNSUPPORTED
+    assert L.wino_conv2d_bwd_filter(2, 4, 8, 8, 4, 1, 0, fake, null, fake, fake, need, null) == w.WINO_EINVAL
+    assert L.wino_conv2d_bwd_filter(2, 4, 8, 8, 4, 1, 0, fake, fake, odd, fake, need, null) == w.WINO_EINVAL
+    assert L.wino_conv2d_bwd_filter(2, 0, 8, 8, 4, 1, 0, fake, fake, fake, fake, need, null) == w.WINO_EINVAL
+    assert L.wino_bwd_filter_workspace_bytes(0, 4, 8, 8, 4) == 0
     # size queries on bad input
     assert L.wino_workspace_bytes(1, 4, 8, 8, 4, 1, 3, 0) == 0
     assert L.wino_filter_bytes(0, 4, 2, 0) == 0
