@@ -15,6 +15,7 @@ Prints ONE JSON line.  Besides the contract fields it carries
   stages        per-stage achieved GB/s (transforms) and TFLOP/s (multiply), per layer;
   n1            the same stack at batch 1 (the latency case of the paper's Table 5);
   bwd_data      the input gradient of the same layers (Section 4.2: same algorithm, rotated filters);
+  bwd_filter    the filter gradient of the same layers (Section 4.2, Eq. (14): F(3x3,2x2));
   cpu_baseline  the fp64 CPU oracle timed on a bounded sample of the same workload.
 """
 import argparse
@@ -206,6 +207,30 @@ def time_bwd_data(torch, w, layers, ws_bytes, steps):
             "note": "conv1.1 needs no input gradient; effective flops as for the forward pass"}
 
 
+def time_bwd_filter(torch, w, layers, steps):
+    """Filter gradient (Section 4.2, Eq. (14): F(3x3,2x2)) of all 13 layers, fp32: D is the layer's
+    input, the error tensor its output buffer."""
+    if any(L.D.dtype != torch.float32 or L.Y.dtype != torch.float32 for L in layers):
+        return None
+    need = max(w.wino_bwd_filter_workspace_bytes(L.N, L.C, L.HW, L.HW, L.K) for L in layers)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    grads = [torch.empty_like(L.G) for L in layers]
+    per = []
+    for L, dG in zip(layers, grads):
+        for _ in range(2):
+            w.wino_conv2d_bwd_filter(L.D, L.Y, pad=1, dG=dG, workspace=ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            w.wino_conv2d_bwd_filter(L.D, L.Y, pad=1, dG=dG, workspace=ws)
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / steps
+        per.append({"layer": L.name, "ms": sec * 1e3, "eff_tflops": L.flops / sec / 1e12})
+    sec = sum(p["ms"] for p in per) / 1e3
+    return {"eff_tflops": sum(L.flops for L in layers) / sec / 1e12, "ms_per_step": sec * 1e3, "layers": len(layers),
+            "per_layer": per, "note": "effective flops as for the forward pass"}
+
+
 def cpu_baseline(layers, budget_s=12.0, max_images=32):
     """The fp64 oracle (Eq. (1)) on the host cores over whole images of the same workload:
     image after image through all 13 layers until about `budget_s` seconds have been spent."""
@@ -349,6 +374,9 @@ def main():
         bd = time_bwd_data(torch, w, layers, ws.numel(), max(3, args.steps // 2))
         if bd:
             out["bwd_data"] = bd
+        bf = time_bwd_filter(torch, w, layers, max(3, args.steps // 2))
+        if bf:
+            out["bwd_filter"] = bf
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers)
     if not args.no_n1 and args.batch != 1:
