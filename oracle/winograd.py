@@ -4,6 +4,13 @@ What is written out here, all from Section 4 of the paper:
 
 * the transform matrices B^T, G, A^T of F(2,3) (Eq. (7)) and F(4,3) (Eq. (15)) as exact
   rationals, plus F(3,2) (Eq. (14)) which the weight-gradient variant uses;
+* F(6,3), which Section 4.3 mentions (as F(6x6,3x3)) without printing matrices: they are
+  built here by the construction Section 4 refers to (a minimal linear-convolution
+  algorithm from polynomial evaluation and interpolation, transposed into a filtering
+  algorithm; `cook_toom`) on the interpolation points 0, 1, -1, 2, -2, 1/2, -1/2 and
+  infinity, the natural continuation of the points 0, 1, -1, 2, -2, infinity that
+  reproduce Eq. (15); the row scaling between G and B^T, which the construction leaves
+  free, is chosen so that B^T has the column of ones seen in Eq. (7) and Eq. (15);
 * the 1-D matrix form Y = A^T[(G g) . (B^T d)] (Eq. (6)) and its 2-D nesting
   Y = A^T[[G g G^T] . [B^T d B]]A (Eq. (8)), usable on Fractions or floats;
 * Algorithm 1 in its four loops -- filter transform and scatter to U, tile gather,
@@ -55,6 +62,32 @@ _MATRICES = {
             [0, 1, -1, 2, -2, 0],
             [0, 1, 1, 4, 4, 0],
             [0, 1, -1, 8, -8, 1]]),
+    # F(6,3): not printed in the paper (Section 4.3 defers it); from cook_toom() on the points
+    # 0, 1, -1, 2, -2, 1/2, -1/2, infinity, scaled like Eq. (15); checked against the
+    # construction and as an exact filter in tests/test_oracle_winograd.py
+    (6, 3): dict(
+        BT=[[1, 0, Fr(-21, 4), 0, Fr(21, 4), 0, -1, 0],
+            [0, 1, 1, Fr(-17, 4), Fr(-17, 4), 1, 1, 0],
+            [0, -1, 1, Fr(17, 4), Fr(-17, 4), -1, 1, 0],
+            [0, Fr(1, 2), Fr(1, 4), Fr(-5, 2), Fr(-5, 4), 2, 1, 0],
+            [0, Fr(-1, 2), Fr(1, 4), Fr(5, 2), Fr(-5, 4), -2, 1, 0],
+            [0, 2, 4, Fr(-5, 2), -5, Fr(1, 2), 1, 0],
+            [0, -2, 4, Fr(5, 2), -5, Fr(-1, 2), 1, 0],
+            [0, -1, 0, Fr(21, 4), 0, Fr(-21, 4), 0, 1]],
+        G=[[Fr(1), 0, 0],
+           [Fr(-2, 9), Fr(-2, 9), Fr(-2, 9)],
+           [Fr(-2, 9), Fr(2, 9), Fr(-2, 9)],
+           [Fr(1, 90), Fr(1, 45), Fr(2, 45)],
+           [Fr(1, 90), Fr(-1, 45), Fr(2, 45)],
+           [Fr(32, 45), Fr(16, 45), Fr(8, 45)],
+           [Fr(32, 45), Fr(-16, 45), Fr(8, 45)],
+           [0, 0, Fr(1)]],
+        AT=[[1, 1, 1, 1, 1, 1, 1, 0],
+            [0, 1, -1, 2, -2, Fr(1, 2), Fr(-1, 2), 0],
+            [0, 1, 1, 4, 4, Fr(1, 4), Fr(1, 4), 0],
+            [0, 1, -1, 8, -8, Fr(1, 8), Fr(-1, 8), 0],
+            [0, 1, 1, 16, 16, Fr(1, 16), Fr(1, 16), 0],
+            [0, 1, -1, 32, -32, Fr(1, 32), Fr(-1, 32), 1]]),
     # F(3,2), Eq. (14)
     (3, 2): dict(
         BT=[[1, 0, -1, 0],
@@ -79,6 +112,43 @@ def matrices(m, r=3):
 
 def matrices_f64(m, r=3):
     return tuple(np.array([[float(x) for x in row] for row in mat]) for mat in matrices(m, r))
+
+
+# Interpolation points behind each matrix set (None = the point at infinity).
+POINTS = {(2, 3): [0, 1, -1, None], (4, 3): [0, 1, -1, 2, -2, None], (3, 2): [0, 1, -1, None],
+          (6, 3): [0, 1, -1, 2, -2, Fr(1, 2), Fr(-1, 2), None]}
+
+
+def _inverse(A):
+    """Exact inverse of a square matrix of Fractions (Gauss-Jordan)."""
+    n = len(A)
+    M = [[Fr(x) for x in row] + [Fr(int(i == j)) for j in range(n)] for i, row in enumerate(A)]
+    for col in range(n):
+        piv = next(r for r in range(col, n) if M[r][col] != 0)
+        M[col], M[piv] = M[piv], M[col]
+        M[col] = [x / M[col][col] for x in M[col]]
+        for r in range(n):
+            if r != col and M[r][col] != 0:
+                f = M[r][col]
+                M[r] = [x - f * y for x, y in zip(M[r], M[col])]
+    return [row[n:] for row in M]
+
+
+def cook_toom(points, m, r):
+    """The construction Section 4 refers to, unscaled.  A product of polynomials of degrees
+    r-1 and m-1 has n = m+r-1 coefficients; it is fixed by its values at n points (at
+    infinity: its leading coefficient).  With E_k the n x k matrix that evaluates a polynomial
+    with k coefficients at the points, linear convolution is s = E_n^-1 [(E_r g) . (E_m d)];
+    exchanging the roles of d and s (transposition) gives the filter
+    y = E_m^T [(E_r g) . (E_n^-T x)].  Returns (E_n^-T, E_r, E_m^T), i.e. B^T, G, A^T up to
+    a scaling f_j of row j of G against 1/f_j of row j of B^T."""
+    n = m + r - 1
+    assert len(points) == n
+
+    def evaluate(k):
+        return [[Fr(int(j == k - 1)) if p is None else Fr(p) ** j for j in range(k)] for p in points]
+
+    return transpose(_inverse(evaluate(n))), evaluate(r), transpose(evaluate(m))
 
 
 # ---- tiny exact linear algebra on lists (works for Fractions, ints, floats) ----------------

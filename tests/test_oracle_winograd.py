@@ -23,7 +23,30 @@ def _corr2d(d, g, m, n):
              for j in range(n)] for i in range(m)]
 
 
-@pytest.mark.parametrize("m,r", [(2, 3), (4, 3), (3, 2)])
+@pytest.mark.parametrize("m,r", [(2, 3), (4, 3), (3, 2), (6, 3)])
+def test_matrices_follow_from_their_interpolation_points(m, r):
+    """Every matrix set equals the evaluation/interpolation construction of Section 4 on its
+    points up to the scalings the construction leaves free: column j of A^T by a_j, row j of G by
+    f_j, row j of B^T by b_j with a_j f_j b_j = 1 (a product term is unchanged).  Ties the F(6,3)
+    set, which the paper does not print, to the same construction as the printed ones."""
+    bt, g, at = wg.cook_toom(wg.POINTS[(m, r)], m, r)
+    BT, G, AT = wg.matrices(m, r)
+
+    def scale(ours, base):
+        f = next(a / b for a, b in zip(ours, base) if b != 0)
+        assert [f * b for b in base] == list(ours)
+        return f
+    for j in range(m + r - 1):
+        a = scale([row[j] for row in AT], [row[j] for row in at])
+        assert a * scale(G[j], g[j]) * scale(BT[j], bt[j]) == 1
+
+
+def test_interpolation_construction_rejects_a_wrong_point():
+    bt, g, at = wg.cook_toom([0, 1, -1, 3, -2, None], 4, 3)
+    assert bt != wg.cook_toom(wg.POINTS[(4, 3)], 4, 3)[0]
+
+
+@pytest.mark.parametrize("m,r", [(2, 3), (4, 3), (3, 2), (6, 3)])
 def test_1d_matrix_form_is_exact_correlation(m, r):
     """Eq. (6) with the printed matrices equals the r-tap FIR filter exactly, using
     mu = m + r - 1 general multiplications (Eq. (3))."""
@@ -36,7 +59,7 @@ def test_1d_matrix_form_is_exact_correlation(m, r):
         assert nmul == m + r - 1
 
 
-@pytest.mark.parametrize("m,r", [(2, 3), (4, 3), (3, 2)])
+@pytest.mark.parametrize("m,r", [(2, 3), (4, 3), (3, 2), (6, 3)])
 def test_2d_nesting_is_exact_correlation(m, r):
     """Eq. (8) equals direct 2-D correlation exactly with (m+r-1)^2 multiplications (Eq. (4));
     16 vs 36 for F(2x2,3x3) and 36 vs 144 for F(4x4,3x3) (Sections 4.1, 4.3)."""
@@ -48,9 +71,9 @@ def test_2d_nesting_is_exact_correlation(m, r):
         y, nmul = wg.fir_2d(m, r, d, g)
         assert y == _corr2d(d, g, m, m)
         assert nmul == a * a
-    assert {2: 16, 4: 36, 3: 16}[m] == a * a
+    assert {2: 16, 4: 36, 3: 16, 6: 64}[m] == a * a
     if r == 3:
-        assert Fr(m * m * 9, a * a) == {2: Fr(9, 4), 4: Fr(4)}[m]
+        assert Fr(m * m * 9, a * a) == {2: Fr(9, 4), 4: Fr(4), 6: Fr(81, 16)}[m]
 
 
 def test_f23_printed_products():
@@ -72,7 +95,7 @@ def test_f23_printed_products():
 
 
 def test_matrix_shapes_and_a_transposed_operand_fails():
-    for m in (2, 4):
+    for m in (2, 4, 6):
         BT, G, AT = wg.matrices(m)
         a = m + 2
         assert (len(BT), len(BT[0])) == (a, a)
@@ -88,7 +111,7 @@ def test_matrix_shapes_and_a_transposed_operand_fails():
     assert bad != _corr2d(d, g, 4, 4)
 
 
-@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("m", [2, 4, 6])
 def test_delta_filter_tile_is_identity(m):
     """A filter that is 1 at its centre returns the centre m x m block of the tile."""
     a = m + 2
@@ -98,7 +121,7 @@ def test_delta_filter_tile_is_identity(m):
     assert y == [[d[i + 1][j + 1] for j in range(m)] for i in range(m)]
 
 
-@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("m", [2, 4, 6])
 def test_tile_transform_linearity(m):
     rng = random.Random(m)
     a = m + 2
@@ -111,7 +134,8 @@ def test_tile_transform_linearity(m):
 
 
 @pytest.mark.parametrize("H,W,pad,m", [(56, 56, 1, 2), (28, 28, 1, 4), (14, 14, 1, 4), (14, 14, 1, 2),
-                                       (224, 224, 1, 4), (7, 9, 1, 4), (7, 9, 0, 2), (5, 5, 0, 4)])
+                                       (224, 224, 1, 4), (7, 9, 1, 4), (7, 9, 0, 2), (5, 5, 0, 4),
+                                       (56, 56, 1, 6), (14, 14, 1, 6), (9, 20, 0, 6)])
 def test_tile_bookkeeping(H, W, pad, m):
     """Tiles cover every output exactly once; origins follow m*t - pad (Section 4.1's tiling)."""
     N = 2
@@ -132,8 +156,9 @@ def test_tile_bookkeeping(H, W, pad, m):
     assert len(seen) == P and (cover == 1).all()
 
 
-@pytest.mark.parametrize("m", [2, 4])
-@pytest.mark.parametrize("shape", [(2, 3, 8, 8, 4, 1), (1, 2, 7, 9, 3, 1), (1, 2, 9, 6, 2, 0), (3, 1, 5, 5, 1, 1)])
+@pytest.mark.parametrize("m", [2, 4, 6])
+@pytest.mark.parametrize("shape", [(2, 3, 8, 8, 4, 1), (1, 2, 7, 9, 3, 1), (1, 2, 9, 6, 2, 0), (3, 1, 5, 5, 1, 1),
+                                   (1, 2, 13, 20, 3, 1)])
 def test_algorithm1_matches_direct_oracle(m, shape):
     """Algorithm 1 in float64 reproduces Eq. (1) (incl. ragged edge tiles) to rounding."""
     N, C, H, W, K, pad = shape
