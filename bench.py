@@ -16,6 +16,7 @@ Prints ONE JSON line.  Besides the contract fields it carries
   n1            the same stack at batch 1 (the latency case of the paper's Table 5);
   bwd_data      the input gradient of the same layers (Section 4.2: same algorithm, rotated filters);
   bwd_filter    the filter gradient of the same layers (Section 4.2, Eq. (14): F(3x3,2x2));
+  f6x6          the same layers through F(6x6,3x3) (Section 4.3), per layer, next to the headline algorithm;
   cpu_baseline  the fp64 CPU oracle timed on a bounded sample of the same workload.
 """
 import argparse
@@ -231,6 +232,34 @@ def time_bwd_filter(torch, w, layers, steps):
             "per_layer": per, "note": "effective flops as for the forward pass"}
 
 
+def time_f6x6(torch, w, layers, layer_ms, steps):
+    """The same layers through F(6x6,3x3) (Section 4.3 mentions it; 5.06x fewer multiplications, edge
+    tiles zero-filled where 6 does not divide the image), fp32, four separate stages."""
+    todo = [(L, t) for L, t in zip(layers, layer_ms) if not L.direct]
+    if any(L.D.dtype != torch.float32 for L, _ in todo):
+        return None
+    ws = torch.empty(max(w.wino_workspace_bytes(L.N, L.C, L.HW, L.HW, L.K, 1, 6, L.dt) for L, _ in todo),
+                     dtype=torch.uint8, device="cuda")
+    per, best_ms = [], sum(t for L, t in zip(layers, layer_ms) if L.direct)
+    for L, base in todo:
+        for _ in range(2):
+            w.wino_conv2d_fwd_ex(L.D, G=L.G, pad=1, m=6, Y=L.Y, workspace=ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            w.wino_conv2d_fwd_ex(L.D, G=L.G, pad=1, m=6, Y=L.Y, workspace=ws)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / steps * 1e3
+        per.append({"layer": L.name, "ms": ms, "eff_tflops": L.flops / ms / 1e9, "headline_m": L.m, "headline_ms": base})
+        best_ms += min(ms, base)
+    tot = sum(p["ms"] for p in per)
+    return {"eff_tflops": sum(L.flops for L, _ in todo) / tot / 1e9, "ms_per_step": tot, "layers": len(per),
+            "per_layer": per,
+            "best_of_per_layer": {"ms_per_step": best_ms, "eff_tflops": sum(L.flops for L in layers) / best_ms / 1e9,
+                                  "note": "all 13 layers, each with the faster of its headline algorithm and "
+                                          "F(6x6,3x3); context only, not the headline policy"}}
+
+
 def cpu_baseline(layers, budget_s=12.0, max_images=32):
     """The fp64 oracle (Eq. (1)) on the host cores over whole images of the same workload:
     image after image through all 13 layers until about `budget_s` seconds have been spent."""
@@ -258,11 +287,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--dtype", choices=["f32", "f16"], default="f32")
-    ap.add_argument("--m", default="auto", help="auto | 2 | 4")
+    ap.add_argument("--m", default="auto", help="auto | 2 | 4 | 6 (6: fp32 only)")
     ap.add_argument("--no-n1", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stages", action="store_true")
-    ap.add_argument("--no-bwd", action="store_true", help="skip the input-gradient line")
+    ap.add_argument("--no-bwd", action="store_true", help="skip the input- and filter-gradient lines")
+    ap.add_argument("--no-f6", action="store_true", help="skip the F(6x6,3x3) line")
     ap.add_argument("--probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 1 GiB device copy (counter calibration), then every "
                          "kernel of one step once; prints the algorithmic bytes per kernel and exits")
@@ -377,6 +407,10 @@ def main():
         bf = time_bwd_filter(torch, w, layers, max(3, args.steps // 2))
         if bf:
             out["bwd_filter"] = bf
+    if not args.no_f6 and policy == "auto":
+        f6 = time_f6x6(torch, w, layers, layer_ms, max(3, args.steps // 2))
+        if f6:
+            out["f6x6"] = f6
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers)
     if not args.no_n1 and args.batch != 1:

@@ -7,9 +7,10 @@
  *     Y[i][k][x][y] = sum_c sum_u sum_v D[i][c][x+u-pad][y+v-pad] * G[k][c][u][v]
  *
  * (2-D correlation, no filter flip, zeros outside the image) for 3x3 filters at stride 1 with
- * the algorithm F(m x m, 3 x 3) of Section 4, m = 2 (Eq. (7), (8)) or m = 4 (Eq. (15)), in
- * the four stages of Algorithm 1, plus a direct evaluation of Eq. (1) for layers the fast
- * algorithm does not cover.
+ * the algorithm F(m x m, 3 x 3) of Section 4, m = 2 (Eq. (7), (8)), m = 4 (Eq. (15)) or m = 6
+ * (Section 4.3 mentions F(6 x 6, 3 x 3) without printing its matrices; here: interpolation
+ * points 0, +-1, +-2, +-1/2, infinity; fp32 storage only), in the four stages of Algorithm 1,
+ * plus a direct evaluation of Eq. (1) for layers the fast algorithm does not cover.
  *
  * Conventions for every entry point
  *   - D, G, U, V, M, Y and workspaces are DEVICE pointers owned by the caller; the library
@@ -46,7 +47,7 @@ extern "C" {
 typedef enum {
     WINO_OK = 0,
     WINO_EINVAL = 1,       /* null / misaligned pointer, non-positive extent, bad enum */
-    WINO_EUNSUPPORTED = 2, /* m not in {2,4}, pad not in {0,1}, empty output, unsupported dtype */
+    WINO_EUNSUPPORTED = 2, /* m not in {2,4,6} (6: fp32 only), pad not in {0,1}, empty output, unsupported dtype */
     WINO_EWORKSPACE = 3,   /* workspace smaller than wino_workspace_bytes() */
     WINO_EHIP = 4          /* a HIP call failed; see wino_last_hip_error() */
 } wino_status_t;

@@ -111,8 +111,10 @@ hipError_t launch_filter_transform_bwd(const Geo &g, const void *G, void *U, hip
     if (g.dt == WINO_F32) {
         if (g.m == 2)
             filter_transform_bwd_kernel<2, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, K, C, g.Kp, g.Cp);
-        else
+        else if (g.m == 4)
             filter_transform_bwd_kernel<4, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, K, C, g.Kp, g.Cp);
+        else
+            filter_transform_bwd_kernel<6, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, K, C, g.Kp, g.Cp);
     } else {
         if (g.m == 2)
             filter_transform_bwd_kernel<2, __half><<<grid, block, 0, s>>>((const __half *)G, (__half *)U, K, C, g.Kp, g.Cp);
@@ -128,8 +130,10 @@ hipError_t launch_filter_transform(const Geo &g, const void *G, void *U, hipStre
     if (g.dt == WINO_F32) {
         if (g.m == 2)
             filter_transform_kernel<2, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, g.K, g.C, g.Kp, g.Cp);
-        else
+        else if (g.m == 4)
             filter_transform_kernel<4, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, g.K, g.C, g.Kp, g.Cp);
+        else
+            filter_transform_kernel<6, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, g.K, g.C, g.Kp, g.Cp);
     } else {
         if (g.m == 2)
             filter_transform_kernel<2, __half><<<grid, block, 0, s>>>((const __half *)G, (__half *)U, g.K, g.C, g.Kp, g.Cp);

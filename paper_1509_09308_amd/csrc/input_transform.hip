@@ -247,8 +247,10 @@ hipError_t launch_input_transform(const Geo &g, const void *D, void *V, hipStrea
     if (g.dt == WINO_F32) {
         if (g.m == 2)
             input_transform_kernel<2, float><<<grid, block, 0, s>>>((const float *)D, (float *)V, g);
-        else
+        else if (g.m == 4)
             input_transform_kernel<4, float><<<grid, block, 0, s>>>((const float *)D, (float *)V, g);
+        else
+            input_transform_kernel<6, float><<<grid, block, 0, s>>>((const float *)D, (float *)V, g);
     } else {
         dim3 gridh((g.Pp + 63) / 64, g.Cp / 8), blockh(512);
         const __half *d = (const __half *)D;

@@ -62,6 +62,11 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float *__re
         if (full_row) {
             if constexpr (M == 4) {
                 *reinterpret_cast<float4 *>(row) = make_float4(y[p][0], y[p][1], y[p][2], y[p][3]);
+            } else if constexpr (M == 6) {
+                // 6-wide segments are 8-byte aligned when Wo is a multiple of 6
+                *reinterpret_cast<float2 *>(row) = make_float2(y[p][0], y[p][1]);
+                *reinterpret_cast<float2 *>(row + 2) = make_float2(y[p][2], y[p][3]);
+                *reinterpret_cast<float2 *>(row + 4) = make_float2(y[p][4], y[p][5]);
             } else {
                 *reinterpret_cast<float2 *>(row) = make_float2(y[p][0], y[p][1]);
             }
@@ -79,13 +84,17 @@ hipError_t launch_output_transform(const Geo &g, int y_dt, const float *M, void 
     if (y_dt == WINO_F32) {
         if (g.m == 2)
             output_transform_kernel<2, float><<<grid, block, 0, s>>>(M, (float *)Y, g, splits);
-        else
+        else if (g.m == 4)
             output_transform_kernel<4, float><<<grid, block, 0, s>>>(M, (float *)Y, g, splits);
+        else
+            output_transform_kernel<6, float><<<grid, block, 0, s>>>(M, (float *)Y, g, splits);
     } else {
         if (g.m == 2)
             output_transform_kernel<2, __half><<<grid, block, 0, s>>>(M, (__half *)Y, g, splits);
-        else
+        else if (g.m == 4)
             output_transform_kernel<4, __half><<<grid, block, 0, s>>>(M, (__half *)Y, g, splits);
+        else
+            output_transform_kernel<6, __half><<<grid, block, 0, s>>>(M, (__half *)Y, g, splits);
     }
     return hipGetLastError();
 }

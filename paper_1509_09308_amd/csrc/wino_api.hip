@@ -20,6 +20,9 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 bool bad_ptr(const void *p) { return p == nullptr || !aligned16(p); }
 bool bad_dtype(int dt) { return dt != WINO_F32 && dt != WINO_F16; }
 size_t elem_size(int dt) { return dt == WINO_F16 ? 2 : 4; }
+// F(2x2,3x3) and F(4x4,3x3) in both storage types; F(6x6,3x3) in fp32 only (its transformed values
+// span too many binades for fp16 storage)
+bool bad_m(int m, int dt) { return !(m == 2 || m == 4 || (m == 6 && dt == WINO_F32)); }
 
 // Validates the geometry shared by every Winograd entry point and fills `g`.
 // N, C, K may be passed as 1 by callers that do not use them.
@@ -27,7 +30,7 @@ int make_geo(int N, int C, int H, int W, int K, int pad, int m, int dt, Geo *g)
 {
     if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0) return WINO_EINVAL;
     if (bad_dtype(dt)) return WINO_EINVAL;
-    if (m != 2 && m != 4) return WINO_EUNSUPPORTED;
+    if (bad_m(m, dt)) return WINO_EUNSUPPORTED;
     if (pad != 0 && pad != 1) return WINO_EUNSUPPORTED;
     const int Ho = H + 2 * pad - 2, Wo = W + 2 * pad - 2;
     if (Ho <= 0 || Wo <= 0) return WINO_EUNSUPPORTED;
@@ -48,7 +51,7 @@ int make_geo_kcp(int K, int C, long long P, int m, int dt, Geo *g)
 {
     if (K <= 0 || C <= 0 || P <= 0) return WINO_EINVAL;
     if (bad_dtype(dt)) return WINO_EINVAL;
-    if (m != 2 && m != 4) return WINO_EUNSUPPORTED;
+    if (bad_m(m, dt)) return WINO_EUNSUPPORTED;
     if (P > (1LL << 30) || C > 65000 || K > 65000) return WINO_EUNSUPPORTED;
     *g = Geo{};
     g->m = m; g->alpha = m + 2; g->a2 = (m + 2) * (m + 2);
@@ -114,7 +117,7 @@ int wino_tile_coords(int N, int H, int W, int pad, int m, long long b, int out[5
 int wino_padded_dims(int K, int C, long long P, int m, int dt, int *Kp, int *Cp, long long *Pp)
 {
     if (K <= 0 || C <= 0 || P < 0 || bad_dtype(dt)) return WINO_EINVAL;
-    if (m != 2 && m != 4) return WINO_EUNSUPPORTED;
+    if (bad_m(m, dt)) return WINO_EUNSUPPORTED;
     if (P > (1LL << 30)) return WINO_EUNSUPPORTED;
     if (Kp) *Kp = pad_k(K);
     if (Cp) *Cp = pad_c(C, dt);

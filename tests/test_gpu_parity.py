@@ -31,7 +31,7 @@ def test_config1_small_layer():
     assert rel_err(Y, ref) <= TOL[("f32", 2)]
 
 
-@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("m", [2, 4, 6])
 def test_config2_vgg_layer(m):
     """N=8, C=K=512, 28x28, fp32, both algorithms."""
     torch, w = require_gpu()
@@ -43,7 +43,7 @@ def test_config2_vgg_layer(m):
     assert e <= TOL[("f32", m)]
 
 
-@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("m", [2, 4, 6])
 @pytest.mark.parametrize("shape", [(1, 1, 3, 3, 1, 1), (1, 1, 4, 4, 1, 0), (2, 3, 5, 7, 4, 1), (1, 19, 13, 29, 70, 1),
                                    (3, 33, 14, 14, 65, 1), (2, 16, 31, 18, 130, 0), (5, 130, 9, 9, 40, 1),
                                    (1, 7, 67, 131, 9, 1)])
@@ -55,7 +55,9 @@ def test_ragged_and_degenerate_shapes(m, shape):
     ref = direct.conv2d_fwd(D, G, pad=pad)
     Y = _run_full(w, D, G, pad, m)
     assert Y.shape == ref.shape
-    assert rel_err(Y, ref) <= TOL[("f32", m)]
+    e = rel_err(Y, ref)
+    print("ragged %s m=%d rel err %.3e" % (shape, m, e))
+    assert e <= TOL[("f32", m)]
 
 
 @pytest.mark.parametrize("layer", range(1, 13))
@@ -102,6 +104,35 @@ def test_config4_full_size_sampled(layer):
     print("%s N=64 m=%d sampled rel err %.3e" % (name, m, e))
     assert e <= TOL[("f32", m)]
     assert bool(torch.isfinite(Y).all())
+
+
+@pytest.mark.parametrize("layer", [3, 5, 9])
+def test_f6x6_full_size_sampled(layer):
+    """F(6x6,3x3) at N=64 on VGG shapes whose images 6 does not divide (edge tiles zero-filled)."""
+    torch, w = require_gpu()
+    name, C, HW, K = synth.VGG16_LAYERS[layer]
+    N, m = 64, 6
+    D, G = synth.make_layer(N, C, HW, HW, K, synth.layer_seed(8, layer))
+    d, g = to_gpu(D), to_gpu(G)
+    ws = w.alloc_workspace(N, C, HW, HW, K, 1, m)
+    Y = w.wino_conv2d_fwd_ex(d, G=g, pad=1, m=m, workspace=ws)
+    pts = synth.sample_points((N, K, HW, HW), 4000, seed=layer)
+    idx = torch.from_numpy(pts.astype(np.int64)).cuda()
+    got = Y[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy()
+    ref = direct.conv2d_points(D, G, pts, pad=1)
+    e = rel_err(got, ref)
+    print("%s N=64 m=6 sampled rel err %.3e" % (name, e))
+    assert e <= TOL[("f32", 6)]
+    assert bool(torch.isfinite(Y).all())
+
+
+def test_f6x6_rejects_f16_storage():
+    torch, w = require_gpu()
+    D = torch.zeros((1, 8, 12, 12), device="cuda", dtype=torch.float16)
+    G = torch.zeros((8, 8, 3, 3), device="cuda", dtype=torch.float16)
+    with pytest.raises(w.WinoError) as ei:
+        w.wino_conv2d_fwd_ex(D, G=G, pad=1, m=6)
+    assert ei.value.status == w.WINO_EUNSUPPORTED
 
 
 # ---- fp16 storage of D, G, U, V; fp32 accumulation; fp32 Y (config 5) ----------------------------

@@ -12,12 +12,12 @@ from gpu_util import require_gpu, rel_err, to_gpu
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("m", [2, 4, 6])
 @pytest.mark.parametrize("K,C", [(32, 32), (70, 19), (5, 3), (256, 128)])
 def test_filter_transform(m, K, C):
     torch, w = require_gpu()
     rng = np.random.default_rng(K * 7 + C + m)
-    # multiples of 4 make G g G^T exact for F(2,3) (entries 1, 1/2); F(4,3) has 1/6 and is rounded
+    # multiples of 4 make G g G^T exact for F(2,3) (entries 1, 1/2); F(4,3) has 1/6, F(6,3) has 1/90: rounded
     G = (rng.integers(-8, 9, (K, C, 3, 3)) * 4).astype(np.float32)
     U = w.wino_filter_transform(to_gpu(G), m)
     torch.cuda.synchronize()
@@ -32,7 +32,7 @@ def test_filter_transform(m, K, C):
     assert not full[:, :, K:, :].any() and not full[:, :, :, C:].any()
 
 
-@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("m", [2, 4, 6])
 @pytest.mark.parametrize("N,C,H,W,pad", [(1, 4, 8, 8, 1), (2, 3, 14, 14, 1), (1, 2, 7, 9, 1), (2, 5, 9, 6, 0),
                                          (1, 17, 56, 56, 1), (3, 2, 30, 34, 1)])
 def test_input_transform_bit_exact(m, N, C, H, W, pad):
@@ -42,7 +42,7 @@ def test_input_transform_bit_exact(m, N, C, H, W, pad):
     V = w.wino_input_transform(to_gpu(D), pad, m)
     torch.cuda.synchronize()
     P = wg.num_tiles(N, H, W, pad, m)
-    ref = wg.data_transform(D, pad, m)          # integers: B^T is an integer matrix
+    ref = wg.data_transform(D, pad, m)          # B^T has integer entries (quarters for F(6,3)): exact
     got = w.unpack_v(V, C, P, m)
     assert got.shape == ref.shape
     assert np.array_equal(got.astype(np.float64), ref)
@@ -50,7 +50,7 @@ def test_input_transform_bit_exact(m, N, C, H, W, pad):
     assert not full[:, :, C:, :].any() and not full[:, :, :, P:].any()
 
 
-@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("m", [2, 4, 6])
 @pytest.mark.parametrize("K,C,P", [(32, 32, 784), (64, 64, 256), (70, 19, 100), (128, 48, 300), (256, 256, 130),
                                    (5, 3, 17), (192, 64, 49)])
 def test_batched_gemm_exact_on_integers(m, K, C, P):
@@ -83,7 +83,7 @@ def test_batched_gemm_one_hot_routing():
                 assert np.array_equal(M[xi, nu, k], v[xi, nu, (k * 5 + xi * a + nu) % C])
 
 
-@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("m", [2, 4, 6])
 @pytest.mark.parametrize("N,K,H,W,pad", [(1, 4, 8, 8, 1), (2, 3, 14, 14, 1), (1, 2, 7, 9, 1), (2, 5, 9, 6, 0),
                                          (1, 33, 56, 56, 1), (3, 2, 30, 34, 1)])
 def test_output_transform_bit_exact(m, N, K, H, W, pad):
@@ -91,10 +91,13 @@ def test_output_transform_bit_exact(m, N, K, H, W, pad):
     a = m + 2
     P = wg.num_tiles(N, H, W, pad, m)
     rng = np.random.default_rng(H * 17 + W + m)
-    mm = rng.integers(-500, 501, (a, a, K, P)).astype(np.float32)
+    if m == 6:   # A^T of F(6,3) has entries down to 1/32: multiples of 32 keep both passes exact in fp32
+        mm = (rng.integers(-3, 4, (a, a, K, P)) * 32).astype(np.float32)
+    else:
+        mm = rng.integers(-500, 501, (a, a, K, P)).astype(np.float32)
     Y = w.wino_output_transform(w.pack_m(mm, m), N, K, H, W, pad, m)
     torch.cuda.synchronize()
-    ref = wg.inverse_transform(mm.astype(np.float64), N, H, W, pad, m)   # A^T is an integer matrix
+    ref = wg.inverse_transform(mm.astype(np.float64), N, H, W, pad, m)
     assert np.array_equal(Y.cpu().numpy().astype(np.float64), ref)
 
 
@@ -114,10 +117,11 @@ def test_f2x2_delta_filter_end_to_end_bitwise(shape):
     assert np.array_equal(Y.cpu().numpy(), D)
 
 
-@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("m", [2, 4, 6])
 def test_integer_layer_end_to_end_exact(m):
     """Integer data, filters that are multiples of the transform denominators: F(2x2) is
-    exact end to end; F(4x4) is exact except for the rounding of 1/6-type constants."""
+    exact end to end; F(4x4) and F(6x6) are exact except for the rounding of 1/6- and 1/90-type
+    constants (amplified, for F(6x6), by the larger entries of its matrices)."""
     torch, w = require_gpu()
     D, G = synth.make_integer_layer(2, 6, 18, 22, 7, seed=3, gscale=4.0 if m == 2 else 576.0)
     Y = w.wino_conv2d_fwd(to_gpu(D), to_gpu(G), pad=1, m=m).cpu().numpy()
@@ -125,7 +129,9 @@ def test_integer_layer_end_to_end_exact(m):
     if m == 2:
         assert np.array_equal(Y.astype(np.float64), ref)
     else:
-        assert rel_err(Y, ref) < 1e-6
+        e = rel_err(Y, ref)
+        print("integer layer m=%d rel err %.3e" % (m, e))
+        assert e < (1e-6 if m == 4 else 1e-5)
 
 
 @pytest.mark.parametrize("shape", [(1, 3, 20, 20, 8, 3, 3, 1, 1), (2, 3, 17, 23, 5, 5, 5, 2, 2),

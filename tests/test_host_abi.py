@@ -68,6 +68,12 @@ def test_argument_validation_without_gpu(L):
                                 null) == w.WINO_EINVAL
     assert L.wino_conv2d_fwd_ex(1, 4, 8, 8, 4, 1, 2, 0, 0, fake, fake, null, fake, fake, need, 99,
                                 null) == w.WINO_EINVAL
+    # F(6x6,3x3): fp32 storage only
+    assert L.wino_workspace_bytes(1, 4, 8, 8, 4, 1, 6, 0) > 0
+    assert L.wino_workspace_bytes(1, 4, 8, 8, 4, 1, 6, 1) == 0
+    assert L.wino_conv2d_variant(1, 4, 8, 8, 4, 1, 6, 1, 0, 0) == -w.WINO_EUNSUPPORTED
+    assert L.wino_conv2d_variant(1, 4, 8, 8, 4, 1, 6, 0, 0, 0) == w.FLAG_UNFUSED
+    assert L.wino_num_tiles(2, 14, 14, 1, 6) == 2 * 3 * 3
     # filter gradient: fp32 and pad 1 only, workspace and pointers checked
     need = L.wino_bwd_filter_workspace_bytes(2, 4, 8, 8, 4)
     assert need >= 16 * 32 * 32 * 4 * 3          # W, V (Pb = 32 blocks, 32 padded rows) and one M
@@ -85,7 +91,8 @@ def test_argument_validation_without_gpu(L):
 
 
 SHAPES = [(1, 56, 56, 1, 2), (8, 28, 28, 1, 2), (8, 28, 28, 1, 4), (1, 224, 224, 1, 4), (2, 112, 112, 1, 4),
-          (3, 14, 14, 1, 4), (3, 14, 14, 1, 2), (2, 7, 9, 1, 4), (2, 7, 9, 0, 2), (1, 5, 5, 0, 4), (64, 14, 14, 1, 4)]
+          (3, 14, 14, 1, 4), (3, 14, 14, 1, 2), (2, 7, 9, 1, 4), (2, 7, 9, 0, 2), (1, 5, 5, 0, 4), (64, 14, 14, 1, 4),
+          (2, 56, 56, 1, 6), (3, 14, 14, 1, 6), (1, 9, 20, 0, 6)]
 
 
 @pytest.mark.parametrize("N,H,W,pad,m", SHAPES)
@@ -136,7 +143,7 @@ def test_pack_unpack_round_trip_host_only():
     """The binding's layout helpers invert each other (checked on CPU tensors)."""
     rng = np.random.default_rng(0)
     for dt, npdt in ((0, np.float32), (1, np.float16)):
-        for m in (2, 4):
+        for m in ((2, 4, 6) if dt == 0 else (2, 4)):
             a = m + 2
             u = rng.standard_normal((a, a, 5, 19)).astype(npdt)
             v = rng.standard_normal((a, a, 19, 45)).astype(npdt)
