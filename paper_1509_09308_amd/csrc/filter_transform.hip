@@ -2,64 +2,16 @@
 // to the alpha^2 matrices U^(xi,nu).  Run once per set of weights (the "FX" variant of
 // Section 6); bound by memory traffic: 9 values in, alpha^2 values out per (k, c).
 #include "wino_internal.h"
-#include "transforms.h"
+#include "stage_bodies.h"
 
 namespace wino {
 
-template <typename T> __device__ __forceinline__ float ld_f(const T *p);
-template <> __device__ __forceinline__ float ld_f<float>(const float *p) { return *p; }
-template <> __device__ __forceinline__ float ld_f<__half>(const __half *p) { return __half2float(*p); }
-
-// One thread per (k, c) of the padded Kp x Cp grid, k fastest: a wavefront is 64 consecutive
-// filters of one channel, so each of its alpha^2 stores is 256 contiguous bytes.  A workgroup
-// covers KT filters x CT channels; the 9*CT source values of one filter are contiguous in G and
-// are staged through LDS with coalesced loads.
 template <int M, typename T>
 __global__ __launch_bounds__(256) void filter_transform_kernel(const T *__restrict__ G, T *__restrict__ U, int K,
                                                                int C, int Kp, int Cp)
 {
-    constexpr int A = M + 2, KT = 64, CT = 4, ROW = CT * 9 + 1;
-    __shared__ float gs[KT * ROW];
-    const int k0 = blockIdx.x * KT, c0 = blockIdx.y * CT;
-    for (int idx = threadIdx.x; idx < KT * CT * 9; idx += 256) {
-        const int kl = idx / (CT * 9), j = idx % (CT * 9);
-        const int k = k0 + kl, c = c0 + j / 9;
-        float v = 0.0f;
-        if (k < K && c < C) v = ld_f<T>(G + ((size_t)k * C + c0) * 9 + j);
-        gs[kl * ROW + j] = v;
-    }
-    __syncthreads();
-    const int kl = threadIdx.x % KT, cl = threadIdx.x / KT;
-    const int k = k0 + kl, c = c0 + cl;
-    if (k >= Kp || c >= Cp) return;
-    float g[3][3], t[A][3], u[A][A];
-#pragma unroll
-    for (int i = 0; i < 3; ++i)
-#pragma unroll
-        for (int j = 0; j < 3; ++j) g[i][j] = gs[kl * ROW + cl * 9 + i * 3 + j];
-    // t = G g : transform the columns of g
-#pragma unroll
-    for (int j = 0; j < 3; ++j) {
-        float col[3] = {g[0][j], g[1][j], g[2][j]}, o[A];
-        g_mul<M>(col, o);
-#pragma unroll
-        for (int i = 0; i < A; ++i) t[i][j] = o[i];
-    }
-    // u = t G^T : transform the rows of t
-#pragma unroll
-    for (int i = 0; i < A; ++i) g_mul<M>(t[i], u[i]);
-#pragma unroll
-    for (int xi = 0; xi < A; ++xi)
-#pragma unroll
-        for (int nu = 0; nu < A; ++nu) {
-            const int e = xi * A + nu;
-            if constexpr (sizeof(T) == 4) {
-                U[((size_t)e * Cp + c) * Kp + k] = u[xi][nu];
-            } else {
-                // fp16 layout [e][c/8][k][c%8]
-                U[(((size_t)e * (Cp / 8) + c / 8) * Kp + k) * 8 + (c % 8)] = __float2half_rn(u[xi][nu]);
-            }
-        }
+    __shared__ float gs[FT_LDS];
+    filter_transform_block<M, T>(G, U, K, C, Kp, Cp, blockIdx.x, blockIdx.y, gs);
 }
 
 // Filter transform for the gradient with respect to the input (Section 4.2 of the paper): that

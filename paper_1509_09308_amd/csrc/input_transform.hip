@@ -6,152 +6,21 @@
 #include <stdlib.h>
 
 #include "wino_internal.h"
-#include "transforms.h"
+#include "stage_bodies.h"
 
 namespace wino {
-
-template <typename T> __device__ __forceinline__ float ld_in(const T *p);
-template <> __device__ __forceinline__ float ld_in<float>(const float *p) { return *p; }
-template <> __device__ __forceinline__ float ld_in<__half>(const __half *p) { return __half2float(*p); }
-
-// One thread per (c, b); b is the fastest index of a workgroup so the stores to every
-// V^(xi,nu) row are contiguous across a wavefront.  Channels c >= C and tiles b >= P are
-// padding and are written as zeros.
-typedef float floatx4_v __attribute__((ext_vector_type(4)));
 
 template <int M, typename T, bool VEC = false>
 __global__ __launch_bounds__(256) void input_transform_kernel(const T *__restrict__ D, T *__restrict__ V, Geo g)
 {
-    constexpr int A = M + 2;
-    const int b = blockIdx.x * 256 + threadIdx.x;
-    const int c = blockIdx.y;
-    if (b >= g.Pp) return;
-    float d[A][A];
-#pragma unroll
-    for (int p = 0; p < A; ++p)
-#pragma unroll
-        for (int q = 0; q < A; ++q) d[p][q] = 0.0f;
-    if (c < g.C && b < g.P) {
-        const int ty = b % g.Tw;
-        const int t2 = b / g.Tw;
-        const int tx = t2 % g.Th;
-        const int i = t2 / g.Th;
-        const int x0 = M * tx - g.pad, y0 = M * ty - g.pad;
-        const T *src = D + ((size_t)i * g.C + c) * g.H * g.W;
-#pragma unroll
-        for (int p = 0; p < A; ++p) {
-            const int x = x0 + p;
-            if (x >= 0 && x < g.H) {
-                if constexpr (VEC) {
-                    // pad 1 and W a multiple of 4: columns 1..4 are one aligned 16-byte load
-                    const float *row = reinterpret_cast<const float *>(src) + (size_t)x * g.W + y0;
-                    const floatx4_v mid = *reinterpret_cast<const floatx4_v *>(row + 1);
-                    d[p][1] = mid[0]; d[p][2] = mid[1]; d[p][3] = mid[2]; d[p][4] = mid[3];
-                    if (y0 >= 0) d[p][0] = row[0];
-                    if (y0 + 5 < g.W) d[p][5] = row[5];
-                } else {
-#pragma unroll
-                    for (int q = 0; q < A; ++q) {
-                        const int y = y0 + q;
-                        if (y >= 0 && y < g.W) d[p][q] = ld_in<T>(src + (size_t)x * g.W + y);
-                    }
-                }
-            }
-        }
-    }
-    // t = B^T d (columns), v = t B (rows)
-    float t[A][A], v[A][A];
-#pragma unroll
-    for (int q = 0; q < A; ++q) {
-        float col[A], o[A];
-#pragma unroll
-        for (int p = 0; p < A; ++p) col[p] = d[p][q];
-        bt_mul<M>(col, o);
-#pragma unroll
-        for (int p = 0; p < A; ++p) t[p][q] = o[p];
-    }
-#pragma unroll
-    for (int p = 0; p < A; ++p) bt_mul<M>(t[p], v[p]);
-#pragma unroll
-    for (int xi = 0; xi < A; ++xi)
-#pragma unroll
-        for (int nu = 0; nu < A; ++nu) {
-            const int e = xi * A + nu;
-            if constexpr (sizeof(T) == 4) {
-                V[((size_t)e * g.Cp + c) * g.Pp + b] = v[xi][nu];
-            } else {
-                V[(((size_t)e * (g.Cp / 8) + c / 8) * g.Pp + b) * 8 + (c % 8)] = __float2half_rn(v[xi][nu]);
-            }
-        }
+    input_transform_block<M, T, VEC>(D, V, g, blockIdx.x, blockIdx.y);
 }
-
-// fp32, pad 1, W a multiple of 8 (an even number of tiles per row): two horizontally adjacent
-// tiles per thread.  Their 10 input columns are fetched per row as two aligned 16-byte loads
-// (32 contiguous bytes per lane, so a wavefront requests whole cache lines) plus the two outer
-// columns, which are absent on the image border; the two results go out as one 8-byte store per
-// component, 512 contiguous bytes per wavefront and store instruction.
-typedef float floatx4_it __attribute__((ext_vector_type(4)));
-typedef float floatx2_it __attribute__((ext_vector_type(2)));
 
 template <int M>
 __global__ __launch_bounds__(256) void input_transform_pair_kernel(const float *__restrict__ D, float *__restrict__ V,
                                                                    Geo g)
 {
-    constexpr int A = M + 2;
-    static_assert(M == 4, "two 6-wide tiles share 10 columns: 1 + 4 + 4 + 1");
-    const int b0 = (blockIdx.x * 256 + threadIdx.x) * 2;   // even; Tw is even, so b0 and b0+1 share a tile row
-    const int c = blockIdx.y;
-    if (b0 >= g.Pp) return;
-    float d[A][10];
-#pragma unroll
-    for (int p = 0; p < A; ++p)
-#pragma unroll
-        for (int q = 0; q < 10; ++q) d[p][q] = 0.0f;
-    if (c < g.C && b0 < g.P) {   // P is even as well, so both tiles exist
-        const int ty = b0 % g.Tw;
-        const int t2 = b0 / g.Tw;
-        const int tx = t2 % g.Th;
-        const int i = t2 / g.Th;
-        const int x0 = M * tx - 1, y0 = M * ty - 1;
-        const float *src = D + ((size_t)i * g.C + c) * g.H * g.W;
-#pragma unroll
-        for (int p = 0; p < A; ++p) {
-            const int x = x0 + p;
-            if (x >= 0 && x < g.H) {
-                const float *row = src + (size_t)x * g.W + y0;
-                const floatx4_it m0 = *reinterpret_cast<const floatx4_it *>(row + 1);
-                const floatx4_it m1 = *reinterpret_cast<const floatx4_it *>(row + 5);
-                d[p][1] = m0[0]; d[p][2] = m0[1]; d[p][3] = m0[2]; d[p][4] = m0[3];
-                d[p][5] = m1[0]; d[p][6] = m1[1]; d[p][7] = m1[2]; d[p][8] = m1[3];
-                if (y0 >= 0) d[p][0] = row[0];
-                if (y0 + 9 < g.W) d[p][9] = row[9];
-            }
-        }
-    }
-    float v[2][A][A];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        float tt[A][A];
-#pragma unroll
-        for (int q = 0; q < A; ++q) {
-            float col[A], o[A];
-#pragma unroll
-            for (int p = 0; p < A; ++p) col[p] = d[p][4 * t + q];
-            bt_mul<M>(col, o);
-#pragma unroll
-            for (int p = 0; p < A; ++p) tt[p][q] = o[p];
-        }
-#pragma unroll
-        for (int p = 0; p < A; ++p) bt_mul<M>(tt[p], v[t][p]);
-    }
-#pragma unroll
-    for (int xi = 0; xi < A; ++xi)
-#pragma unroll
-        for (int nu = 0; nu < A; ++nu) {
-            const int e = xi * A + nu;
-            *reinterpret_cast<floatx2_it *>(V + ((size_t)e * g.Cp + c) * g.Pp + b0) =
-                floatx2_it{v[0][xi][nu], v[1][xi][nu]};
-        }
+    input_transform_pair_block<M>(D, V, g, blockIdx.x, blockIdx.y);
 }
 
 // fp16 storage.  V is laid out [e][c/8][b][c%8] (8 channels of one tile are the 16 bytes a lane

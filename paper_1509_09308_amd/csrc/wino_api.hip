@@ -257,17 +257,24 @@ static int run_layer(const Geo &g, int y_dt, const void *D, const void *G, const
     void *Uw = ws, *Vw = ws + ub;
     float *Mw = (float *)(ws + ub + vb);
     hipError_t e;
+    if (flags == WINO_FLAG_AUTO && y_dt == WINO_F32 && fused_preferred(g)) flags = WINO_FLAG_FUSED;
+    bool v_done = false;
     if (U == nullptr) {
-        e = bwd ? launch_filter_transform_bwd(g, G, Uw, s) : launch_filter_transform(g, G, Uw, s);
+        if (!bwd && flags != WINO_FLAG_FUSED && prep_eligible(g)) {
+            // filters and input tiles are transformed by one launch
+            e = launch_prep(g, (const float *)G, (float *)Uw, (const float *)D, (float *)Vw, s);
+            v_done = true;
+        } else {
+            e = bwd ? launch_filter_transform_bwd(g, G, Uw, s) : launch_filter_transform(g, G, Uw, s);
+        }
         if (e != hipSuccess) return hip_fail(e);
         U = Uw;
     }
-    if (flags == WINO_FLAG_AUTO && y_dt == WINO_F32 && fused_preferred(g)) flags = WINO_FLAG_FUSED;
     if (flags == WINO_FLAG_FUSED) {
         if ((e = launch_fused(g, (const float *)D, (const float *)U, (float *)Y, s)) != hipSuccess) return hip_fail(e);
         return WINO_OK;
     }
-    if ((e = launch_input_transform(g, D, Vw, s)) != hipSuccess) return hip_fail(e);
+    if (!v_done && (e = launch_input_transform(g, D, Vw, s)) != hipSuccess) return hip_fail(e);
     if ((e = launch_batched_gemm(g, U, Vw, Mw, splits, s)) != hipSuccess)
         return e == hipErrorNotSupported ? (int)WINO_EUNSUPPORTED : hip_fail(e);
     if ((e = launch_output_transform(g, y_dt, Mw, Y, splits, s)) != hipSuccess) return hip_fail(e);

@@ -36,6 +36,8 @@ hipError_t launch_output_transform(const Geo &g, int y_dt, const float *M, void 
 bool fused_eligible(const Geo &g);
 bool fused_preferred(const Geo &g);
 hipError_t launch_fused(const Geo &g, const float *D, const float *U, float *Y, hipStream_t s);
+bool prep_eligible(const Geo &g);
+hipError_t launch_prep(const Geo &g, const float *G, float *U, const float *D, float *V, hipStream_t s);
 bool wgrad_supported(long long N, long long C, long long H, long long W, long long K);
 size_t wgrad_workspace_bytes(int N, int C, int H, int W, int K);
 hipError_t launch_wgrad(int N, int C, int H, int W, int K, const float *D, const float *E, float *dG, void *workspace,
