@@ -278,6 +278,94 @@ __global__ __launch_bounds__(256) void wgrad_output_kernel(const float *__restri
         for (int q = 0; q < 3; ++q) dst[p * 3 + q] = y[p][q];
 }
 
+// Layers with very few channels (the 3-channel first layer): the transforms above would spend
+// almost all their time on the error tensor (16 values written and read back per 4 read) for a
+// handful of products, so the gradient is evaluated directly from its definition instead.  One
+// wavefront takes KB = 4 filters of one image and one of RS row bands; lanes run along 4-pixel
+// segments of the error rows (16-byte loads); the 3 x 6 input window of a segment is loaded once
+// per channel and used for all 4 filters; 4 * 9 * CH running sums per lane are reduced across the
+// wavefront at the end.  The per-(image, band) partial sums are added by
+// wgrad_direct_reduce_kernel in a fixed order.  Needs W % 4 == 0.
+constexpr int WD_KB = 4, WD_RS = 4;
+
+template <int CH>
+__global__ __launch_bounds__(256) void wgrad_direct_kernel(const float *__restrict__ D, const float *__restrict__ E,
+                                                           float *__restrict__ part, int N, int H, int W, int K)
+{
+    const int KG = (K + WD_KB - 1) / WD_KB;
+    int task = blockIdx.x * 4 + (threadIdx.x >> 6);   // ((i * RS + band) * KG + kg)
+    const int lane = threadIdx.x & 63;
+    if (task >= N * WD_RS * KG) return;
+    const int kg = task % KG;
+    task /= KG;
+    const int band = task % WD_RS, i = task / WD_RS;
+    const int rows = (H + WD_RS - 1) / WD_RS;
+    const int x_lo = band * rows, x_hi = min(H, x_lo + rows);
+    const float *Di = D + (size_t)i * CH * H * W;
+    const int W4 = W >> 2, nq = max(0, x_hi - x_lo) * W4;
+    float acc[WD_KB][CH][3][3];
+#pragma unroll
+    for (int f = 0; f < WD_KB; ++f)
+#pragma unroll
+        for (int c = 0; c < CH; ++c)
+#pragma unroll
+            for (int u = 0; u < 3; ++u)
+#pragma unroll
+                for (int v = 0; v < 3; ++v) acc[f][c][u][v] = 0.0f;
+    for (int q = lane; q < nq; q += 64) {
+        const int xr = q / W4, x = x_lo + xr, y = (q - xr * W4) * 4;
+        floatx4_w e[WD_KB];
+#pragma unroll
+        for (int f = 0; f < WD_KB; ++f) {
+            const int k = min(kg * WD_KB + f, K - 1);   // filters past K are computed and dropped
+            e[f] = *reinterpret_cast<const floatx4_w *>(E + (((size_t)i * K + k) * H + x) * W + y);
+        }
+#pragma unroll
+        for (int c = 0; c < CH; ++c)
+#pragma unroll
+            for (int u = 0; u < 3; ++u) {
+                const int xx = x + u - 1;
+                if (xx < 0 || xx >= H) continue;
+                const float *row = Di + ((size_t)c * H + xx) * W + y;
+                const floatx4_w mid = *reinterpret_cast<const floatx4_w *>(row);
+                const float d[6] = {y > 0 ? row[-1] : 0.0f, mid[0], mid[1], mid[2], mid[3], y + 4 < W ? row[4] : 0.0f};
+#pragma unroll
+                for (int f = 0; f < WD_KB; ++f)
+#pragma unroll
+                    for (int v = 0; v < 3; ++v)
+                        acc[f][c][u][v] += e[f][0] * d[v] + e[f][1] * d[v + 1] + e[f][2] * d[v + 2] + e[f][3] * d[v + 3];
+            }
+    }
+    float *dst = part + (size_t)(i * WD_RS + band) * K * CH * 9;
+#pragma unroll
+    for (int f = 0; f < WD_KB; ++f)
+#pragma unroll
+        for (int c = 0; c < CH; ++c)
+#pragma unroll
+            for (int u = 0; u < 3; ++u)
+#pragma unroll
+                for (int v = 0; v < 3; ++v) {
+                    float a = acc[f][c][u][v];
+#pragma unroll
+                    for (int off = 32; off >= 1; off >>= 1) a += __shfl_xor(a, off, 64);
+                    const int k = kg * WD_KB + f;
+                    if (lane == 0 && k < K) dst[((size_t)k * CH + c) * 9 + u * 3 + v] = a;
+                }
+}
+
+// dG[k][c][uv] = sum over images and row bands of part[.][k][c][uv]; one thread per output.
+__global__ __launch_bounds__(256) void wgrad_direct_reduce_kernel(const float *__restrict__ part, float *__restrict__ dG,
+                                                                  int nparts, int KC9)
+{
+    const int o = blockIdx.x * 256 + threadIdx.x;
+    if (o >= KC9) return;
+    float a = 0.0f;
+    for (int i = 0; i < nparts; ++i) a += part[(size_t)i * KC9 + o];
+    dG[o] = a;
+}
+
+static bool wgrad_direct_ok(int C, int W) { return C <= 4 && W % 4 == 0; }
+
 static WgradGeo make_wgeo(int N, int C, int H, int W, int K)
 {
     WgradGeo g;
@@ -312,6 +400,7 @@ bool wgrad_supported(long long N, long long C, long long H, long long W, long lo
 
 size_t wgrad_workspace_bytes(int N, int C, int H, int W, int K)
 {
+    if (wgrad_direct_ok(C, W)) return ((size_t)N * WD_RS * K * C * 9 * 4 + 255) & ~(size_t)255;
     const WgradGeo g = make_wgeo(N, C, H, W, K);
     int bm, bn, shares, nk_split;
     wgrad_shape(g, &bm, &bn, &shares, &nk_split);
@@ -322,6 +411,16 @@ size_t wgrad_workspace_bytes(int N, int C, int H, int W, int K)
 hipError_t launch_wgrad(int N, int C, int H, int W, int K, const float *D, const float *E, float *dG, void *workspace,
                         hipStream_t s)
 {
+    if (wgrad_direct_ok(C, W)) {
+        float *part = (float *)workspace;
+        const dim3 grid((N * WD_RS * ((K + WD_KB - 1) / WD_KB) + 3) / 4), blk(256);
+        if (C == 1) wgrad_direct_kernel<1><<<grid, blk, 0, s>>>(D, E, part, N, H, W, K);
+        else if (C == 2) wgrad_direct_kernel<2><<<grid, blk, 0, s>>>(D, E, part, N, H, W, K);
+        else if (C == 3) wgrad_direct_kernel<3><<<grid, blk, 0, s>>>(D, E, part, N, H, W, K);
+        else wgrad_direct_kernel<4><<<grid, blk, 0, s>>>(D, E, part, N, H, W, K);
+        wgrad_direct_reduce_kernel<<<dim3((K * C * 9 + 255) / 256), blk, 0, s>>>(part, dG, N * WD_RS, K * C * 9);
+        return hipGetLastError();
+    }
     const WgradGeo g = make_wgeo(N, C, H, W, K);
     int bm, bn, shares, nk_split;
     wgrad_shape(g, &bm, &bn, &shares, &nk_split);

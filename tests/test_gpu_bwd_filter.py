@@ -21,7 +21,9 @@ TOL_SMALL, TOL_FULL = 2e-6, 2e-5
 
 @pytest.mark.parametrize("shape", [(2, 16, 12, 12, 24), (1, 19, 13, 29, 70), (3, 33, 14, 14, 65), (1, 3, 9, 9, 8),
                                    (2, 64, 28, 28, 128), (1, 130, 7, 5, 140), (4, 8, 1, 1, 8), (1, 1, 2, 2, 1),
-                                   (5, 40, 33, 31, 200)])
+                                   (5, 40, 33, 31, 200),
+                                   # at most 4 channels and W % 4 == 0: the direct kernel
+                                   (2, 3, 12, 16, 10), (3, 1, 8, 4, 5), (2, 4, 6, 8, 7), (1, 2, 5, 12, 3), (3, 3, 31, 36, 70)])
 def test_bwd_filter_matches_oracle(shape):
     torch, w = require_gpu()
     N, C, H, W, K = shape
@@ -36,7 +38,7 @@ def test_bwd_filter_matches_oracle(shape):
     assert err <= TOL_SMALL
 
 
-@pytest.mark.parametrize("shape", [(2, 8, 16, 20, 12), (3, 5, 7, 9, 33), (1, 32, 15, 15, 32)])
+@pytest.mark.parametrize("shape", [(2, 8, 16, 20, 12), (3, 5, 7, 9, 33), (1, 32, 15, 15, 32), (2, 3, 10, 12, 9)])
 def test_bwd_filter_exact_on_integers(shape):
     """Integer inputs with E a multiple of 4: every transform value and every partial sum is an
     integer below 2^24, so the result must equal the oracle's bit for bit."""
@@ -90,7 +92,7 @@ def test_bwd_filter_rejections():
     assert ei.value.status == w.WINO_EWORKSPACE
 
 
-@pytest.mark.parametrize("layer", [1, 5, 9, 12])
+@pytest.mark.parametrize("layer", [0, 1, 5, 9, 12])
 def test_bwd_filter_full_size_sampled(layer):
     """VGG-16 shapes at N=64, fp32: sampled elements of dG recomputed by the oracle."""
     torch, w = require_gpu()

@@ -75,14 +75,16 @@ def test_argument_validation_without_gpu(L):
     assert L.wino_conv2d_variant(1, 4, 8, 8, 4, 1, 6, 0, 0, 0) == w.FLAG_UNFUSED
     assert L.wino_num_tiles(2, 14, 14, 1, 6) == 2 * 3 * 3
     # filter gradient: fp32 and pad 1 only, workspace and pointers checked
-    need = L.wino_bwd_filter_workspace_bytes(2, 4, 8, 8, 4)
+    need = L.wino_bwd_filter_workspace_bytes(2, 8, 8, 8, 4)
     assert need >= 16 * 32 * 32 * 4 * 3          # W, V (Pb = 32 blocks, 32 padded rows) and one M
-    assert L.wino_conv2d_bwd_filter(2, 4, 8, 8, 4, 1, 0, fake, fake, fake, fake, need - 1, null) == w.WINO_EWORKSPACE
-    assert L.wino_conv2d_bwd_filter(2, 4, 8, 8, 4, 0, 0, fake, fake, fake, fake, need, null) == w.WINO_EUNSUPPORTED
-    assert L.wino_conv2d_bwd_filter(2, 4, 8, 8, 4, 1, 1, fake, fake, fake, fake, need, null) == w.WINO_EUNSUPPORTED
-    assert L.wino_conv2d_bwd_filter(2, 4, 8, 8, 4, 1, 0, fake, null, fake, fake, need, null) == w.WINO_EINVAL
-    assert L.wino_conv2d_bwd_filter(2, 4, 8, 8, 4, 1, 0, fake, fake, odd, fake, need, null) == w.WINO_EINVAL
+    assert L.wino_conv2d_bwd_filter(2, 8, 8, 8, 4, 1, 0, fake, fake, fake, fake, need - 1, null) == w.WINO_EWORKSPACE
+    assert L.wino_conv2d_bwd_filter(2, 8, 8, 8, 4, 0, 0, fake, fake, fake, fake, need, null) == w.WINO_EUNSUPPORTED
+    assert L.wino_conv2d_bwd_filter(2, 8, 8, 8, 4, 1, 1, fake, fake, fake, fake, need, null) == w.WINO_EUNSUPPORTED
+    assert L.wino_conv2d_bwd_filter(2, 8, 8, 8, 4, 1, 0, fake, null, fake, fake, need, null) == w.WINO_EINVAL
+    assert L.wino_conv2d_bwd_filter(2, 8, 8, 8, 4, 1, 0, fake, fake, odd, fake, need, null) == w.WINO_EINVAL
     assert L.wino_conv2d_bwd_filter(2, 0, 8, 8, 4, 1, 0, fake, fake, fake, fake, need, null) == w.WINO_EINVAL
+    # at most 4 channels and W a multiple of 4: evaluated directly, workspace = a few partial gradients per image
+    assert 0 < L.wino_bwd_filter_workspace_bytes(2, 3, 8, 8, 4) < 2 * 8 * 4 * 3 * 9 * 4
     assert L.wino_bwd_filter_workspace_bytes(0, 4, 8, 8, 4) == 0
     # size queries on bad input
     assert L.wino_workspace_bytes(1, 4, 8, 8, 4, 1, 3, 0) == 0
