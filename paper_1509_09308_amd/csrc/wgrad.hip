@@ -7,6 +7,8 @@
 // Stages, each its own kernel: error transform (E -> W[e][k][b]), data transform (D -> V[e][c][b]),
 // the 16 products on fp32 MFMAs with the reduction split over workgroups, and the inverse
 // transform that also adds the partial products.  fp32, stride 1, pad 1.
+#include <stdlib.h>
+
 #include "wino_internal.h"
 
 namespace wino {
@@ -243,6 +245,192 @@ __global__ __launch_bounds__(256) void wgrad_gemm_kernel(const float *__restrict
         }
 }
 
+// The same products with both transforms inside the multiply: W and V never reach memory.  For
+// layers with few filters and channels the stand-alone transforms and the multiply above are all
+// bound by the 4x expansion of E and D into W and V; here a workgroup of 8 wavefronts owns a
+// 64 x 64 block of all 16 M^(e) and walks its share of the error blocks 16 at a time:
+//   1. every thread transforms two horizontally adjacent 2 x 2 error blocks (filter r) and the two
+//      4 x 4 input tiles around them (channel r) from registers loaded during the previous step
+//      -- per row one aligned 16-byte load plus the two outer columns -- and writes the results
+//      to LDS as [e][r][b] (b contiguous, row stride 18: conflict-free 8-byte accesses);
+//   2. after a barrier the raw data of the next 16 blocks is requested, then each wavefront
+//      multiplies: 8 of the 16 components x one 32 x 32 quarter of the block, 64 MFMAs, operands
+//      read as in wgrad_gemm_kernel (one 8-byte read feeds two MFMAs), the 8 accumulators
+//      interleaved so that consecutive MFMAs are independent.
+// Transform and multiply phases alternate rather than overlap; on this chip MFMA and ordinary
+// vector instructions do not overlap anyway, and the global loads (about 3 us of latency for this
+// access pattern: 64 planes x 128 bytes per step) are in flight during phase 2.  Loads are
+// unconditional from clamped (valid) addresses; what falls outside the image, past the last block
+// or past K / C is zeroed afterwards, so the loop has no branches and no divisions.
+// Needs W % 4 == 0 (block pairs never straddle a row; 16-byte loads) and tensors of fewer than
+// 2^31 elements (32-bit offsets).  Partial M per share as above.
+constexpr int WF_BK = 16, WF_LS = WF_BK + 2;
+
+__global__ __launch_bounds__(512) void wgrad_fused_kernel(const float *__restrict__ D, const float *__restrict__ E,
+                                                          float *__restrict__ Mo, WgradGeo g, int tiles_k, int tiles_c,
+                                                          int slabs_per_share)
+{
+    __shared__ float Ws[16 * 64 * WF_LS];
+    __shared__ float Vs[16 * 64 * WF_LS];
+
+    int bid = blockIdx.x;
+    const int kt = bid % tiles_k;
+    bid /= tiles_k;
+    const int ct = bid % tiles_c;
+    const int z = bid / tiles_c;
+    const int tid = threadIdx.x;
+    const int r = tid >> 3, pl = tid & 7;        // row of the block (filter / channel), pair of blocks
+    const int k = kt * 64 + r, c = ct * 64 + r;
+    const int slab_lo = z * slabs_per_share;
+    const int slab_hi = min(slab_lo + slabs_per_share, (g.Pb + WF_BK - 1) / WF_BK);
+
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int st = wave & 3, ch = wave >> 2;
+    const int wm = st >> 1, wn = st & 1;
+    const int li = lane & 31, lh = lane >> 5;
+
+    floatx16_w acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[e][q] = 0.0f;
+
+    // position of this thread's pair of blocks (b, b + 1; b even, so is by)
+    const int kc = min(k, g.K - 1), cc = min(c, g.C - 1);
+    int b_cur = slab_lo * WF_BK + 2 * pl;
+    int by, bx, im;
+    {
+        const int b = min(b_cur, g.Pb - 2);
+        by = b % g.Bw;
+        const int t2 = b / g.Bw;
+        bx = t2 % g.Bh;
+        im = t2 / g.Bh;
+    }
+    floatx4_w er[2], dm[4];    // error rows 2bx, 2bx+1 and input rows 2bx-1 .. 2bx+2, columns 2by .. 2by+3
+    float dl[4], dr[4];        // input columns 2by-1 and 2by+4
+    bool okb, ok1, okl, okr, okx[4];
+    auto load_raw = [&]() {
+        okb = b_cur < g.Pb;
+        ok1 = 2 * bx + 1 < g.H;
+        okl = by > 0;
+        okr = by + 2 < g.Bw;
+        const unsigned eo = (((unsigned)im * g.K + kc) * g.H + 2 * bx) * g.W + 2 * by;
+        er[0] = *reinterpret_cast<const floatx4_w *>(E + eo);
+        er[1] = *reinterpret_cast<const floatx4_w *>(E + eo + (ok1 ? g.W : 0));
+        const unsigned dbase = ((unsigned)im * g.C + cc) * g.H * g.W + 2 * by;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int x = 2 * bx - 1 + p;
+            okx[p] = x >= 0 && x < g.H;
+            const float *row = D + dbase + (unsigned)min(max(x, 0), g.H - 1) * g.W;
+            dm[p] = *reinterpret_cast<const floatx4_w *>(row);
+            dl[p] = *(row - (okl ? 1 : 0));
+            dr[p] = *(row + (okr ? 4 : 3));
+        }
+    };
+    auto advance = [&]() {
+        b_cur += WF_BK;
+        if (b_cur < g.Pb) {          // past the end the position stays on the last valid pair
+            by += WF_BK;
+            while (by >= g.Bw) {
+                by -= g.Bw;
+                if (++bx == g.Bh) {
+                    bx = 0;
+                    ++im;
+                }
+            }
+        }
+    };
+    auto transform_to_lds = [&]() {
+        const bool ke = okb && k < g.K, kd = okb && c < g.C;
+        float t[4][4], o[4], wa[16], wb[16];
+        // w = G e G^T of the two error blocks
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+            float *dst = blk ? wb : wa;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const float col[2] = {ke ? er[0][2 * blk + q] : 0.0f, (ke && ok1) ? er[1][2 * blk + q] : 0.0f};
+                g32_mul(col, o);
+#pragma unroll
+                for (int p = 0; p < 4; ++p) t[p][q] = o[p];
+            }
+#pragma unroll
+            for (int p = 0; p < 4; ++p) g32_mul(t[p], dst + 4 * p);
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            *reinterpret_cast<floatx2_w *>(&Ws[(e * 64 + r) * WF_LS + 2 * pl]) = floatx2_w{wa[e], wb[e]};
+        // v = B^T d B of the two input tiles: columns 2by-1 .. 2by+2 and 2by+1 .. 2by+4
+        float d[4][6];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const bool v = kd && okx[p];
+            d[p][0] = (v && okl) ? dl[p] : 0.0f;
+            d[p][1] = v ? dm[p][0] : 0.0f;
+            d[p][2] = v ? dm[p][1] : 0.0f;
+            d[p][3] = v ? dm[p][2] : 0.0f;
+            d[p][4] = v ? dm[p][3] : 0.0f;
+            d[p][5] = (v && okr) ? dr[p] : 0.0f;
+        }
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+            float *dst = blk ? wb : wa;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float col[4] = {d[0][2 * blk + q], d[1][2 * blk + q], d[2][2 * blk + q], d[3][2 * blk + q]};
+                bt32_mul(col, o);
+#pragma unroll
+                for (int p = 0; p < 4; ++p) t[p][q] = o[p];
+            }
+#pragma unroll
+            for (int p = 0; p < 4; ++p) bt32_mul(t[p], dst + 4 * p);
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            *reinterpret_cast<floatx2_w *>(&Vs[(e * 64 + r) * WF_LS + 2 * pl]) = floatx2_w{wa[e], wb[e]};
+    };
+    const int a_off = (wm * 32 + li) * WF_LS + 2 * lh, b_off = (wn * 32 + li) * WF_LS + 2 * lh;
+    auto multiply = [&]() {
+#pragma unroll
+        for (int t = 0; t < WF_BK / 4; ++t) {
+            floatx2_w a[8], b[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int eo = (ch * 8 + e) * 64 * WF_LS;
+                a[e] = *reinterpret_cast<const floatx2_w *>(&Ws[eo + a_off + 4 * t]);
+                b[e] = *reinterpret_cast<const floatx2_w *>(&Vs[eo + b_off + 4 * t]);
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    acc[e] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e][h], b[e][h], acc[e], 0, 0, 0);
+        }
+    };
+
+    load_raw();
+    for (int slab = slab_lo; slab < slab_hi; ++slab) {
+        transform_to_lds();
+        __syncthreads();
+        advance();
+        load_raw();          // after the last slab this re-reads a valid position and is discarded
+        multiply();
+        __syncthreads();
+    }
+
+    // a share past the end of the blocks still writes its (zero) partial M
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int rt = kt * 64 + wm * 32, ctile = ct * 64 + wn * 32;
+        if (rt < g.Kp && ctile < g.Cq) {
+            float *dst = Mo + (((size_t)z * 16 + ch * 8 + e) * g.Kp + rt + 4 * lh) * g.Cq + ctile + li;
+#pragma unroll
+            for (int q = 0; q < 16; ++q) dst[(size_t)(8 * (q / 4) + (q % 4)) * g.Cq] = acc[e][q];
+        }
+    }
+}
+
 // dG[k][c] = A^T (sum over shares of M[e][k][c]) A; one thread per (k, c), c fastest.
 __global__ __launch_bounds__(256) void wgrad_output_kernel(const float *__restrict__ Mi, float *__restrict__ dG,
                                                            WgradGeo g, int shares)
@@ -392,6 +580,29 @@ static void wgrad_shape(const WgradGeo &g, int *bm, int *bn, int *shares, int *n
     *shares = (nk + *nk_split - 1) / *nk_split;
 }
 
+// The fused kernel is chosen where the stand-alone transforms dominate: few filters and channels
+// (every 64 x 64 block of M repeats both transforms, so their cost grows with K * C).
+static bool wgrad_fused_ok(const WgradGeo &g)
+{
+    const char *tune = getenv("WINO_WGRAD_FUSED");   // tuning only: 0 = never, 1 = whenever possible
+    if (g.W % 4 != 0) return false;
+    if ((long long)g.N * (g.K > g.C ? g.K : g.C) * g.H * g.W >= (1LL << 31)) return false;   // 32-bit offsets
+    if (tune) return tune[0] == '1';
+    return g.K <= 256 && g.C <= 256;   // measured at N=64: faster up to 256 x 256, slower at 512 x 512
+}
+
+static void wgrad_fused_shape(const WgradGeo &g, int *tiles_k, int *tiles_c, int *shares, int *slabs_per_share)
+{
+    *tiles_k = (g.Kp + 63) / 64;
+    *tiles_c = (g.Cq + 63) / 64;
+    const int slabs = (g.Pb + WF_BK - 1) / WF_BK;
+    int want = 512 / (*tiles_k * *tiles_c);   // one workgroup fits a CU at a time: two rounds of 256
+    if (want > slabs / 4) want = slabs / 4;   // at least 4 slabs per share
+    if (want < 1) want = 1;
+    *slabs_per_share = (slabs + want - 1) / want;
+    *shares = (slabs + *slabs_per_share - 1) / *slabs_per_share;
+}
+
 bool wgrad_supported(long long N, long long C, long long H, long long W, long long K)
 {
     const long long Pb = N * ((H + 1) / 2) * ((W + 1) / 2);
@@ -403,8 +614,13 @@ size_t wgrad_workspace_bytes(int N, int C, int H, int W, int K)
     if (wgrad_direct_ok(C, W)) return ((size_t)N * WD_RS * K * C * 9 * 4 + 255) & ~(size_t)255;
     const WgradGeo g = make_wgeo(N, C, H, W, K);
     int bm, bn, shares, nk_split;
-    wgrad_shape(g, &bm, &bn, &shares, &nk_split);
     auto al = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    if (wgrad_fused_ok(g)) {
+        int tk, tc, sps;
+        wgrad_fused_shape(g, &tk, &tc, &shares, &sps);
+        return al((size_t)shares * 16 * g.Kp * g.Cq * 4);
+    }
+    wgrad_shape(g, &bm, &bn, &shares, &nk_split);
     return al((size_t)16 * g.Kp * g.Pbp * 4) + al((size_t)16 * g.Cq * g.Pbp * 4) + al((size_t)shares * 16 * g.Kp * g.Cq * 4);
 }
 
@@ -423,6 +639,14 @@ hipError_t launch_wgrad(int N, int C, int H, int W, int K, const float *D, const
     }
     const WgradGeo g = make_wgeo(N, C, H, W, K);
     int bm, bn, shares, nk_split;
+    if (wgrad_fused_ok(g)) {
+        int tk, tc, sps;
+        wgrad_fused_shape(g, &tk, &tc, &shares, &sps);
+        float *Mw = (float *)workspace;
+        wgrad_fused_kernel<<<dim3((unsigned)(tk * tc * shares)), dim3(512), 0, s>>>(D, E, Mw, g, tk, tc, sps);
+        wgrad_output_kernel<<<dim3((C + 255) / 256, K), dim3(256), 0, s>>>(Mw, dG, g, shares);
+        return hipGetLastError();
+    }
     wgrad_shape(g, &bm, &bn, &shares, &nk_split);
     auto al = [](size_t x) { return (x + 255) & ~(size_t)255; };
     char *ws = (char *)workspace;

@@ -22,6 +22,9 @@ TOL_SMALL, TOL_FULL = 2e-6, 2e-5
 @pytest.mark.parametrize("shape", [(2, 16, 12, 12, 24), (1, 19, 13, 29, 70), (3, 33, 14, 14, 65), (1, 3, 9, 9, 8),
                                    (2, 64, 28, 28, 128), (1, 130, 7, 5, 140), (4, 8, 1, 1, 8), (1, 1, 2, 2, 1),
                                    (5, 40, 33, 31, 200),
+                                   # W % 4 == 0 and at most 256 filters / channels: transforms inside the multiply
+                                   (2, 19, 12, 16, 70), (1, 130, 8, 8, 140), (2, 5, 7, 8, 6), (1, 8, 2, 4, 8),
+                                   (3, 64, 9, 20, 33), (1, 256, 6, 12, 200),
                                    # at most 4 channels and W % 4 == 0: the direct kernel
                                    (2, 3, 12, 16, 10), (3, 1, 8, 4, 5), (2, 4, 6, 8, 7), (1, 2, 5, 12, 3), (3, 3, 31, 36, 70)])
 def test_bwd_filter_matches_oracle(shape):

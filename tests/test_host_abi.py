@@ -76,7 +76,7 @@ def test_argument_validation_without_gpu(L):
     assert L.wino_num_tiles(2, 14, 14, 1, 6) == 2 * 3 * 3
     # filter gradient: fp32 and pad 1 only, workspace and pointers checked
     need = L.wino_bwd_filter_workspace_bytes(2, 8, 8, 8, 4)
-    assert need >= 16 * 32 * 32 * 4 * 3          # W, V (Pb = 32 blocks, 32 padded rows) and one M
+    assert need >= 16 * 32 * 32 * 4              # at least one partial M (16 components, 32 x 32 padded)
     assert L.wino_conv2d_bwd_filter(2, 8, 8, 8, 4, 1, 0, fake, fake, fake, fake, need - 1, null) == w.WINO_EWORKSPACE
     assert L.wino_conv2d_bwd_filter(2, 8, 8, 8, 4, 0, 0, fake, fake, fake, fake, need, null) == w.WINO_EUNSUPPORTED
     assert L.wino_conv2d_bwd_filter(2, 8, 8, 8, 4, 1, 1, fake, fake, fake, fake, need, null) == w.WINO_EUNSUPPORTED
