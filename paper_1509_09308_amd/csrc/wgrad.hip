@@ -431,6 +431,44 @@ __global__ __launch_bounds__(512) void wgrad_fused_kernel(const float *__restric
     }
 }
 
+// First level of the sum over shares when there are many of them: out[zg][i] = sum of in[z][i] over
+// the WR_GROUP shares z of group zg, in share order.  One thread per element and group, so the
+// partial results (up to 134 MB for a 64 x 64 layer with 512 shares) are read by thousands of
+// wavefronts instead of the few that own an output.
+constexpr int WR_GROUP = 16, WR_MIN_SHARES = 33;
+
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restrict__ in, float *__restrict__ out,
+                                                           int nelem4, int shares)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int zg = blockIdx.y;
+    if (i >= nelem4) return;
+    const int z0 = zg * WR_GROUP, z1 = min(z0 + WR_GROUP, shares);
+    const floatx4_w *src = reinterpret_cast<const floatx4_w *>(in);
+    floatx4_w a = src[(size_t)z0 * nelem4 + i];
+    for (int z = z0 + 1; z < z1; ++z) a += src[(size_t)z * nelem4 + i];
+    reinterpret_cast<floatx4_w *>(out)[(size_t)zg * nelem4 + i] = a;
+}
+
+// Reduces `shares` partial arrays of nelem floats at `part` to fewer (when there are more than 32 and
+// nelem % 4 == 0; otherwise nothing is done), using `tmp`
+// (room for ceil(shares / WR_GROUP) arrays).  Returns where the remaining partials are and how many.
+static const float *wgrad_pre_reduce(const float *part, float *tmp, size_t nelem, int *shares, hipStream_t s)
+{
+    if (*shares < WR_MIN_SHARES || nelem % 4 != 0) return part;
+    const int groups = (*shares + WR_GROUP - 1) / WR_GROUP;
+    const int n4 = (int)(nelem / 4);
+    wgrad_reduce_kernel<<<dim3((n4 + 255) / 256, groups), dim3(256), 0, s>>>(part, tmp, n4, *shares);
+    *shares = groups;
+    return tmp;
+}
+
+static size_t wgrad_pre_reduce_bytes(size_t nelem, int shares)
+{
+    if (shares < WR_MIN_SHARES || nelem % 4 != 0) return 0;
+    return (((size_t)((shares + WR_GROUP - 1) / WR_GROUP) * nelem * 4) + 255) & ~(size_t)255;
+}
+
 // dG[k][c] = A^T (sum over shares of M[e][k][c]) A; one thread per (k, c), c fastest.
 __global__ __launch_bounds__(256) void wgrad_output_kernel(const float *__restrict__ Mi, float *__restrict__ dG,
                                                            WgradGeo g, int shares)
@@ -611,17 +649,19 @@ bool wgrad_supported(long long N, long long C, long long H, long long W, long lo
 
 size_t wgrad_workspace_bytes(int N, int C, int H, int W, int K)
 {
-    if (wgrad_direct_ok(C, W)) return ((size_t)N * WD_RS * K * C * 9 * 4 + 255) & ~(size_t)255;
+    if (wgrad_direct_ok(C, W))
+        return (((size_t)N * WD_RS * K * C * 9 * 4 + 255) & ~(size_t)255) + wgrad_pre_reduce_bytes((size_t)K * C * 9, N * WD_RS);
     const WgradGeo g = make_wgeo(N, C, H, W, K);
     int bm, bn, shares, nk_split;
     auto al = [](size_t x) { return (x + 255) & ~(size_t)255; };
     if (wgrad_fused_ok(g)) {
         int tk, tc, sps;
         wgrad_fused_shape(g, &tk, &tc, &shares, &sps);
-        return al((size_t)shares * 16 * g.Kp * g.Cq * 4);
+        return al((size_t)shares * 16 * g.Kp * g.Cq * 4) + wgrad_pre_reduce_bytes((size_t)16 * g.Kp * g.Cq, shares);
     }
     wgrad_shape(g, &bm, &bn, &shares, &nk_split);
-    return al((size_t)16 * g.Kp * g.Pbp * 4) + al((size_t)16 * g.Cq * g.Pbp * 4) + al((size_t)shares * 16 * g.Kp * g.Cq * 4);
+    return al((size_t)16 * g.Kp * g.Pbp * 4) + al((size_t)16 * g.Cq * g.Pbp * 4) + al((size_t)shares * 16 * g.Kp * g.Cq * 4) +
+           wgrad_pre_reduce_bytes((size_t)16 * g.Kp * g.Cq, shares);
 }
 
 hipError_t launch_wgrad(int N, int C, int H, int W, int K, const float *D, const float *E, float *dG, void *workspace,
@@ -634,7 +674,10 @@ hipError_t launch_wgrad(int N, int C, int H, int W, int K, const float *D, const
         else if (C == 2) wgrad_direct_kernel<2><<<grid, blk, 0, s>>>(D, E, part, N, H, W, K);
         else if (C == 3) wgrad_direct_kernel<3><<<grid, blk, 0, s>>>(D, E, part, N, H, W, K);
         else wgrad_direct_kernel<4><<<grid, blk, 0, s>>>(D, E, part, N, H, W, K);
-        wgrad_direct_reduce_kernel<<<dim3((K * C * 9 + 255) / 256), blk, 0, s>>>(part, dG, N * WD_RS, K * C * 9);
+        int nparts = N * WD_RS;
+        float *tmp = (float *)((char *)workspace + (((size_t)nparts * K * C * 9 * 4 + 255) & ~(size_t)255));
+        const float *ps = wgrad_pre_reduce(part, tmp, (size_t)K * C * 9, &nparts, s);
+        wgrad_direct_reduce_kernel<<<dim3((K * C * 9 + 255) / 256), blk, 0, s>>>(ps, dG, nparts, K * C * 9);
         return hipGetLastError();
     }
     const WgradGeo g = make_wgeo(N, C, H, W, K);
@@ -643,8 +686,10 @@ hipError_t launch_wgrad(int N, int C, int H, int W, int K, const float *D, const
         int tk, tc, sps;
         wgrad_fused_shape(g, &tk, &tc, &shares, &sps);
         float *Mw = (float *)workspace;
+        float *tmp = (float *)((char *)workspace + (((size_t)shares * 16 * g.Kp * g.Cq * 4 + 255) & ~(size_t)255));
         wgrad_fused_kernel<<<dim3((unsigned)(tk * tc * shares)), dim3(512), 0, s>>>(D, E, Mw, g, tk, tc, sps);
-        wgrad_output_kernel<<<dim3((C + 255) / 256, K), dim3(256), 0, s>>>(Mw, dG, g, shares);
+        const float *Ms = wgrad_pre_reduce(Mw, tmp, (size_t)16 * g.Kp * g.Cq, &shares, s);
+        wgrad_output_kernel<<<dim3((C + 255) / 256, K), dim3(256), 0, s>>>(Ms, dG, g, shares);
         return hipGetLastError();
     }
     wgrad_shape(g, &bm, &bn, &shares, &nk_split);
@@ -668,7 +713,9 @@ hipError_t launch_wgrad(int N, int C, int H, int W, int K, const float *D, const
         wgrad_gemm_kernel<64, 128><<<grid, block, 0, s>>>(Wt, Vt, Mw, g.Kp, g.Cq, g.Pbp, tiles_m, tiles_n, nk_split);
     else
         wgrad_gemm_kernel<64, 64><<<grid, block, 0, s>>>(Wt, Vt, Mw, g.Kp, g.Cq, g.Pbp, tiles_m, tiles_n, nk_split);
-    wgrad_output_kernel<<<dim3((C + 255) / 256, K), block, 0, s>>>(Mw, dG, g, shares);
+    float *tmp = (float *)((char *)Mw + al((size_t)shares * 16 * g.Kp * g.Cq * 4));
+    const float *Ms = wgrad_pre_reduce(Mw, tmp, (size_t)16 * g.Kp * g.Cq, &shares, s);
+    wgrad_output_kernel<<<dim3((C + 255) / 256, K), block, 0, s>>>(Ms, dG, g, shares);
     return hipGetLastError();
 }
 
