@@ -81,10 +81,36 @@ __global__ __launch_bounds__(256) void direct_conv_kernel(const T *__restrict__ 
 // filter and contiguous across a wavefront.
 typedef float floatx4_dc __attribute__((ext_vector_type(4)));
 
-__global__ __launch_bounds__(256) void direct_conv3x3_f32_kernel(const float *__restrict__ D,
-                                                                 const float *__restrict__ G, float *__restrict__ Y,
-                                                                 int C, int H, int W, int K, int pad, int Ho, int Wo,
-                                                                 int Wq, int CC)
+// four consecutive elements from an address aligned to four elements, widened to fp32
+template <typename T> __device__ __forceinline__ floatx4_dc ld4_d(const T *p);
+template <> __device__ __forceinline__ floatx4_dc ld4_d<float>(const float *p)
+{
+    return *reinterpret_cast<const floatx4_dc *>(p);
+}
+template <> __device__ __forceinline__ floatx4_dc ld4_d<__half>(const __half *p)
+{
+    const uint2 raw = *reinterpret_cast<const uint2 *>(p);
+    const __half2 a = *reinterpret_cast<const __half2 *>(&raw.x), b = *reinterpret_cast<const __half2 *>(&raw.y);
+    return floatx4_dc{__low2float(a), __high2float(a), __low2float(b), __high2float(b)};
+}
+template <typename T> __device__ __forceinline__ void st4_d(T *p, floatx4_dc v);
+template <> __device__ __forceinline__ void st4_d<float>(float *p, floatx4_dc v)
+{
+    *reinterpret_cast<floatx4_dc *>(p) = v;
+}
+template <> __device__ __forceinline__ void st4_d<__half>(__half *p, floatx4_dc v)
+{
+    const __half2 a = __floats2half2_rn(v[0], v[1]), b = __floats2half2_rn(v[2], v[3]);
+    uint2 raw;
+    raw.x = *reinterpret_cast<const unsigned *>(&a);
+    raw.y = *reinterpret_cast<const unsigned *>(&b);
+    *reinterpret_cast<uint2 *>(p) = raw;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void direct_conv3x3_kernel(const T *__restrict__ D, const T *__restrict__ G,
+                                                             T *__restrict__ Y, int C, int H, int W, int K, int pad,
+                                                             int Ho, int Wo, int Wq, int CC)
 {
     __shared__ float gs[DC_LDS_FLOATS];
     const int item = blockIdx.x * 256 + threadIdx.x;   // (output row, group of 4 columns)
@@ -99,39 +125,38 @@ __global__ __launch_bounds__(256) void direct_conv3x3_f32_kernel(const float *__
     for (int p = 0; p < 4; ++p)
 #pragma unroll
         for (int kk = 0; kk < DC_KB; ++kk) acc[p][kk] = 0.0f;
-    const float *Di = D + (size_t)i * C * H * W;
+    const T *Di = D + (size_t)i * C * H * W;
     for (int c0 = 0; c0 < C; c0 += CC) {
         const int cn = min(CC, C - c0);
         __syncthreads();
         for (int idx = threadIdx.x; idx < cn * 9 * DC_KB; idx += 256) {
             const int kk = idx % DC_KB, j = idx / DC_KB;
             const int k = k0 + kk;
-            gs[idx] = (k < K) ? G[((size_t)k * C + c0) * 9 + j] : 0.0f;
+            gs[idx] = (k < K) ? ld_d<T>(G + ((size_t)k * C + c0) * 9 + j) : 0.0f;
         }
         __syncthreads();
         if (!live) continue;
         for (int cc = 0; cc < cn; ++cc) {
-            const float *Dc = Di + (size_t)(c0 + cc) * H * W;
+            const T *Dc = Di + (size_t)(c0 + cc) * H * W;
             float win[3][6];
 #pragma unroll
             for (int u = 0; u < 3; ++u) {
                 const int x = ox + u - pad;
                 const bool rok = x >= 0 && x < H;
-                const float *row = Dc + (size_t)(rok ? x : 0) * W;
+                const T *row = Dc + (size_t)(rok ? x : 0) * W;
                 if (vec_in) {
-                    const floatx4_dc mid = rok ? *reinterpret_cast<const floatx4_dc *>(row + y0 + 1)
-                                               : floatx4_dc{0.f, 0.f, 0.f, 0.f};
-                    win[u][0] = (rok && y0 >= 0) ? row[y0] : 0.0f;
+                    const floatx4_dc mid = rok ? ld4_d<T>(row + y0 + 1) : floatx4_dc{0.f, 0.f, 0.f, 0.f};
+                    win[u][0] = (rok && y0 >= 0) ? ld_d<T>(row + y0) : 0.0f;
                     win[u][1] = mid[0];
                     win[u][2] = mid[1];
                     win[u][3] = mid[2];
                     win[u][4] = mid[3];
-                    win[u][5] = (rok && y0 + 5 < W) ? row[y0 + 5] : 0.0f;
+                    win[u][5] = (rok && y0 + 5 < W) ? ld_d<T>(row + y0 + 5) : 0.0f;
                 } else {
 #pragma unroll
                     for (int q = 0; q < 6; ++q) {
                         const int y = y0 + q;
-                        win[u][q] = (rok && y >= 0 && y < W) ? row[y] : 0.0f;
+                        win[u][q] = (rok && y >= 0 && y < W) ? ld_d<T>(row + y) : 0.0f;
                     }
                 }
             }
@@ -160,13 +185,13 @@ __global__ __launch_bounds__(256) void direct_conv3x3_f32_kernel(const float *__
 #pragma unroll
     for (int kk = 0; kk < DC_KB; ++kk) {
         if (k0 + kk < K) {
-            float *dst = Y + (((size_t)i * K + k0 + kk) * Ho + ox) * Wo + oy;
+            T *dst = Y + (((size_t)i * K + k0 + kk) * Ho + ox) * Wo + oy;
             if (vec_out) {
-                *reinterpret_cast<floatx4_dc *>(dst) = floatx4_dc{acc[0][kk], acc[1][kk], acc[2][kk], acc[3][kk]};
+                st4_d<T>(dst, floatx4_dc{acc[0][kk], acc[1][kk], acc[2][kk], acc[3][kk]});
             } else {
 #pragma unroll
                 for (int p = 0; p < 4; ++p)
-                    if (oy + p < Wo) dst[p] = acc[p][kk];
+                    if (oy + p < Wo) st_d<T>(dst + p, acc[p][kk]);
             }
         }
     }
@@ -181,11 +206,15 @@ hipError_t launch_direct_conv(int N, int C, int H, int W, int K, int R, int S, i
     if (CC > C) CC = C;
     dim3 grid((Ho * Wo + 255) / 256, (K + DC_KB - 1) / DC_KB, N), block(256);
     if (grid.y > 65535 || grid.z > 65535) return hipErrorInvalidValue;
-    if (dt == WINO_F32 && R == 3 && S == 3 && stride == 1) {
+    if (R == 3 && S == 3 && stride == 1) {
         const int Wq = (Wo + 3) / 4;
         dim3 grid3((Ho * Wq + 255) / 256, grid.y, N);
-        direct_conv3x3_f32_kernel<<<grid3, block, 0, s>>>((const float *)D, (const float *)G, (float *)Y, C, H, W, K,
-                                                          pad, Ho, Wo, Wq, CC);
+        if (dt == WINO_F32)
+            direct_conv3x3_kernel<float><<<grid3, block, 0, s>>>((const float *)D, (const float *)G, (float *)Y, C, H, W,
+                                                                 K, pad, Ho, Wo, Wq, CC);
+        else
+            direct_conv3x3_kernel<__half><<<grid3, block, 0, s>>>((const __half *)D, (const __half *)G, (__half *)Y, C,
+                                                                  H, W, K, pad, Ho, Wo, Wq, CC);
         return hipGetLastError();
     }
     if (dt == WINO_F32)

@@ -152,6 +152,26 @@ def test_direct_fallback(shape):
     assert np.array_equal(Yi.astype(np.float64), direct.conv2d_fwd(Di, Gi, pad=pad, stride=stride))
 
 
+@pytest.mark.parametrize("shape", [(1, 3, 20, 20, 8, 3, 3, 1, 1), (2, 3, 17, 23, 5, 3, 3, 1, 1), (2, 5, 12, 16, 33, 3, 3, 0, 1),
+                                   (1, 4, 9, 11, 6, 5, 3, 2, 2), (2, 3, 224, 224, 64, 3, 3, 1, 1)])
+def test_direct_fallback_f16_storage(shape):
+    """fp16 D, G and Y, fp32 accumulation: within one fp16 rounding of the oracle on the same stored values,
+    and exact where the result is representable."""
+    torch, w = require_gpu()
+    N, C, H, W, K, R, S, pad, stride = shape
+    D, G = synth.make_layer(N, C, H, W, K, seed=H + R + 1, R=R, S=S, dtype=np.float16)
+    Y = w.direct_conv2d_fwd(to_gpu(D), to_gpu(G), pad=pad, stride=stride).cpu().numpy()
+    ref = direct.conv2d_fwd(D, G, pad=pad, stride=stride)
+    assert Y.dtype == np.float16 and Y.shape == ref.shape
+    assert rel_err(Y, ref) < 1e-3
+    Di = np.round(D.astype(np.float32) * 2).astype(np.float16)
+    Gi = np.round(G.astype(np.float32) * 8).astype(np.float16)
+    Yi = w.direct_conv2d_fwd(to_gpu(Di), to_gpu(Gi), pad=pad, stride=stride).cpu().numpy()
+    refi = direct.conv2d_fwd(Di, Gi, pad=pad, stride=stride)
+    assert np.abs(refi).max() <= 2048          # integers this small are exact in fp16
+    assert np.array_equal(Yi.astype(np.float64), refi)
+
+
 # ---- fp16 storage (D, G, U, V in fp16; fp32 accumulation; M and Y in fp32) -----------------------
 
 @pytest.mark.parametrize("m", [2, 4])
