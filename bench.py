@@ -176,6 +176,7 @@ def time_stages(torch, w, layers, ws, steps):
                 "filter": 9 * L.K * L.C * s + a2 * L.K * L.C * s,
                 "input": L.N * L.C * L.HW * L.HW * s + a2 * L.C * L.P * s,
                 "output": a2 * L.K * L.P * 4 + L.N * L.K * L.HW * L.HW * 4,
+                "gemm": a2 * (L.K * L.C + L.C * L.P) * s + a2 * L.K * L.P * 4,   # U and V read, M (fp32) written
             }
             tile = "%d, %d" % (128 if Kp >= 128 else 64, 128 if Pp >= 128 else 64)
             st["kernel"] = ("gemm_f32_kernel<%s, 2, 2, 16>" % tile) if L.dt == w.WINO_F32 else ("gemm_f16_kernel<%s>" % tile)
@@ -264,6 +265,34 @@ def time_f6x6(torch, w, layers, layer_ms, steps):
                                           "F(6x6,3x3); context only, not the headline policy"}}
 
 
+def time_graph(torch, w, layers, ws, steps):
+    """The whole step captured once in a HIP graph and replayed: removes the host's launch work, not the
+    GPU's per-kernel start-up and drain.  Replays alternate with eager steps and are compared with them."""
+    refs = [L.Y.clone() for L in layers]
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        run_step(w, layers, ws)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            run_step(w, layers, ws)
+    torch.cuda.synchronize()
+    same = True
+    for _ in range(3):
+        for L in layers:
+            L.Y.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        same = same and all(torch.equal(a, L.Y) for a, L in zip(refs, layers))
+        run_step(w, layers, ws)
+        torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    return {"ms_per_step": (time.perf_counter() - t0) / steps * 1e3, "replays_equal_eager": bool(same)}
+
+
 def cpu_baseline(layers, budget_s=12.0, max_images=32):
     """The fp64 oracle (Eq. (1)) on the host cores over whole images of the same workload:
     image after image through all 13 layers until about `budget_s` seconds have been spent."""
@@ -297,6 +326,9 @@ def main():
     ap.add_argument("--no-stages", action="store_true")
     ap.add_argument("--no-bwd", action="store_true", help="skip the input- and filter-gradient lines")
     ap.add_argument("--no-f6", action="store_true", help="skip the F(6x6,3x3) line")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the batch-1 stack captured in a HIP graph and replayed (every replay is checked "
+                         "against the eager result)")
     ap.add_argument("--probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 1 GiB device copy (counter calibration), then every "
                          "kernel of one step once; prints the algorithmic bytes per kernel and exits")
@@ -383,8 +415,9 @@ def main():
                         hb += st["bytes"][k]
                         hms += st[k]
             rows.append(row)
-            d = dom.setdefault(st["kernel"], {"flops": 0.0, "ms": 0.0, "launches": 0})
+            d = dom.setdefault(st["kernel"], {"flops": 0.0, "ms": 0.0, "launches": 0, "bytes": 0.0})
             d["flops"] += st["gemm_flops"]
+            d["bytes"] += st["bytes"].get("gemm", 0.0) if main == "gemm" else 0.0
             d["ms"] += st[main]
             d["launches"] += 1
         out["stages"] = rows
@@ -399,6 +432,13 @@ def main():
                                "traffic": MEASURED_TRAFFIC.get((out["config"]["workload"], name)), "kernel": name,
                                "launches_per_step": d["launches"], "avg_launch_ms": d["ms"] / d["launches"],
                                "flops_per_launch": d["flops"] / d["launches"]}
+            # a multiply whose flops per byte fall below the machine balance (peak flops / peak bytes) is
+            # bound by HBM, not by the matrix cores: the fp16-storage multiply (fp32 M written out) is
+            if d["bytes"] > 0 and d["flops"] / d["bytes"] < peak * 1e12 / (PEAK["hbm_GBs"] * 1e9):
+                gbs = d["bytes"] / d["ms"] / 1e6
+                out["roofline"].update({"bound": "hbm", "achieved": gbs, "peak": PEAK["hbm_GBs"], "unit": "GB/s",
+                                        "frac": gbs / PEAK["hbm_GBs"], "bytes_per_launch": d["bytes"] / d["launches"],
+                                        "mfma_tflops": ach, "flops_per_byte": d["flops"] / d["bytes"]})
         if hms > 0:
             out["transform_roofline"] = {"bound": "hbm", "achieved": hb / hms / 1e6, "peak": PEAK["hbm_GBs"],
                                          "unit": "GB/s", "frac": hb / hms / 1e6 / PEAK["hbm_GBs"],
@@ -426,6 +466,8 @@ def main():
         f1 = sum(L.flops for L in l1)
         out["n1"] = {"eff_tflops": f1 / s1 / 1e12, "ms_per_step": s1 * 1e3, "images_per_sec": 1.0 / s1,
                      "algorithm": {L.name: ("direct" if L.direct else "F(%dx%d,3x3)" % (L.m, L.m)) for L in l1}}
+        if args.graph:
+            out["n1"]["hip_graph"] = time_graph(torch, w, l1, ws1, max(args.steps, 20))
     print(json.dumps(out))
 
 
