@@ -58,7 +58,8 @@ typedef enum { WINO_F32 = 0, WINO_F16 = 1 } wino_dtype_t;
 #define WINO_FLAG_AUTO 0u
 #define WINO_FLAG_UNFUSED 1u      /* four separate stages exactly as in Algorithm 1 */
 #define WINO_FLAG_FUSED 2u        /* loops 2-4 of Algorithm 1 in one kernel: V and M never reach memory
-                                   * (fp32 F(4x4,3x3) only; WINO_EUNSUPPORTED otherwise) */
+                                   * (F(4x4,3x3) with fp32 Y; fp16 storage needs pad 1 and W % 4 == 0 as well;
+                                   * WINO_EUNSUPPORTED otherwise) */
 
 const char *wino_status_string(int status);
 /* hipError_t of the most recent failing HIP call made by the calling thread (0 if none). */

@@ -23,6 +23,8 @@
 //
 // A workgroup of 8 wavefronts owns FK = 64 filters x FP = 32 tiles:
 // wave = (k half wm) * 4 + (tile group wn) * 2 + (component half h).
+#include <stdlib.h>
+
 #include "wino_internal.h"
 #include "transforms.h"
 
@@ -384,6 +386,7 @@ __global__ __launch_bounds__(512) void fused_f4_kernel(const float *__restrict__
 
 bool fused_eligible(const Geo &g)
 {
+    if (g.dt == WINO_F16) return fused_f16_eligible(g);
     if (g.dt != WINO_F32 || g.m != 4) return false;
     // 32-bit byte offsets into D below the out-of-bounds marker
     const unsigned long long bytes = (unsigned long long)g.N * g.C * g.H * g.W * 4ull;
@@ -396,11 +399,17 @@ bool fused_preferred(const Geo &g)
 {
     if (!fused_eligible(g)) return false;
     const long long blocks = (long long)((g.P + FP - 1) / FP) * ((g.K + FK - 1) / FK);
+    if (g.dt == WINO_F16) {
+        const char *tune = getenv("WINO_FUSED_F16_MAXK");   // tuning only
+        return g.K <= (tune ? atoi(tune) : 128) && blocks >= 512;
+    }
     return g.K <= 128 && blocks >= 512;
 }
 
-hipError_t launch_fused(const Geo &g, const float *D, const float *U, float *Y, hipStream_t s)
+hipError_t launch_fused(const Geo &g, const void *Dv, const void *Uv, float *Y, hipStream_t s)
 {
+    if (g.dt == WINO_F16) return launch_fused_f16(g, Dv, Uv, Y, s);
+    const float *D = (const float *)Dv, *U = (const float *)Uv;
     const int n_pt = (g.P + FP - 1) / FP, n_kb = (g.K + FK - 1) / FK;
     const long long blocks = (long long)n_pt * n_kb;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;

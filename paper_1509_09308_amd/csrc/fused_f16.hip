@@ -1,0 +1,242 @@
+// Loops 2-4 of Algorithm 1 (Lavin & Gray) in one kernel for fp16 storage: F(4x4,3x3), V and M never
+// reach memory (Section 6 describes such a fused kernel for F(2x2,3x3)).  With fp16 operands the
+// multiply is 16 times cheaper than in fp32 while M stays fp32, so the four-stage path of a layer
+// with few filters spends its time writing and re-reading V and above all M; here a workgroup keeps
+// all 36 components of a 64-filter x 32-tile block in registers and the layer costs one read of D
+// and one write of Y.
+//
+// Workgroup = 4 wavefronts owning 32 filters x 32 tiles, small enough in registers and LDS for two
+// workgroups per CU: the phases below alternate inside a workgroup, so a second one is what keeps
+// the memory system busy while the first computes or stores.  Per step of 8 channels:
+//   1. transform phase: every thread unpacks the 6 x 6 fp16 tile of one (tile, channel) pair (per row
+//      one aligned 8-byte load and the two outer columns, requested one step ahead; zeros outside
+//      the image), computes v = B^T (d B) in fp32, rounds once to fp16 and writes the 36 values to
+//      LDS in the operand order of the MFMA, [e][c / 4][tile][c % 4]; the 36 x 32 x 8 transformed filters
+//      of the step are copied from U (same order, [e][c / 8][k][c % 8]) with 16-byte loads;
+//   2. multiply phase: wavefront cg owns components 9 cg .. 9 cg + 8: one v_mfma_f32_32x32x8_f16
+//      per component, both operands one 8-byte LDS read per lane, fp32 accumulation.
+// After the last step the accumulators go through LDS in four pieces of 8 filters, every thread
+// gathers the 36 components of one (filter, tile) pair, applies Y = A^T m A and writes the 4 x 4
+// outputs that are inside the image as 16-byte rows.
+// Needs m = 4, pad = 1, W % 4 == 0 (aligned 8-byte loads and 16-byte stores), fp32 Y.
+#include "wino_internal.h"
+#include "transforms.h"
+
+namespace wino {
+
+typedef float floatx16_h __attribute__((ext_vector_type(16)));
+typedef float floatx4_h __attribute__((ext_vector_type(4)));
+typedef _Float16 halfx4_h __attribute__((ext_vector_type(4)));
+
+constexpr int HF_K = 32, HF_P = 32, HF_C = 8, HF_T = 256;         // filters, tiles, channels per step, threads
+constexpr int HF_U_WORDS = 36 * HF_K;                             // 16-byte words of U per step
+constexpr int HF_V_WORDS = 36 * HF_P;                             // 16-byte words of V per step
+constexpr int HF_M_FLOATS = 36 * 8 * HF_P;                        // one piece of M in the epilogue
+constexpr int HF_LDS_WORDS = 2 * HF_U_WORDS + HF_V_WORDS;           // two filter buffers and one for V
+static_assert(HF_M_FLOATS * 4 <= HF_LDS_WORDS * 16, "the epilogue reuses the operand area");
+static_assert(HF_U_WORDS % 64 == 0, "filters are copied in chunks of one 16-byte word per lane");
+
+#define WINO_H_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+#define WINO_H_GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+
+__device__ __forceinline__ int xcd_group(int bid, int nblocks)
+{
+    // workgroups are dealt to the 8 XCDs round-robin; make logically consecutive blocks (which share
+    // input tiles) share an XCD and its L2
+    const int per = nblocks / 8;
+    if (bid >= per * 8) return bid;
+    return (bid % 8) * per + bid / 8;
+}
+
+__global__ __launch_bounds__(HF_T, 2) void fused_f16_kernel(const __half *__restrict__ D, const uint4 *__restrict__ U,
+                                                        float *__restrict__ Y, Geo g, int n_kb)
+{
+    __shared__ uint4 smem[HF_LDS_WORDS];
+    uint4 *Us = smem;                                               // buffer b at + b * HF_U_WORDS
+    __half *Vs = reinterpret_cast<__half *>(smem + 2 * HF_U_WORDS);
+    const uint4 *Vw = smem + 2 * HF_U_WORDS;
+
+    const int bid = xcd_group(blockIdx.x, gridDim.x);
+    const int kb = bid % n_kb, tb = bid / n_kb;
+    const int k0 = kb * HF_K, b0 = tb * HF_P;
+    const int tid = threadIdx.x;
+
+    // ---- transform-phase role: (tile, channel of the step) ------------------------------------
+    const int tl = tid & 31, cl = tid >> 5;
+    const int b = b0 + tl;
+    const bool tile_ok = b < g.P;
+    int x0 = 0, y0 = 0;
+    const __half *src = D;
+    {
+        const int bb = tile_ok ? b : 0;
+        const int ty = bb % g.Tw;
+        const int t2 = bb / g.Tw;
+        const int tx = t2 % g.Th;
+        const int i = t2 / g.Th;
+        x0 = 4 * tx - 1;
+        y0 = 4 * ty - 1;
+        src = D + (size_t)i * g.C * g.H * g.W;
+    }
+    const size_t plane = (size_t)g.H * g.W;
+
+    // ---- multiply-phase role -------------------------------------------------------------------
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int cg = wave;
+    const int li = lane & 31, lg = lane >> 5;
+    floatx16_h acc[9];
+#pragma unroll
+    for (int e = 0; e < 9; ++e)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[e][r] = 0.0f;
+
+    const int nsteps = g.Cp / HF_C;
+
+    // raw fp16 taps of one tile: per row the four middle columns (8 bytes) and the two outer ones.
+    // They are requested one step ahead: the loads of step s+1 are issued as soon as step s has
+    // unpacked its own, and stay in flight during the transform, the multiply and the next filter copy.
+    uint2 rmid[6];
+    __half rl[6], rr[6];
+    auto load_raw = [&](int step) {
+        const int c = step * HF_C + cl;
+        const __half *pc = src + (size_t)min(c, g.C - 1) * plane;
+#pragma unroll
+        for (int p = 0; p < 6; ++p) {
+            const __half *row = pc + (size_t)min(max(x0 + p, 0), g.H - 1) * g.W + y0;
+            rmid[p] = *reinterpret_cast<const uint2 *>(row + 1);
+            rl[p] = row[y0 >= 0 ? 0 : 1];
+            rr[p] = row[y0 + 5 < g.W ? 5 : 4];
+        }
+    };
+    // Transformed filters of a step, [e][c8 = step][k] -> Us[e * 32 + k]: direct global -> LDS loads of
+    // 16 bytes per lane (no registers), one step ahead into the other buffer.  A wavefront's loads
+    // return in order and the taps of a step are requested after that step's filters, so once a
+    // wavefront has its taps the filters it requested are in LDS; the barrier extends that to all.
+    constexpr int NCH = (HF_U_WORDS / 64 + 3) / 4;   // chunks of 64 words per wavefront
+    unsigned uoff[NCH];                              // word offset of this lane's word in step 0
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+        const int w = min(wave + 4 * j, HF_U_WORDS / 64 - 1) * 64 + lane;
+        uoff[j] = (unsigned)((w / HF_K) * nsteps) * g.Kp + min(k0 + w % HF_K, g.Kp - 1);
+    }
+    auto load_u = [&](int buf, int step) {
+        const uint4 *ub = U + (size_t)step * g.Kp;
+#pragma unroll
+        for (int j = 0; j < NCH; ++j) {
+            const int chunk = wave + 4 * j;
+            if (chunk < HF_U_WORDS / 64)
+                __builtin_amdgcn_global_load_lds(WINO_H_GLB_PTR(ub + uoff[j]),
+                                                 WINO_H_LDS_PTR(Us + buf * HF_U_WORDS + chunk * 64), 16, 0, 0);
+        }
+    };
+    load_u(0, 0);
+    load_raw(0);
+    for (int step = 0; step < nsteps; ++step) {
+        const uint4 *Ub = Us + (step & 1) * HF_U_WORDS;
+        if (step + 1 < nsteps) load_u((step + 1) & 1, step + 1);
+        // 1. one input tile: unpack, transform rows then columns (v = B^T (d B)), round, scatter
+        {
+            const bool ok = tile_ok && step * HF_C + cl < g.C;
+            float t[6][6];
+#pragma unroll
+            for (int p = 0; p < 6; ++p) {
+                const int x = x0 + p;
+                const bool rok = ok && x >= 0 && x < g.H;
+                const __half2 h01 = *reinterpret_cast<const __half2 *>(&rmid[p].x);
+                const __half2 h23 = *reinterpret_cast<const __half2 *>(&rmid[p].y);
+                const float d[6] = {(rok && y0 >= 0) ? __half2float(rl[p]) : 0.0f,
+                                    rok ? __low2float(h01) : 0.0f,
+                                    rok ? __high2float(h01) : 0.0f,
+                                    rok ? __low2float(h23) : 0.0f,
+                                    rok ? __high2float(h23) : 0.0f,
+                                    (rok && y0 + 5 < g.W) ? __half2float(rr[p]) : 0.0f};
+                bt_mul<4>(d, t[p]);
+            }
+            if (step + 1 < nsteps) load_raw(step + 1);
+            __half *dst = Vs + ((size_t)(cl >> 2) * HF_P + tl) * 4 + (cl & 3);   // [e][c / 4][tile][c % 4]
+#pragma unroll
+            for (int q = 0; q < 6; ++q) {
+                const float col[6] = {t[0][q], t[1][q], t[2][q], t[3][q], t[4][q], t[5][q]};
+                float o[6];
+                bt_mul<4>(col, o);
+#pragma unroll
+                for (int p = 0; p < 6; ++p) dst[(size_t)(p * 6 + q) * (HF_P * 8)] = __float2half_rn(o[p]);
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);   // LDS writes done; the global loads stay in flight
+        __builtin_amdgcn_s_barrier();
+        // 2. nine components x (32 filters x 32 tiles x 8 channels); lane (li, lg) feeds channels 4 lg .. 4 lg + 3
+#pragma unroll
+        for (int e = 0; e < 9; ++e) {
+            const int ee = cg * 9 + e;
+            const uint2 ua = reinterpret_cast<const uint2 *>(Ub)[(ee * HF_K + li) * 2 + lg];
+            const uint2 vb = reinterpret_cast<const uint2 *>(Vw)[(ee * 2 + lg) * HF_P + li];
+            acc[e] = __builtin_amdgcn_mfma_f32_32x32x8f16(*reinterpret_cast<const halfx4_h *>(&ua),
+                                                          *reinterpret_cast<const halfx4_h *>(&vb), acc[e], 0, 0, 0);
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __builtin_amdgcn_s_barrier();
+    }
+    __syncthreads();
+
+    // ---- inverse transform: four pieces of 8 filters -------------------------------------------
+    float *Ms = reinterpret_cast<float *>(smem);
+    const int frow = tid >> 5;                 // 0..7: filter row of the piece handled in the gather
+    const int ot = tid & 31;                   // tile of the gather (same tile as in the transform phase)
+    float *ybase = Y;
+    int orow = 0;
+    {
+        const int bb = tile_ok ? b : 0;
+        const int ty = bb % g.Tw;
+        const int t2 = bb / g.Tw;
+        orow = 4 * (t2 % g.Th);
+        ybase = Y + ((size_t)(t2 / g.Th) * g.K * g.Ho + orow) * g.Wo + 4 * ty;
+    }
+    for (int q = 0; q < 4; ++q) {
+        // accumulator register r of lane (li, lg) is filter 8 * (r / 4) + 4 * lg + r % 4, tile li
+#pragma unroll
+        for (int e = 0; e < 9; ++e)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) Ms[((cg * 9 + e) * 8 + 4 * lg + rr) * HF_P + li] = acc[e][4 * q + rr];
+        __syncthreads();
+        const int k = k0 + 8 * q + frow;
+        if (tile_ok && k < g.K) {
+            float m[6][6], tt[4][6], y[4][4];
+#pragma unroll
+            for (int xi = 0; xi < 6; ++xi)
+#pragma unroll
+                for (int nu = 0; nu < 6; ++nu) m[xi][nu] = Ms[((xi * 6 + nu) * 8 + frow) * HF_P + ot];
+#pragma unroll
+            for (int nu = 0; nu < 6; ++nu) {
+                const float col[6] = {m[0][nu], m[1][nu], m[2][nu], m[3][nu], m[4][nu], m[5][nu]};
+                float o[4];
+                at_mul<4>(col, o);
+#pragma unroll
+                for (int p = 0; p < 4; ++p) tt[p][nu] = o[p];
+            }
+#pragma unroll
+            for (int p = 0; p < 4; ++p) at_mul<4>(tt[p], y[p]);
+            float *dst = ybase + (size_t)k * g.Ho * g.Wo;
+#pragma unroll
+            for (int p = 0; p < 4; ++p)
+                if (orow + p < g.Ho)
+                    *reinterpret_cast<floatx4_h *>(dst + (size_t)p * g.Wo) = floatx4_h{y[p][0], y[p][1], y[p][2], y[p][3]};
+        }
+        __syncthreads();
+    }
+}
+
+bool fused_f16_eligible(const Geo &g)
+{
+    return g.dt == WINO_F16 && g.m == 4 && g.pad == 1 && g.W % 4 == 0;
+}
+
+hipError_t launch_fused_f16(const Geo &g, const void *D, const void *U, float *Y, hipStream_t s)
+{
+    const int n_kb = (g.Kp + HF_K - 1) / HF_K;
+    const long long blocks = (long long)((g.P + HF_P - 1) / HF_P) * n_kb;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    fused_f16_kernel<<<dim3((unsigned)blocks), dim3(HF_T), 0, s>>>((const __half *)D, (const uint4 *)U, Y, g, n_kb);
+    return hipGetLastError();
+}
+
+}  // namespace wino

@@ -271,7 +271,7 @@ static int run_layer(const Geo &g, int y_dt, const void *D, const void *G, const
         U = Uw;
     }
     if (flags == WINO_FLAG_FUSED) {
-        if ((e = launch_fused(g, (const float *)D, (const float *)U, (float *)Y, s)) != hipSuccess) return hip_fail(e);
+        if ((e = launch_fused(g, D, U, (float *)Y, s)) != hipSuccess) return hip_fail(e);
         return WINO_OK;
     }
     if (!v_done && (e = launch_input_transform(g, D, Vw, s)) != hipSuccess) return hip_fail(e);

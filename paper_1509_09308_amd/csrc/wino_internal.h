@@ -35,7 +35,9 @@ hipError_t launch_batched_gemm(const Geo &g, const void *U, const void *V, float
 hipError_t launch_output_transform(const Geo &g, int y_dt, const float *M, void *Y, int splits, hipStream_t s);
 bool fused_eligible(const Geo &g);
 bool fused_preferred(const Geo &g);
-hipError_t launch_fused(const Geo &g, const float *D, const float *U, float *Y, hipStream_t s);
+hipError_t launch_fused(const Geo &g, const void *D, const void *U, float *Y, hipStream_t s);
+bool fused_f16_eligible(const Geo &g);
+hipError_t launch_fused_f16(const Geo &g, const void *D, const void *U, float *Y, hipStream_t s);
 bool prep_eligible(const Geo &g);
 hipError_t launch_prep(const Geo &g, const float *G, float *U, const float *D, float *V, hipStream_t s);
 bool wgrad_supported(long long N, long long C, long long H, long long W, long long K);

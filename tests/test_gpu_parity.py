@@ -153,6 +153,39 @@ def test_f16_storage_layers(m, shape):
     assert e <= TOL[("f16", m)]
 
 
+@pytest.mark.parametrize("shape", [(2, 32, 28, 28, 48), (1, 19, 13, 28, 70), (3, 130, 14, 16, 65), (2, 16, 31, 20, 130),
+                                   (1, 8, 4, 4, 8), (2, 64, 56, 56, 64), (1, 3, 17, 12, 5)])
+def test_f16_fused_path_matches_oracle(shape):
+    """fp16 storage, loops 2-4 in one kernel: ragged heights, channel and filter counts that do not fill
+    a step or a block, tiles past the end of the last block."""
+    torch, w = require_gpu()
+    N, C, H, W, K = shape
+    D, G = synth.make_layer(N, C, H, W, K, seed=sum(shape), dtype=np.float16)
+    ref = direct.conv2d_fwd(D, G, pad=1)
+    d, g = to_gpu(D), to_gpu(G)
+    assert w.wino_conv2d_variant(N, C, H, W, K, 1, 4, w.WINO_F16, flags=w.FLAG_FUSED) == w.FLAG_FUSED
+    Yf = w.wino_conv2d_fwd_ex(d, G=g, pad=1, m=4, flags=w.FLAG_FUSED).cpu().numpy()
+    Yu = w.wino_conv2d_fwd_ex(d, G=g, pad=1, m=4, flags=w.FLAG_UNFUSED).cpu().numpy()
+    e = rel_err(Yf, ref)
+    print("fp16 fused %s rel err %.3e (unfused %.3e)" % (shape, e, rel_err(Yu, ref)))
+    assert e <= TOL[("f16", 4)]
+    # same fp16 operands, same fp32 accumulation: the two paths differ only in summation order
+    assert rel_err(Yf, Yu) <= 5e-4   # v = B^T (d B) here, (B^T d) B there: an fp16 rounding of V can flip
+
+
+def test_f16_fused_exact_on_integers():
+    """Small integers and filters scaled by 576 / 4: every fp16 rounding is exact except those of the
+    1/6-type constants; every output position must be the right one."""
+    torch, w = require_gpu()
+    D, G = synth.make_integer_layer(3, 8, 22, 24, 70, seed=9, gscale=144.0, dmax=3, gmax=1)
+    D16, G16 = D.astype(np.float16), G.astype(np.float16)
+    ref = direct.conv2d_fwd(D16, G16, pad=1)
+    Yf = w.wino_conv2d_fwd_ex(to_gpu(D16), G=to_gpu(G16), pad=1, m=4, flags=w.FLAG_FUSED).cpu().numpy()
+    e = rel_err(Yf, ref)
+    print("fp16 fused integer layer rel err %.3e" % e)
+    assert e < 1e-6
+
+
 @pytest.mark.parametrize("layer", [1, 4, 9, 12])
 def test_config5_full_size_sampled(layer):
     """N=32, fp16 storage, F(4x4,3x3) on every layer (ragged at 14x14), benchmark launch shape."""
@@ -212,6 +245,13 @@ def test_fused_flag_rejected_where_unsupported():
     with pytest.raises(w.WinoError) as ei:
         w.wino_conv2d_fwd_ex(to_gpu(D), G=to_gpu(G), pad=1, m=2, flags=w.FLAG_FUSED)
     assert ei.value.status == w.WINO_EUNSUPPORTED
-    with pytest.raises(w.WinoError):
-        w.wino_conv2d_fwd_ex(to_gpu(D.astype(np.float16)), G=to_gpu(G.astype(np.float16)), pad=1, m=4,
-                             flags=w.FLAG_FUSED)
+    # fp16 storage: the one-kernel path needs m = 4, pad = 1 and W % 4 == 0
+    d16, g16 = to_gpu(D.astype(np.float16)), to_gpu(G.astype(np.float16))
+    for kw in (dict(pad=1, m=2), dict(pad=0, m=4)):
+        with pytest.raises(w.WinoError) as ei:
+            w.wino_conv2d_fwd_ex(d16, G=g16, flags=w.FLAG_FUSED, **kw)
+        assert ei.value.status == w.WINO_EUNSUPPORTED
+    D2, G2 = synth.make_layer(1, 8, 8, 10, 8, seed=2, dtype=np.float16)
+    with pytest.raises(w.WinoError) as ei:
+        w.wino_conv2d_fwd_ex(to_gpu(D2), G=to_gpu(G2), pad=1, m=4, flags=w.FLAG_FUSED)
+    assert ei.value.status == w.WINO_EUNSUPPORTED

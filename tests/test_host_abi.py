@@ -180,7 +180,13 @@ def test_variant_query_host_only(L):
     assert w.wino_conv2d_variant(64, 64, 224, 224, 64, 1, 4, flags=w.FLAG_UNFUSED) == w.FLAG_UNFUSED
     assert w.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 4, flags=w.FLAG_FUSED) == w.FLAG_FUSED
     assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 2, 0, 0, w.FLAG_FUSED) == -w.WINO_EUNSUPPORTED
-    assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 4, 1, 0, w.FLAG_FUSED) == -w.WINO_EUNSUPPORTED   # fp16
+    # fp16 storage has a one-kernel path of its own: m = 4, pad = 1, W % 4 == 0, fp32 outputs
+    assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 4, 1, 0, w.FLAG_FUSED) == w.FLAG_FUSED
+    assert L.wino_conv2d_variant(2, 8, 8, 10, 8, 1, 4, 1, 0, w.FLAG_FUSED) == -w.WINO_EUNSUPPORTED
+    assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 0, 4, 1, 0, w.FLAG_FUSED) == -w.WINO_EUNSUPPORTED
+    assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 4, 1, 1, w.FLAG_FUSED) == -w.WINO_EUNSUPPORTED   # fp16 Y
+    assert L.wino_conv2d_variant(32, 64, 224, 224, 64, 1, 4, 1, 0, 0) == w.FLAG_FUSED
+    assert L.wino_conv2d_variant(32, 512, 28, 28, 512, 1, 4, 1, 0, 0) == w.FLAG_UNFUSED
     assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 3, 0, 0, 0) == -w.WINO_EUNSUPPORTED
     assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 4, 0, 0, 7) == -w.WINO_EINVAL
     # inputs of 2 GiB or more need 64-bit tap offsets: not eligible
