@@ -2,6 +2,8 @@
 // points and the whole-layer drivers.  Declarations and contracts are in include/wino.h.
 #include <mutex>
 
+#include <stdlib.h>
+
 #include "wino_internal.h"
 
 using namespace wino;
@@ -259,6 +261,15 @@ static int run_layer(const Geo &g, int y_dt, const void *D, const void *G, const
     hipError_t e;
     if (flags == WINO_FLAG_AUTO && y_dt == WINO_F32 && fused_preferred(g)) flags = WINO_FLAG_FUSED;
     bool v_done = false;
+    {
+        // fp32, filters given untransformed: the two-workgroups-per-CU kernel with its own filter order
+        const char *tune = getenv("WINO_FUSED_PAIR");   // tuning only: 0 = off
+        if (flags == WINO_FLAG_FUSED && U == nullptr && !bwd && fused_pair_eligible(g) && !(tune && tune[0] == '0')) {
+            if ((e = launch_filter_transform_pair(g, (const float *)G, (float *)Uw, s)) != hipSuccess) return hip_fail(e);
+            if ((e = launch_fused_pair(g, (const float *)D, (const float *)Uw, (float *)Y, s)) != hipSuccess) return hip_fail(e);
+            return WINO_OK;
+        }
+    }
     if (U == nullptr) {
         if (!bwd && flags != WINO_FLAG_FUSED && prep_eligible(g)) {
             // filters and input tiles are transformed by one launch
