@@ -136,22 +136,32 @@ def time_stages(torch, w, layers, ws, steps):
         U = w.alloc_u(L.K, L.C, L.m, L.dt)
         st = {"variant": L.variant, "gemm_flops": 2 * a2 * L.K * L.C * L.P}
         if L.variant == w.FLAG_FUSED:
+            # fp32: the call transforms the filters itself (into the channel-pair order its kernel reads), so
+            # the filter transform (a 5-10 us launch) cannot be separated and is inside "fused";
+            # fp16 storage: pre-transformed filters are passed and timed on their own
             acc = {"filter": 0.0, "fused": 0.0}
+            f32 = L.dt == w.WINO_F32
             for it in range(steps + 1):
                 e = [es() for _ in range(3)]
                 e[0].record()
-                w.wino_filter_transform(L.G, L.m, U=U)
+                if not f32:
+                    w.wino_filter_transform(L.G, L.m, U=U)
                 e[1].record()
-                w.wino_conv2d_fwd_ex(L.D, U=U, K=L.K, pad=1, m=L.m, Y=L.Y, workspace=ws, flags=w.FLAG_FUSED)
+                if f32:
+                    w.wino_conv2d_fwd_ex(L.D, G=L.G, pad=1, m=L.m, Y=L.Y, workspace=ws, flags=w.FLAG_FUSED)
+                else:
+                    w.wino_conv2d_fwd_ex(L.D, U=U, K=L.K, pad=1, m=L.m, Y=L.Y, workspace=ws, flags=w.FLAG_FUSED)
                 e[2].record()
                 torch.cuda.synchronize()
                 if it:
                     for j, k in enumerate(("filter", "fused")):
                         acc[k] += e[j].elapsed_time(e[j + 1]) / steps
             st.update(acc)
-            st["kernel"] = "fused_f4_kernel<false, false>"
+            if f32:
+                del st["filter"]
+            st["kernel"] = "fused_pair_kernel" if f32 else "fused_f16_kernel"
             st["bytes"] = {"filter": 9 * L.K * L.C * s + a2 * L.K * L.C * s,
-                           "fused": L.N * L.C * L.HW * L.HW * 4 + a2 * L.K * L.C * 4 + L.N * L.K * L.HW * L.HW * 4}
+                           "fused": L.N * L.C * L.HW * L.HW * s + a2 * L.K * L.C * s + L.N * L.K * L.HW * L.HW * 4}
         else:
             V = w.alloc_v(L.C, L.P, L.m, L.dt)
             M = w.alloc_m(L.K, L.P, L.m)

@@ -36,8 +36,10 @@ static_assert(FB_M_FLOATS <= FB_U_WORDS * 4 + FB_V_FLOATS, "the epilogue reuses 
 #define WINO_P_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 #define WINO_P_GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 
-// u = G g G^T written in the pair order the kernel below copies: U2[e][c / 2][k][c % 2].
-template <int M>
+// u = G g G^T written in the pair order the kernel below copies: U2[e][c / 2][k][c % 2].  K, C, Kp, Cp
+// describe the layer the kernel computes.  BWD: that layer is the input gradient (Section 4.2 of the
+// paper): its filter (k, c) is filter (c, k) of the stored G[C][K][3][3], rotated by 180 degrees.
+template <int M, bool BWD>
 __global__ __launch_bounds__(256) void filter_transform_pair_kernel(const float *__restrict__ G, float *__restrict__ U2,
                                                                     int K, int C, int Kp, int Cp)
 {
@@ -49,7 +51,12 @@ __global__ __launch_bounds__(256) void filter_transform_pair_kernel(const float 
 #pragma unroll
     for (int i = 0; i < 3; ++i)
 #pragma unroll
-        for (int j = 0; j < 3; ++j) g[i][j] = (k < K && c < C) ? G[((size_t)k * C + c) * 9 + i * 3 + j] : 0.0f;
+        for (int j = 0; j < 3; ++j) {
+            float v = 0.0f;
+            if (k < K && c < C)
+                v = BWD ? G[((size_t)c * K + k) * 9 + (2 - i) * 3 + (2 - j)] : G[((size_t)k * C + c) * 9 + i * 3 + j];
+            g[i][j] = v;
+        }
 #pragma unroll
     for (int j = 0; j < 3; ++j) {
         float col[3] = {g[0][j], g[1][j], g[2][j]}, o[A];
@@ -244,10 +251,13 @@ bool fused_pair_eligible(const Geo &g)
            (size_t)36 * (g.Cp / 2) * g.Kp < (1ull << 31);   // 32-bit word offsets into U2
 }
 
-hipError_t launch_filter_transform_pair(const Geo &g, const float *G, float *U2, hipStream_t s)
+hipError_t launch_filter_transform_pair(const Geo &g, const float *G, float *U2, bool bwd, hipStream_t s)
 {
     dim3 grid((g.Kp + 63) / 64, (g.Cp + 3) / 4), block(256);
-    filter_transform_pair_kernel<4><<<grid, block, 0, s>>>(G, U2, g.K, g.C, g.Kp, g.Cp);
+    if (bwd)
+        filter_transform_pair_kernel<4, true><<<grid, block, 0, s>>>(G, U2, g.K, g.C, g.Kp, g.Cp);
+    else
+        filter_transform_pair_kernel<4, false><<<grid, block, 0, s>>>(G, U2, g.K, g.C, g.Kp, g.Cp);
     return hipGetLastError();
 }
 
