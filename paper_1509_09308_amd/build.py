@@ -21,7 +21,10 @@ def sources():
 def build(verbose=False):
     """Always recompiles; returns the path of the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB_PATH] + sources()
+    flags = list(HIPCC_FLAGS)
+    if os.environ.get("WINO_TUNING") == "1":
+        flags.append("-DWINO_TUNING")       # lets WINO_* environment variables override launch choices (sweeps)
+    cmd = [hipcc] + flags + ["-o", LIB_PATH] + sources()
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)

@@ -400,7 +400,7 @@ bool fused_preferred(const Geo &g)
     if (!fused_eligible(g)) return false;
     const long long blocks = (long long)((g.P + FP - 1) / FP) * ((g.K + FK - 1) / FK);
     if (g.dt == WINO_F16) {
-        const char *tune = getenv("WINO_FUSED_F16_MAXK");   // tuning only
+        const char *tune = tuning_env("WINO_FUSED_F16_MAXK");   // tuning only
         return g.K <= (tune ? atoi(tune) : 128) && blocks >= 512;
     }
     return g.K <= 128 && blocks >= 512;

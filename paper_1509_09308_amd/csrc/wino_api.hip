@@ -263,7 +263,7 @@ static int run_layer(const Geo &g, int y_dt, const void *D, const void *G, const
     bool v_done = false;
     {
         // fp32, filters given untransformed: the two-workgroups-per-CU kernel with its own filter order
-        const char *tune = getenv("WINO_FUSED_PAIR");   // tuning only: 0 = off
+        const char *tune = tuning_env("WINO_FUSED_PAIR");   // tuning only: 0 = off
         if (flags == WINO_FLAG_FUSED && U == nullptr && fused_pair_eligible(g) && !(tune && tune[0] == '0')) {
             if ((e = launch_filter_transform_pair(g, (const float *)G, (float *)Uw, bwd, s)) != hipSuccess) return hip_fail(e);
             if ((e = launch_fused_pair(g, (const float *)D, (const float *)Uw, (float *)Y, s)) != hipSuccess) return hip_fail(e);

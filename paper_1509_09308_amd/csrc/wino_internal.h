@@ -1,5 +1,6 @@
 // Internal declarations shared by the kernels and the C-ABI layer of libwino (gfx950 only).
 #pragma once
+#include <stdlib.h>
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <stddef.h>
@@ -8,6 +9,19 @@
 #include "../../include/wino.h"
 
 namespace wino {
+
+// Environment variables that override launch choices exist for tuning sweeps only: they are read only by a
+// library built with -DWINO_TUNING (build.py with WINO_TUNING=1 in the environment); a normal build ignores them.
+inline const char *tuning_env(const char *name)
+{
+#ifdef WINO_TUNING
+    return getenv(name);
+#else
+    (void)name;
+    return nullptr;
+#endif
+}
+
 
 // Problem geometry and the padded extents of the transform-domain buffers.
 struct Geo {

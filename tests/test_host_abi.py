@@ -191,3 +191,13 @@ def test_variant_query_host_only(L):
     assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 4, 0, 0, 7) == -w.WINO_EINVAL
     # inputs of 2 GiB or more need 64-bit tap offsets: not eligible
     assert L.wino_conv2d_variant(256, 64, 224, 224, 64, 1, 4, 0, 0, w.FLAG_FUSED) == -w.WINO_EUNSUPPORTED
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py --gpus N > 1 exits with a message before touching any GPU (this build is single-GPU)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode != 0
+    assert "one GPU" in res.stderr and res.stdout.strip() == ""
