@@ -60,6 +60,25 @@ def test_ragged_and_degenerate_shapes(m, shape):
     assert e <= TOL[("f32", m)]
 
 
+@pytest.mark.parametrize("shape", [(1, 1024, 14, 14, 1024, 1), (2, 768, 9, 23, 40, 1), (1, 48, 7, 250, 1030, 0)])
+def test_large_channel_counts_and_wide_images(shape):
+    """More than 512 channels / filters (several filter blocks, long channel loops) and very wide, short images."""
+    torch, w = require_gpu()
+    N, C, H, W, K, pad = shape
+    D, G = synth.make_layer(N, C, H, W, K, seed=sum(shape))
+    ref = direct.conv2d_fwd(D, G, pad=pad)
+    for m in (2, 4, 6):
+        e = rel_err(_run_full(w, D, G, pad, m), ref)
+        print("large %s m=%d rel err %.3e" % (shape, m, e))
+        assert e <= TOL[("f32", m)]
+    if pad == 1:
+        E = np.random.default_rng(1).standard_normal((N, K, H, W), dtype=np.float32)
+        dD = w.wino_conv2d_bwd_data(to_gpu(E), G=to_gpu(G), pad=1, m=4).cpu().numpy()
+        assert rel_err(dD, direct.conv2d_bwd_data(E, G, H, W, pad=1)) <= TOL[("f32", 4)]
+        dG = w.wino_conv2d_bwd_filter(to_gpu(D), to_gpu(E), pad=1).cpu().numpy()
+        assert rel_err(dG, direct.conv2d_bwd_filter(D, E, pad=1)) <= 2e-6
+
+
 @pytest.mark.parametrize("layer", range(1, 13))
 def test_config3_vgg16_stack_n1(layer):
     """Every Winograd-eligible VGG-16 layer at N=1, fp32, both algorithms, whole output."""
