@@ -60,6 +60,15 @@ typedef enum { WINO_F32 = 0, WINO_F16 = 1 } wino_dtype_t;
 #define WINO_FLAG_FUSED 2u        /* loops 2-4 of Algorithm 1 in one kernel: V and M never reach memory
                                    * (F(4x4,3x3) with fp32 Y; fp16 storage needs pad 1 and W % 4 == 0 as well;
                                    * WINO_EUNSUPPORTED otherwise) */
+#define WINO_FLAG_ONE_LAUNCH 3u   /* all four loops of Algorithm 1 in ONE kernel launch, the filter transform
+                                   * computed inside the kernel (the variant of Section 6 without separately
+                                   * transformed filters): F(2x2,3x3), fp32 D, G and Y, untransformed filters G
+                                   * (U must be NULL); WINO_EUNSUPPORTED otherwise.  Meant for small batches.
+                                   * When the layer has few output blocks the channel sum is shared between
+                                   * workgroups, which meet through arrival counters held inside the library
+                                   * (one set per GPU) and partial outputs in the workspace: two such calls
+                                   * must not run at the same time on one GPU (calls on one stream never do).
+                                   * The result does not depend on the order in which workgroups finish. */
 
 const char *wino_status_string(int status);
 /* hipError_t of the most recent failing HIP call made by the calling thread (0 if none). */
@@ -144,8 +153,9 @@ size_t wino_bwd_filter_workspace_bytes(int N, int C, int H, int W, int K);   /* 
 int wino_conv2d_bwd_filter(int N, int C, int H, int W, int K, int pad, int dt, const void *D, const void *E, void *dG,
                            void *workspace, size_t workspace_bytes, void *stream);
 
-/* Host-side query: the variant wino_conv2d_fwd_ex runs for these arguments -- WINO_FLAG_UNFUSED or
- * WINO_FLAG_FUSED -- when called with `flags` (WINO_FLAG_AUTO resolves to one of the two); a negative
+/* Host-side query: the variant wino_conv2d_fwd_ex runs for these arguments -- WINO_FLAG_UNFUSED,
+ * WINO_FLAG_FUSED or WINO_FLAG_ONE_LAUNCH -- when called with `flags` (WINO_FLAG_AUTO resolves to one of
+ * the first two; WINO_FLAG_ONE_LAUNCH is answered for untransformed filters, G given); a negative
  * wino_status_t (e.g. -WINO_EUNSUPPORTED) if the call would be rejected. */
 int wino_conv2d_variant(int N, int C, int H, int W, int K, int pad, int m, int dt, int y_dt, unsigned flags);
 /* Eq. (1) evaluated directly on the GPU: any R x S filter, stride and padding; for layers the

@@ -14,7 +14,7 @@ from . import build as _build
 
 WINO_OK, WINO_EINVAL, WINO_EUNSUPPORTED, WINO_EWORKSPACE, WINO_EHIP = range(5)
 WINO_F32, WINO_F16 = 0, 1
-FLAG_AUTO, FLAG_UNFUSED, FLAG_FUSED = 0, 1, 2
+FLAG_AUTO, FLAG_UNFUSED, FLAG_FUSED, FLAG_ONE_LAUNCH = 0, 1, 2, 3
 
 _lib = None
 

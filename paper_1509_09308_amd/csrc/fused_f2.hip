@@ -1,0 +1,394 @@
+// All four loops of Algorithm 1 (Lavin & Gray) in ONE launch for F(2x2,3x3), fp32: the filter
+// transform u = G g G^T is computed inside the kernel from the untransformed filters (the variant
+// Section 6 of the paper describes next to the one with pre-transformed filters), so neither U, V
+// nor M ever exist in memory.  Meant for small batches, where a layer is a few microseconds of
+// arithmetic and every extra launch costs as much as the arithmetic itself.
+//
+// Workgroup = 4 wavefronts owning 32 filters x 64 tiles (two blocks of 32) x 16 components and a
+// slice of the channels.  Per step of 8 channels:
+//   1. every thread transforms one filter (k, c) -- 9 loads, 28 flops -- into LDS as
+//      [e][c / 2][k][c % 2], and the 4 x 4 input tiles of one tile and two channels (v = B^T d B,
+//      32 additions each) into LDS as [e][c / 2][tile][c % 2]; the raw values of the next step are
+//      requested before the multiply phase so that they arrive while the MFMAs run;
+//   2. wavefront w owns row xi = w of the transform domain (components 4w .. 4w + 3); lane (i, h)
+//      reads channels 4j + 2h, 4j + 2h + 1 of its filter row and of its two tile columns with one
+//      8-byte read each and feeds v_mfma_f32_32x32x2_f32.
+// After the last step each wavefront applies the row half of Y = A^T m A to its own accumulators
+// (t = m_row A), the four wavefronts exchange t through LDS and every thread finishes the column
+// half for (filter, tile) pairs.
+//
+// Small layers do not have enough (filter block, tile block) pairs to fill the chip, so the channel
+// loop is split over `splits` workgroups.  The inverse transform is linear, so each of them
+// transforms its partial sums and stores 2 x 2 partial outputs to the workspace; the workgroup that
+// arrives last (an atomic ticket per output block) adds the partial outputs in the order of the
+// shares and writes Y, which keeps the result independent of the arrival order.  Nobody waits for
+// anybody: every workgroup stores, takes a ticket and leaves, or finds it is last and finishes.
+#include "wino_internal.h"
+#include "transforms.h"
+
+namespace wino {
+
+typedef float floatx16_t __attribute__((ext_vector_type(16)));
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
+typedef float floatx2_t __attribute__((ext_vector_type(2)));
+
+constexpr int F2_K = 32, F2_P = 64, F2_C = 8, F2_T = 256;     // filters, tiles, channels per step, threads
+constexpr int F2_U_FLOATS = 16 * (F2_C / 2) * F2_K * 2;       // transformed filters of a step
+constexpr int F2_V_FLOATS = 16 * (F2_C / 2) * F2_P * 2;       // transformed tiles of a step
+constexpr int F2_T_FLOATS = 4 * 2 * F2_K * 32;                // epilogue exchange of one tile block
+constexpr int F2_MAX_BLOCKS = 4096;                           // output blocks a split launch may have
+static_assert(F2_T_FLOATS <= F2_U_FLOATS + F2_V_FLOATS, "the epilogue reuses the operand area");
+
+// Arrival counters of the output blocks of a split launch.  Zero when the library is loaded; the
+// workgroup that finishes a block sets its counter back to zero, so every launch starts from zero.
+// Two split launches that overlap on one GPU (different streams) would share them: see wino.h.
+static __device__ unsigned int f2_tickets[F2_MAX_BLOCKS];
+
+__device__ __forceinline__ void f2_tile(const Geo &g, int b, int *img, int *tx, int *ty)
+{
+    *ty = b % g.Tw;
+    const int t2 = b / g.Tw;
+    *tx = t2 % g.Th;
+    *img = t2 / g.Th;
+}
+
+// Partial outputs travel between workgroups, which may sit on different XCDs with separate L2
+// caches.  They are written and read with agent-scope atomic accesses (relaxed, 8 bytes): such a
+// store goes through to the level all XCDs share and such a load reads from there, so the
+// hand-over needs no write-back or invalidation of a whole L2, which an agent-scope fence costs
+// on this chip (several hundred nanoseconds per workgroup, serialised).  Order comes from the
+// counters of the wavefront: the stores have completed before the barrier that precedes the
+// ticket, and the loads are issued after the barrier that follows it.
+__device__ __forceinline__ void f2_st_agent(float *p, float a, float b)
+{
+    const floatx2_t v = {a, b};
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), __builtin_bit_cast(unsigned long long, v),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ floatx2_t f2_ld_agent(const float *p)
+{
+    const unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+    return __builtin_bit_cast(floatx2_t, u);
+}
+
+// Writes the rows and columns of one 2 x 2 output that are inside the image.
+__device__ __forceinline__ void f2_store(const Geo &g, float *Y, int k, int b, floatx4_t y)
+{
+    int img, tx, ty;
+    f2_tile(g, b, &img, &tx, &ty);
+    float *dst = Y + (((size_t)img * g.K + k) * g.Ho + 2 * tx) * g.Wo + 2 * ty;
+    const bool row1 = 2 * tx + 1 < g.Ho, col1 = 2 * ty + 1 < g.Wo;
+    if (col1 && (g.Wo & 1) == 0) {
+        *reinterpret_cast<floatx2_t *>(dst) = floatx2_t{y[0], y[1]};
+        if (row1) *reinterpret_cast<floatx2_t *>(dst + g.Wo) = floatx2_t{y[2], y[3]};
+    } else {
+        dst[0] = y[0];
+        if (col1) dst[1] = y[1];
+        if (row1) {
+            dst[g.Wo] = y[2];
+            if (col1) dst[g.Wo + 1] = y[3];
+        }
+    }
+}
+
+// Barrier that orders LDS traffic only: global loads requested earlier stay in flight across it
+// (__syncthreads() would wait for them too and undo the prefetch).
+__device__ __forceinline__ void f2_lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+struct F2Raw {
+    float in[2][16];    // 4 x 4 taps of one tile in two channels
+    float g[9];         // one 3 x 3 filter
+};
+
+// BWD: the layer is the input gradient (Section 4.2 of the paper): its filter (k, c) is filter
+// (c, k) of the stored G[C][K][3][3], rotated by 180 degrees.
+// One workgroup per CU (up to 512 registers per lane): the raw values of three steps are in flight
+// or waiting in registers, which covers the memory latency of a batch-1 layer (2 - 3 us, three
+// multiply phases long).
+template <bool BWD>
+__global__ __launch_bounds__(F2_T, 1) void fused_f2_kernel(const float *__restrict__ D, const float *__restrict__ G,
+                                                           float *Y, float *part, Geo g, int n_kb, int n_tb,
+                                                           int splits, int steps_per_split)
+{
+    __shared__ float smem[F2_U_FLOATS + F2_V_FLOATS];
+    __shared__ int s_last;
+    float *Us = smem;
+    float *Vs = smem + F2_U_FLOATS;
+
+    const int bid = blockIdx.x;
+    const int kb = bid % n_kb;
+    const int rest = bid / n_kb;
+    const int sp = rest % splits, tb = rest / splits;
+    const int k0 = kb * F2_K, b0 = tb * F2_P;
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int nsteps = (g.C + F2_C - 1) / F2_C;
+    const int step_lo = sp * steps_per_split;
+    const int step_hi = min(step_lo + steps_per_split, nsteps);
+    const int nblk = (g.P - b0 > 32) ? 2 : 1;          // tile blocks of this workgroup that hold tiles
+
+    // ---- transform-phase roles -----------------------------------------------------------------
+    // input: tile `lane`, channels 2 wave and 2 wave + 1 of the step.  A tap is read from
+    // (channel plane, the same for the whole wavefront) + toff (element offset of the lane: image,
+    // clamped row and column); taps outside the image are masked to zero afterwards.
+    const bool tile_ok = b0 + lane < g.P;
+    unsigned toff[16];
+    unsigned tmask = 0;                                 // bit 4p + j: tap (p, j) is inside the image
+    {
+        int img, tx, ty;
+        f2_tile(g, tile_ok ? b0 + lane : 0, &img, &tx, &ty);
+        const int x0 = 2 * tx - g.pad, y0 = 2 * ty - g.pad;
+        const unsigned ibase = (unsigned)img * (unsigned)g.C * (unsigned)(g.H * g.W);
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                toff[4 * p + j] = ibase + (unsigned)(min(max(x0 + p, 0), g.H - 1) * g.W + min(max(y0 + j, 0), g.W - 1));
+                if (tile_ok && x0 + p >= 0 && x0 + p < g.H && y0 + j >= 0 && y0 + j < g.W) tmask |= 1u << (4 * p + j);
+            }
+    }
+    const size_t plane = (size_t)g.H * g.W;
+    // filter: filter kk of the block, channel cc of the step; goff is the lane's element offset from
+    // the first filter of the step (the last step clamps channels past the end)
+    const int kk = tid >> 3, cc = tid & 7;
+    const bool k_ok = k0 + kk < g.K;
+    const int kc = min(k0 + kk, g.K - 1);
+    const int cc_last = min(cc, g.C - 1 - (nsteps - 1) * F2_C);
+    const unsigned goff = BWD ? (unsigned)(cc * g.K + kc) * 9u : (unsigned)(kc * g.C + cc) * 9u;
+    const unsigned goff_last = BWD ? (unsigned)(cc_last * g.K + kc) * 9u : (unsigned)(kc * g.C + cc_last) * 9u;
+    const size_t gstep = BWD ? (size_t)F2_C * g.K * 9 : (size_t)F2_C * 9;
+
+    auto load_raw = [&](F2Raw &r, int step) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const float *pc = D + (size_t)min(step * F2_C + 2 * wave + h, g.C - 1) * plane;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) r.in[h][i] = pc[toff[i]];
+        }
+        const float *pg = G + (size_t)step * gstep;
+        const unsigned go = (step == nsteps - 1) ? goff_last : goff;
+#pragma unroll
+        for (int j = 0; j < 9; ++j) r.g[j] = pg[go + (BWD ? 8 - j : j)];
+    };
+    auto transform_raw = [&](const F2Raw &r, int step) {
+        // v = B^T d B of two channels, stored as channel pairs
+        float v[2][16];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const bool c_ok = step * F2_C + 2 * wave + h < g.C;
+            const unsigned mask = c_ok ? tmask : 0u;
+            float t[4][4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float col[4], o[4];
+#pragma unroll
+                for (int p = 0; p < 4; ++p) col[p] = ((mask >> (4 * p + j)) & 1u) ? r.in[h][4 * p + j] : 0.0f;
+                bt_mul<2>(col, o);
+#pragma unroll
+                for (int p = 0; p < 4; ++p) t[p][j] = o[p];
+            }
+#pragma unroll
+            for (int p = 0; p < 4; ++p) bt_mul<2>(t[p], &v[h][4 * p]);
+        }
+        float *vd = Vs + ((size_t)wave * F2_P + lane) * 2;
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            *reinterpret_cast<floatx2_t *>(vd + (size_t)e * (4 * F2_P * 2)) = floatx2_t{v[0][e], v[1][e]};
+        // u = G g G^T of one filter
+        const bool f_ok = k_ok && step * F2_C + cc < g.C;
+        float t[4][3], u[4][4];
+#pragma unroll
+        for (int j = 0; j < 3; ++j) {
+            const float col[3] = {f_ok ? r.g[j] : 0.0f, f_ok ? r.g[3 + j] : 0.0f, f_ok ? r.g[6 + j] : 0.0f};
+            float o[4];
+            g_mul<2>(col, o);
+#pragma unroll
+            for (int p = 0; p < 4; ++p) t[p][j] = o[p];
+        }
+#pragma unroll
+        for (int p = 0; p < 4; ++p) g_mul<2>(t[p], u[p]);
+        float *ud = Us + ((size_t)(cc >> 1) * F2_K + kk) * 2 + (cc & 1);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) ud[(size_t)e * (4 * F2_K * 2)] = u[e >> 2][e & 3];
+    };
+
+    // ---- multiply-phase role ---------------------------------------------------------------------
+    const int li = lane & 31, lh = lane >> 5;
+    floatx16_t acc[4][2];
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[e][q][r] = 0.0f;
+
+    auto multiply = [&]() {
+        // both tile blocks always: a block without tiles holds zeros and costs no extra time, since
+        // other workgroups of the launch multiply two blocks anyway
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int comp = wave * 4 + e;
+            const float *ua = Us + (size_t)comp * (4 * F2_K * 2) + (lh * F2_K + li) * 2;
+            const float *va = Vs + (size_t)comp * (4 * F2_P * 2) + (lh * F2_P + li) * 2;
+            floatx2_t a[2], bl[2], bh[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                a[j] = *reinterpret_cast<const floatx2_t *>(ua + j * (2 * F2_K * 2));
+                bl[j] = *reinterpret_cast<const floatx2_t *>(va + j * (2 * F2_P * 2));
+                bh[j] = *reinterpret_cast<const floatx2_t *>(va + j * (2 * F2_P * 2) + 32 * 2);
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    acc[e][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j][h], bl[j][h], acc[e][0], 0, 0, 0);
+                    acc[e][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j][h], bh[j][h], acc[e][1], 0, 0, 0);
+                }
+        }
+    };
+    // one step with the raw values in `r`; afterwards `r` is refilled for three steps later
+    auto stage = [&](F2Raw &r, int step) {
+        transform_raw(r, step);
+        f2_lds_barrier();
+        if (step + 3 < step_hi) load_raw(r, step + 3);
+        multiply();
+        f2_lds_barrier();
+    };
+
+    F2Raw r0, r1, r2;
+    load_raw(r0, step_lo);
+    if (step_lo + 1 < step_hi) load_raw(r1, step_lo + 1);
+    if (step_lo + 2 < step_hi) load_raw(r2, step_lo + 2);
+    for (int step = step_lo;;) {
+        stage(r0, step);
+        if (++step >= step_hi) break;
+        stage(r1, step);
+        if (++step >= step_hi) break;
+        stage(r2, step);
+        if (++step >= step_hi) break;
+    }
+
+    // ---- inverse transform -----------------------------------------------------------------------
+    // Accumulator register r of lane (li, lh) is filter 8 (r / 4) + 4 lh + r % 4, tile li of the block.
+    float *Ts = smem;                           // [xi][q][filter 32][tile 32]
+    const int ot = tid & 31, okq = tid >> 5;
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk) {
+        if (blk == nblk) break;               // the same for the whole workgroup
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float mrow[4] = {acc[0][blk][r], acc[1][blk][r], acc[2][blk][r], acc[3][blk][r]};
+            float t[2];
+            at_mul<2>(mrow, t);
+            const int kr = 8 * (r >> 2) + 4 * lh + (r & 3);
+            Ts[((wave * 2 + 0) * F2_K + kr) * 32 + li] = t[0];
+            Ts[((wave * 2 + 1) * F2_K + kr) * 32 + li] = t[1];
+        }
+        __syncthreads();
+        const int b = b0 + blk * 32 + ot;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int kr = okq + 8 * i;
+            floatx4_t y;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const float col[4] = {Ts[((0 * 2 + q) * F2_K + kr) * 32 + ot], Ts[((1 * 2 + q) * F2_K + kr) * 32 + ot],
+                                      Ts[((2 * 2 + q) * F2_K + kr) * 32 + ot], Ts[((3 * 2 + q) * F2_K + kr) * 32 + ot]};
+                float o[2];
+                at_mul<2>(col, o);
+                y[q] = o[0];
+                y[2 + q] = o[1];
+            }
+            if (splits == 1) {
+                if (b < g.P && k0 + kr < g.K) f2_store(g, Y, k0 + kr, b, y);
+            } else if (b < g.P && k0 + kr < g.K) {
+                const size_t blockno = ((size_t)sp * n_tb + tb) * n_kb + kb;
+                float *dst = part + ((blockno * F2_K + kr) * F2_P + blk * 32 + ot) * 4;
+                f2_st_agent(dst, y[0], y[1]);
+                f2_st_agent(dst + 2, y[2], y[3]);
+            }
+        }
+        __syncthreads();
+    }
+    if (splits == 1) return;
+
+    // ---- the last share to arrive adds the partial outputs ---------------------------------------
+    __syncthreads();                          // every wavefront has waited for its stores
+    if (tid == 0)
+        s_last = __hip_atomic_fetch_add(&f2_tickets[tb * n_kb + kb], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                 (unsigned)(splits - 1);
+    __syncthreads();
+    if (!s_last) return;
+    for (int idx = tid; idx < F2_K * 32 * nblk; idx += F2_T) {
+        const int tile = idx % (32 * nblk), kr = idx / (32 * nblk);
+        const int b = b0 + tile;
+        if (b >= g.P || k0 + kr >= g.K) continue;
+        const size_t sstride = (size_t)n_tb * n_kb * F2_K * F2_P * 4;
+        const float *ps = part + ((((size_t)tb * n_kb + kb) * F2_K + kr) * F2_P + tile) * 4;
+        floatx4_t y = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int s0 = 0; s0 < splits; s0 += 8) {          // eight shares in flight, added in order
+            floatx2_t lo[8], hi[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (s0 + u < splits) {
+                    lo[u] = f2_ld_agent(ps + (size_t)(s0 + u) * sstride);
+                    hi[u] = f2_ld_agent(ps + (size_t)(s0 + u) * sstride + 2);
+                }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (s0 + u < splits) y += floatx4_t{lo[u][0], lo[u][1], hi[u][0], hi[u][1]};
+        }
+        f2_store(g, Y, k0 + kr, b, y);
+    }
+    if (tid == 0) __hip_atomic_store(&f2_tickets[tb * n_kb + kb], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+bool fused_f2_eligible(const Geo &g)
+{
+    // 32-bit element offsets into D and G; the grid holds at most 2^31 - 1 workgroups
+    return g.dt == WINO_F32 && g.m == 2 && (long long)g.N * g.C * g.H * g.W < (1LL << 31) &&
+           (long long)g.K * g.C * 9 < (1LL << 31) &&
+           (long long)(g.Kp / F2_K) * ((g.P + F2_P - 1) / F2_P) <= 0x3fffffffLL;
+}
+
+// Channel shares: enough workgroups for two per CU where the channel loop allows it, every share at
+// least one step, output blocks within the ticket array, partial outputs within the workspace.
+static void f2_plan(const Geo &g, size_t workspace_bytes, int *splits, int *per)
+{
+    const long long base = (long long)(g.Kp / F2_K) * ((g.P + F2_P - 1) / F2_P);
+    const int nsteps = (g.C + F2_C - 1) / F2_C;
+    long long s = 1;
+    if (base < 256 && base <= F2_MAX_BLOCKS) s = (512 + base - 1) / base;
+    if (const char *t = tuning_env("WINO_F2_SPLITS")) s = atoi(t);     // tuning only
+    const long long fit = (long long)(workspace_bytes / ((size_t)base * F2_K * F2_P * 4 * sizeof(float)));
+    if (s > fit) s = fit;
+    if (s > nsteps) s = nsteps;
+    if (s < 2 || base > F2_MAX_BLOCKS) s = 1;
+    *per = (int)((nsteps + s - 1) / s);
+    *splits = (nsteps + *per - 1) / *per;
+}
+
+hipError_t launch_fused_f2(const Geo &g, const float *D, const float *G, float *Y, void *workspace,
+                           size_t workspace_bytes, bool bwd, hipStream_t s)
+{
+    const int n_kb = g.Kp / F2_K, n_tb = (g.P + F2_P - 1) / F2_P;
+    int splits, per;
+    f2_plan(g, workspace_bytes, &splits, &per);
+    const long long blocks = (long long)n_kb * n_tb * splits;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (bwd)
+        fused_f2_kernel<true><<<dim3((unsigned)blocks), dim3(F2_T), 0, s>>>(D, G, Y, (float *)workspace, g, n_kb, n_tb,
+                                                                            splits, per);
+    else
+        fused_f2_kernel<false><<<dim3((unsigned)blocks), dim3(F2_T), 0, s>>>(D, G, Y, (float *)workspace, g, n_kb, n_tb,
+                                                                             splits, per);
+    return hipGetLastError();
+}
+
+}  // namespace wino

@@ -236,7 +236,9 @@ int wino_conv2d_variant(int N, int C, int H, int W, int K, int pad, int m, int d
     Geo g;
     const int st = make_geo(N, C, H, W, K, pad, m, dt, &g);
     if (st != WINO_OK) return -st;
-    if (bad_dtype(y_dt) || flags > WINO_FLAG_FUSED) return -WINO_EINVAL;
+    if (bad_dtype(y_dt) || flags > WINO_FLAG_ONE_LAUNCH) return -WINO_EINVAL;
+    if (flags == WINO_FLAG_ONE_LAUNCH)
+        return (fused_f2_eligible(g) && y_dt == WINO_F32) ? (int)WINO_FLAG_ONE_LAUNCH : -WINO_EUNSUPPORTED;
     if (flags == WINO_FLAG_FUSED) return (fused_eligible(g) && y_dt == WINO_F32) ? (int)WINO_FLAG_FUSED : -WINO_EUNSUPPORTED;
     if (flags == WINO_FLAG_AUTO && y_dt == WINO_F32 && fused_preferred(g)) return WINO_FLAG_FUSED;
     return WINO_FLAG_UNFUSED;
@@ -248,8 +250,10 @@ static int run_layer(const Geo &g, int y_dt, const void *D, const void *G, const
                      size_t workspace_bytes, unsigned flags, bool bwd, hipStream_t s)
 {
     if (bad_dtype(y_dt)) return WINO_EINVAL;
-    if (flags > WINO_FLAG_FUSED) return WINO_EINVAL;
+    if (flags > WINO_FLAG_ONE_LAUNCH) return WINO_EINVAL;
     if (flags == WINO_FLAG_FUSED && (!fused_eligible(g) || y_dt != WINO_F32)) return WINO_EUNSUPPORTED;
+    if (flags == WINO_FLAG_ONE_LAUNCH && (!fused_f2_eligible(g) || y_dt != WINO_F32 || U != nullptr))
+        return WINO_EUNSUPPORTED;
     if (bad_ptr(D) || bad_ptr(Y) || bad_ptr(workspace)) return WINO_EINVAL;
     if (U == nullptr ? bad_ptr(G) : !aligned16(U)) return WINO_EINVAL;
     const int splits = gemm_splits(g);
@@ -259,6 +263,10 @@ static int run_layer(const Geo &g, int y_dt, const void *D, const void *G, const
     void *Uw = ws, *Vw = ws + ub;
     float *Mw = (float *)(ws + ub + vb);
     hipError_t e;
+    if (flags == WINO_FLAG_ONE_LAUNCH) {
+        e = launch_fused_f2(g, (const float *)D, (const float *)G, (float *)Y, workspace, workspace_bytes, bwd, s);
+        return e == hipSuccess ? WINO_OK : hip_fail(e);
+    }
     if (flags == WINO_FLAG_AUTO && y_dt == WINO_F32 && fused_preferred(g)) flags = WINO_FLAG_FUSED;
     bool v_done = false;
     {

@@ -55,6 +55,9 @@ bool fused_pair_eligible(const Geo &g);
 hipError_t launch_filter_transform_pair(const Geo &g, const float *G, float *U2, bool bwd, hipStream_t s);
 hipError_t launch_fused_pair(const Geo &g, const float *D, const float *U2, float *Y, hipStream_t s);
 hipError_t launch_fused_f16(const Geo &g, const void *D, const void *U, float *Y, hipStream_t s);
+bool fused_f2_eligible(const Geo &g);
+hipError_t launch_fused_f2(const Geo &g, const float *D, const float *G, float *Y, void *workspace,
+                           size_t workspace_bytes, bool bwd, hipStream_t s);
 bool prep_eligible(const Geo &g);
 hipError_t launch_prep(const Geo &g, const float *G, float *U, const float *D, float *V, hipStream_t s);
 bool wgrad_supported(long long N, long long C, long long H, long long W, long long K);
