@@ -275,6 +275,30 @@ def time_f6x6(torch, w, layers, layer_ms, steps):
                                           "F(6x6,3x3); context only, not the headline policy"}}
 
 
+def time_one_launch(torch, w, layers, steps, warmup):
+    """The batch-1 stack with every Winograd layer as ONE kernel launch: F(2x2,3x3) with the filter
+    transform inside the kernel (Section 6 of the paper, the variant without separately transformed
+    filters); conv1.1 stays direct."""
+    ws = torch.empty(max(w.wino_workspace_bytes(L.N, L.C, L.HW, L.HW, L.K, 1, 2, L.dt) for L in layers if not L.direct),
+                     dtype=torch.uint8, device="cuda")
+
+    def step():
+        for L in layers:
+            if L.direct:
+                w.direct_conv2d_fwd(L.D, L.G, pad=1, Y=L.Y)
+            else:
+                w.wino_conv2d_fwd_ex(L.D, G=L.G, pad=1, m=2, Y=L.Y, workspace=ws, flags=w.FLAG_ONE_LAUNCH)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    t = (time.perf_counter() - t0) / steps
+    return {"ms_per_step": t * 1e3, "eff_tflops": sum(L.flops for L in layers) / t / 1e12, "launches_per_step": len(layers)}
+
+
 def time_graph(torch, w, layers, ws, steps):
     """The whole step captured once in a HIP graph and replayed: removes the host's launch work, not the
     GPU's per-kernel start-up and drain.  Replays alternate with eager steps and are compared with them."""
@@ -476,6 +500,8 @@ def main():
         f1 = sum(L.flops for L in l1)
         out["n1"] = {"eff_tflops": f1 / s1 / 1e12, "ms_per_step": s1 * 1e3, "images_per_sec": 1.0 / s1,
                      "algorithm": {L.name: ("direct" if L.direct else "F(%dx%d,3x3)" % (L.m, L.m)) for L in l1}}
+        if args.dtype == "f32":
+            out["n1"]["one_launch_per_layer"] = time_one_launch(torch, w, l1, max(args.steps, 20), max(args.warmup, 5))
         if args.graph:
             out["n1"]["hip_graph"] = time_graph(torch, w, l1, ws1, max(args.steps, 20))
     print(json.dumps(out))

@@ -108,11 +108,10 @@ struct F2Raw {
 
 // BWD: the layer is the input gradient (Section 4.2 of the paper): its filter (k, c) is filter
 // (c, k) of the stored G[C][K][3][3], rotated by 180 degrees.
-// One workgroup per CU (up to 512 registers per lane): the raw values of three steps are in flight
-// or waiting in registers, which covers the memory latency of a batch-1 layer (2 - 3 us, three
-// multiply phases long).
+// Two workgroups per CU (at most 256 registers per lane), so that one can multiply while the other
+// waits for memory or for its barrier.
 template <bool BWD>
-__global__ __launch_bounds__(F2_T, 1) void fused_f2_kernel(const float *__restrict__ D, const float *__restrict__ G,
+__global__ __launch_bounds__(F2_T, 2) void fused_f2_kernel(const float *__restrict__ D, const float *__restrict__ G,
                                                            float *Y, float *part, Geo g, int n_kb, int n_tb,
                                                            int splits, int steps_per_split)
 {
@@ -228,50 +227,49 @@ __global__ __launch_bounds__(F2_T, 1) void fused_f2_kernel(const float *__restri
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[e][q][r] = 0.0f;
 
+    // Operands of one component: filter pairs a[j], tile pairs of the two blocks bl[j], bh[j].
+    struct Ops {
+        floatx2_t a[2], bl[2], bh[2];
+    };
+    auto read_ops = [&](Ops &o, int e) {
+        const int comp = wave * 4 + e;
+        const float *ua = Us + (size_t)comp * (4 * F2_K * 2) + (lh * F2_K + li) * 2;
+        const float *va = Vs + (size_t)comp * (4 * F2_P * 2) + (lh * F2_P + li) * 2;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            o.a[j] = *reinterpret_cast<const floatx2_t *>(ua + j * (2 * F2_K * 2));
+            o.bl[j] = *reinterpret_cast<const floatx2_t *>(va + j * (2 * F2_P * 2));
+            o.bh[j] = *reinterpret_cast<const floatx2_t *>(va + j * (2 * F2_P * 2) + 32 * 2);
+        }
+    };
     auto multiply = [&]() {
-        // both tile blocks always: a block without tiles holds zeros and costs no extra time, since
-        // other workgroups of the launch multiply two blocks anyway
+        // Both tile blocks always: a block without tiles holds zeros and costs no extra time, since
+        // other workgroups of the launch multiply two blocks anyway.  The operands of the next
+        // component are requested before the MFMAs of the current one, so that the LDS latency
+        // is paid once per step and not once per component.
+        Ops o[2];
+        read_ops(o[0], 0);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int comp = wave * 4 + e;
-            const float *ua = Us + (size_t)comp * (4 * F2_K * 2) + (lh * F2_K + li) * 2;
-            const float *va = Vs + (size_t)comp * (4 * F2_P * 2) + (lh * F2_P + li) * 2;
-            floatx2_t a[2], bl[2], bh[2];
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                a[j] = *reinterpret_cast<const floatx2_t *>(ua + j * (2 * F2_K * 2));
-                bl[j] = *reinterpret_cast<const floatx2_t *>(va + j * (2 * F2_P * 2));
-                bh[j] = *reinterpret_cast<const floatx2_t *>(va + j * (2 * F2_P * 2) + 32 * 2);
-            }
+            if (e + 1 < 4) read_ops(o[(e + 1) & 1], e + 1);
+            __builtin_amdgcn_sched_barrier(0);      // keep the reads ahead of the MFMAs below
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
-                    acc[e][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j][h], bl[j][h], acc[e][0], 0, 0, 0);
-                    acc[e][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j][h], bh[j][h], acc[e][1], 0, 0, 0);
+                    acc[e][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(o[e & 1].a[j][h], o[e & 1].bl[j][h], acc[e][0], 0, 0, 0);
+                    acc[e][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(o[e & 1].a[j][h], o[e & 1].bh[j][h], acc[e][1], 0, 0, 0);
                 }
         }
     };
-    // one step with the raw values in `r`; afterwards `r` is refilled for three steps later
-    auto stage = [&](F2Raw &r, int step) {
+    F2Raw r;
+    load_raw(r, step_lo);
+    for (int step = step_lo; step < step_hi; ++step) {
         transform_raw(r, step);
         f2_lds_barrier();
-        if (step + 3 < step_hi) load_raw(r, step + 3);
+        if (step + 1 < step_hi) load_raw(r, step + 1);      // arrives while the MFMAs run
         multiply();
         f2_lds_barrier();
-    };
-
-    F2Raw r0, r1, r2;
-    load_raw(r0, step_lo);
-    if (step_lo + 1 < step_hi) load_raw(r1, step_lo + 1);
-    if (step_lo + 2 < step_hi) load_raw(r2, step_lo + 2);
-    for (int step = step_lo;;) {
-        stage(r0, step);
-        if (++step >= step_hi) break;
-        stage(r1, step);
-        if (++step >= step_hi) break;
-        stage(r2, step);
-        if (++step >= step_hi) break;
     }
 
     // ---- inverse transform -----------------------------------------------------------------------
@@ -364,7 +362,7 @@ static void f2_plan(const Geo &g, size_t workspace_bytes, int *splits, int *per)
     const long long base = (long long)(g.Kp / F2_K) * ((g.P + F2_P - 1) / F2_P);
     const int nsteps = (g.C + F2_C - 1) / F2_C;
     long long s = 1;
-    if (base < 256 && base <= F2_MAX_BLOCKS) s = (512 + base - 1) / base;
+    if (base < 192) s = (512 + base - 1) / base < 16 ? (512 + base - 1) / base : 16;
     if (const char *t = tuning_env("WINO_F2_SPLITS")) s = atoi(t);     // tuning only
     const long long fit = (long long)(workspace_bytes / ((size_t)base * F2_K * F2_P * 4 * sizeof(float)));
     if (s > fit) s = fit;

@@ -191,6 +191,14 @@ def test_variant_query_host_only(L):
     assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 4, 0, 0, 7) == -w.WINO_EINVAL
     # inputs of 2 GiB or more need 64-bit tap offsets: not eligible
     assert L.wino_conv2d_variant(256, 64, 224, 224, 64, 1, 4, 0, 0, w.FLAG_FUSED) == -w.WINO_EUNSUPPORTED
+    # the one-launch layer (filter transform inside the kernel) exists for fp32 F(2x2,3x3) only, either padding
+    assert w.wino_conv2d_variant(1, 512, 14, 14, 512, 1, 2, flags=w.FLAG_ONE_LAUNCH) == w.FLAG_ONE_LAUNCH
+    assert w.wino_conv2d_variant(3, 5, 9, 11, 7, 0, 2, flags=w.FLAG_ONE_LAUNCH) == w.FLAG_ONE_LAUNCH
+    assert L.wino_conv2d_variant(1, 512, 14, 14, 512, 1, 4, 0, 0, w.FLAG_ONE_LAUNCH) == -w.WINO_EUNSUPPORTED
+    assert L.wino_conv2d_variant(1, 512, 14, 14, 512, 1, 2, 1, 0, w.FLAG_ONE_LAUNCH) == -w.WINO_EUNSUPPORTED  # fp16
+    assert L.wino_conv2d_variant(1, 512, 14, 14, 512, 1, 2, 0, 1, w.FLAG_ONE_LAUNCH) == -w.WINO_EUNSUPPORTED  # fp16 Y
+    assert L.wino_conv2d_variant(2048, 64, 224, 224, 64, 1, 2, 0, 0, w.FLAG_ONE_LAUNCH) == -w.WINO_EUNSUPPORTED
+    assert L.wino_conv2d_variant(1, 512, 14, 14, 512, 1, 2, 0, 0, 4) == -w.WINO_EINVAL
 
 
 def test_bench_refuses_more_than_one_gpu():
