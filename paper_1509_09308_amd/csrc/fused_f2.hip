@@ -4,15 +4,19 @@
 // nor M ever exist in memory.  Meant for small batches, where a layer is a few microseconds of
 // arithmetic and every extra launch costs as much as the arithmetic itself.
 //
-// Workgroup = 4 wavefronts owning 32 filters x 64 tiles (two blocks of 32) x 16 components and a
-// slice of the channels.  Per step of 8 channels:
-//   1. every thread transforms one filter (k, c) -- 9 loads, 28 flops -- into LDS as
-//      [e][c / 2][k][c % 2], and the 4 x 4 input tiles of one tile and two channels (v = B^T d B,
-//      32 additions each) into LDS as [e][c / 2][tile][c % 2]; the raw values of the next step are
-//      requested before the multiply phase so that they arrive while the MFMAs run;
+// Workgroup = 4 wavefronts owning 32 filters x an 8 x 8 block of tiles of one image (two MFMA
+// column blocks of 4 x 8 tiles) x 16 components, and a slice of the channels.  Per step of 8 channels:
+//   1. the 18 x 18 input patch under the tile block is loaded ONCE per channel (11 coalesced
+//      4-byte loads per thread instead of 32 overlapping ones, zeros written for taps outside the
+//      image) into a double-buffered LDS area, one step ahead; every thread reads the 4 x 4 taps
+//      of one tile in two channels from there, computes v = B^T d B (32 additions each) and stores
+//      it as [e][c / 2][tile][c % 2]; every thread also transforms one filter (k, c) -- 9 loads
+//      requested a step ahead, 28 flops -- into LDS as [e][c / 2][k][c % 2];
 //   2. wavefront w owns row xi = w of the transform domain (components 4w .. 4w + 3); lane (i, h)
 //      reads channels 4j + 2h, 4j + 2h + 1 of its filter row and of its two tile columns with one
 //      8-byte read each and feeds v_mfma_f32_32x32x2_f32.
+// A last step that would run past the channels is moved back to end at the last channel; the
+// filters of the channels it sees a second time are zeroed, so nothing is added twice.
 // After the last step each wavefront applies the row half of Y = A^T m A to its own accumulators
 // (t = m_row A), the four wavefronts exchange t through LDS and every thread finishes the column
 // half for (filter, tile) pairs.
@@ -35,6 +39,12 @@ typedef float floatx2_t __attribute__((ext_vector_type(2)));
 constexpr int F2_K = 32, F2_P = 64, F2_C = 8, F2_T = 256;     // filters, tiles, channels per step, threads
 constexpr int F2_U_FLOATS = 16 * (F2_C / 2) * F2_K * 2;       // transformed filters of a step
 constexpr int F2_V_FLOATS = 16 * (F2_C / 2) * F2_P * 2;       // transformed tiles of a step
+constexpr int F2_BT = 8;                                      // the 64 tiles are an 8 x 8 block of one image
+constexpr int F2_PR = 2 * F2_BT + 2;                          // rows and columns of the input patch under it
+constexpr int F2_RS = 20;                                     // LDS row stride of the patch (even: 8-byte tap reads)
+constexpr int F2_PATCH = F2_C * F2_PR * F2_PR;                // patch elements of a step (2592)
+constexpr int F2_R_FLOATS = F2_C * F2_PR * F2_RS;             // one patch buffer in LDS
+constexpr int F2_NLD = (F2_PATCH + F2_T - 1) / F2_T;          // patch elements per thread (11, the last for 32 threads)
 constexpr int F2_T_FLOATS = 4 * 2 * F2_K * 32;                // epilogue exchange of one tile block
 constexpr int F2_MAX_BLOCKS = 4096;                           // output blocks a split launch may have
 static_assert(F2_T_FLOATS <= F2_U_FLOATS + F2_V_FLOATS, "the epilogue reuses the operand area");
@@ -43,14 +53,6 @@ static_assert(F2_T_FLOATS <= F2_U_FLOATS + F2_V_FLOATS, "the epilogue reuses the
 // workgroup that finishes a block sets its counter back to zero, so every launch starts from zero.
 // Two split launches that overlap on one GPU (different streams) would share them: see wino.h.
 static __device__ unsigned int f2_tickets[F2_MAX_BLOCKS];
-
-__device__ __forceinline__ void f2_tile(const Geo &g, int b, int *img, int *tx, int *ty)
-{
-    *ty = b % g.Tw;
-    const int t2 = b / g.Tw;
-    *tx = t2 % g.Th;
-    *img = t2 / g.Th;
-}
 
 // Partial outputs travel between workgroups, which may sit on different XCDs with separate L2
 // caches.  They are written and read with agent-scope atomic accesses (relaxed, 8 bytes): such a
@@ -72,11 +74,9 @@ __device__ __forceinline__ floatx2_t f2_ld_agent(const float *p)
     return __builtin_bit_cast(floatx2_t, u);
 }
 
-// Writes the rows and columns of one 2 x 2 output that are inside the image.
-__device__ __forceinline__ void f2_store(const Geo &g, float *Y, int k, int b, floatx4_t y)
+// Writes the rows and columns of the 2 x 2 output of tile (tx, ty) that are inside the image.
+__device__ __forceinline__ void f2_store(const Geo &g, float *Y, int k, int img, int tx, int ty, floatx4_t y)
 {
-    int img, tx, ty;
-    f2_tile(g, b, &img, &tx, &ty);
     float *dst = Y + (((size_t)img * g.K + k) * g.Ho + 2 * tx) * g.Wo + 2 * ty;
     const bool row1 = 2 * tx + 1 < g.Ho, col1 = 2 * ty + 1 < g.Wo;
     if (col1 && (g.Wo & 1) == 0) {
@@ -101,11 +101,6 @@ __device__ __forceinline__ void f2_lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-struct F2Raw {
-    float in[2][16];    // 4 x 4 taps of one tile in two channels
-    float g[9];         // one 3 x 3 filter
-};
-
 // BWD: the layer is the input gradient (Section 4.2 of the paper): its filter (k, c) is filter
 // (c, k) of the stored G[C][K][3][3], rotated by 180 degrees.
 // Two workgroups per CU (at most 256 registers per lane), so that one can multiply while the other
@@ -115,79 +110,92 @@ __global__ __launch_bounds__(F2_T, 2) void fused_f2_kernel(const float *__restri
                                                            float *Y, float *part, Geo g, int n_kb, int n_tb,
                                                            int splits, int steps_per_split)
 {
-    __shared__ float smem[F2_U_FLOATS + F2_V_FLOATS];
+    __shared__ float smem[F2_U_FLOATS + F2_V_FLOATS + 2 * F2_R_FLOATS];
     __shared__ int s_last;
     float *Us = smem;
     float *Vs = smem + F2_U_FLOATS;
+    float *Rs = smem + F2_U_FLOATS + F2_V_FLOATS;
 
     const int bid = blockIdx.x;
     const int kb = bid % n_kb;
     const int rest = bid / n_kb;
     const int sp = rest % splits, tb = rest / splits;
-    const int k0 = kb * F2_K, b0 = tb * F2_P;
+    const int k0 = kb * F2_K;
+    const int nby = (g.Tw + F2_BT - 1) / F2_BT, nbx = (g.Th + F2_BT - 1) / F2_BT;
+    const int by = tb % nby, bx = (tb / nby) % nbx, img = tb / (nby * nbx);
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int nsteps = (g.C + F2_C - 1) / F2_C;
     const int step_lo = sp * steps_per_split;
     const int step_hi = min(step_lo + steps_per_split, nsteps);
-    const int nblk = (g.P - b0 > 32) ? 2 : 1;          // tile blocks of this workgroup that hold tiles
+    const int nblk = (F2_BT * bx + F2_BT / 2 < g.Th) ? 2 : 1;       // MFMA column blocks that hold tiles
+    // first channel the LDS slots of a step hold: the last step ends at the last channel
+    auto first_channel = [&](int step) { return step == nsteps - 1 ? max(g.C - F2_C, 0) : step * F2_C; };
 
-    // ---- transform-phase roles -----------------------------------------------------------------
-    // input: tile `lane`, channels 2 wave and 2 wave + 1 of the step.  A tap is read from
-    // (channel plane, the same for the whole wavefront) + toff (element offset of the lane: image,
-    // clamped row and column); taps outside the image are masked to zero afterwards.
-    const bool tile_ok = b0 + lane < g.P;
-    unsigned toff[16];
-    unsigned tmask = 0;                                 // bit 4p + j: tap (p, j) is inside the image
-    {
-        int img, tx, ty;
-        f2_tile(g, tile_ok ? b0 + lane : 0, &img, &tx, &ty);
-        const int x0 = 2 * tx - g.pad, y0 = 2 * ty - g.pad;
-        const unsigned ibase = (unsigned)img * (unsigned)g.C * (unsigned)(g.H * g.W);
-#pragma unroll
-        for (int p = 0; p < 4; ++p)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                toff[4 * p + j] = ibase + (unsigned)(min(max(x0 + p, 0), g.H - 1) * g.W + min(max(y0 + j, 0), g.W - 1));
-                if (tile_ok && x0 + p >= 0 && x0 + p < g.H && y0 + j >= 0 && y0 + j < g.W) tmask |= 1u << (4 * p + j);
-            }
-    }
+    // ---- loader role: patch elements tid, tid + 256, ... of [channel slot][row][column] ------------
     const size_t plane = (size_t)g.H * g.W;
-    // filter: filter kk of the block, channel cc of the step; goff is the lane's element offset from
-    // the first filter of the step (the last step clamps channels past the end)
+    unsigned loff[F2_NLD];          // element offset from the first channel of the step, clamped into the image
+    int lidx[F2_NLD];               // LDS index inside a patch buffer
+    unsigned lmask = 0;             // bit n: element n is inside the image
+    {
+        const int x0 = 2 * F2_BT * bx - g.pad, y0 = 2 * F2_BT * by - g.pad;
+#pragma unroll
+        for (int n = 0; n < F2_NLD; ++n) {
+            const int e = tid + n * F2_T;
+            const bool e_ok = e < F2_PATCH;
+            const int ee = e_ok ? e : 0;
+            const int c = ee / (F2_PR * F2_PR), rem = ee % (F2_PR * F2_PR);
+            const int r = rem / F2_PR, q = rem % F2_PR;
+            const int x = x0 + r, y = y0 + q;
+            if (e_ok && x >= 0 && x < g.H && y >= 0 && y < g.W) lmask |= 1u << n;
+            loff[n] = (unsigned)min(c, g.C - 1) * (unsigned)(g.H * g.W) +
+                      (unsigned)(min(max(x, 0), g.H - 1) * g.W + min(max(y, 0), g.W - 1));
+            lidx[n] = (c * F2_PR + r) * F2_RS + q;
+        }
+    }
+    const float *Dimg = D + (size_t)img * g.C * plane;
+    // ---- filter role: filter kk of the block, channel slot cc of the step ---------------------------
     const int kk = tid >> 3, cc = tid & 7;
     const bool k_ok = k0 + kk < g.K;
-    const int kc = min(k0 + kk, g.K - 1);
-    const int cc_last = min(cc, g.C - 1 - (nsteps - 1) * F2_C);
-    const unsigned goff = BWD ? (unsigned)(cc * g.K + kc) * 9u : (unsigned)(kc * g.C + cc) * 9u;
-    const unsigned goff_last = BWD ? (unsigned)(cc_last * g.K + kc) * 9u : (unsigned)(kc * g.C + cc_last) * 9u;
-    const size_t gstep = BWD ? (size_t)F2_C * g.K * 9 : (size_t)F2_C * 9;
+    const int kc = min(k0 + kk, g.K - 1), ccl = min(cc, g.C - 1);
+    const unsigned goff = BWD ? (unsigned)(ccl * g.K + kc) * 9u : (unsigned)(kc * g.C + ccl) * 9u;
+    const size_t gchan = BWD ? (size_t)g.K * 9 : (size_t)9;        // elements from one channel to the next
+    // ---- tile role of the data transform: tile (ti, tj) of the block, channel slots 2 wave, 2 wave + 1
+    const int ti = lane >> 3, tj = lane & 7;
 
-    auto load_raw = [&](F2Raw &r, int step) {
+    float raw[F2_NLD], rg[9];
+    auto load_patch = [&](int step) {
+        const float *pc = Dimg + (size_t)first_channel(step) * plane;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const float *pc = D + (size_t)min(step * F2_C + 2 * wave + h, g.C - 1) * plane;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) r.in[h][i] = pc[toff[i]];
-        }
-        const float *pg = G + (size_t)step * gstep;
-        const unsigned go = (step == nsteps - 1) ? goff_last : goff;
-#pragma unroll
-        for (int j = 0; j < 9; ++j) r.g[j] = pg[go + (BWD ? 8 - j : j)];
+        for (int n = 0; n < F2_NLD; ++n) raw[n] = pc[loff[n]];
     };
-    auto transform_raw = [&](const F2Raw &r, int step) {
-        // v = B^T d B of two channels, stored as channel pairs
+    auto store_patch = [&](float *Rb) {
+#pragma unroll
+        for (int n = 0; n < F2_NLD; ++n)
+            if (n + 1 < F2_NLD || tid < F2_PATCH - (F2_NLD - 1) * F2_T) Rb[lidx[n]] = ((lmask >> n) & 1u) ? raw[n] : 0.0f;
+    };
+    auto load_filter = [&](int step) {
+        const float *pg = G + (size_t)first_channel(step) * gchan;
+#pragma unroll
+        for (int j = 0; j < 9; ++j) rg[j] = pg[goff + (BWD ? 8 - j : j)];
+    };
+    auto transform = [&](const float *Rb, int step) {
+        // v = B^T d B of one tile in two channels, stored as a channel pair
         float v[2][16];
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const bool c_ok = step * F2_C + 2 * wave + h < g.C;
-            const unsigned mask = c_ok ? tmask : 0u;
-            float t[4][4];
+            const float *src = Rb + ((2 * wave + h) * F2_PR + 2 * ti) * F2_RS + 2 * tj;
+            float d[4][4], t[4][4];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const floatx2_t lo = *reinterpret_cast<const floatx2_t *>(src + p * F2_RS);
+                const floatx2_t hi = *reinterpret_cast<const floatx2_t *>(src + p * F2_RS + 2);
+                d[p][0] = lo[0], d[p][1] = lo[1], d[p][2] = hi[0], d[p][3] = hi[1];
+            }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                float col[4], o[4];
-#pragma unroll
-                for (int p = 0; p < 4; ++p) col[p] = ((mask >> (4 * p + j)) & 1u) ? r.in[h][4 * p + j] : 0.0f;
+                const float col[4] = {d[0][j], d[1][j], d[2][j], d[3][j]};
+                float o[4];
                 bt_mul<2>(col, o);
 #pragma unroll
                 for (int p = 0; p < 4; ++p) t[p][j] = o[p];
@@ -199,12 +207,14 @@ __global__ __launch_bounds__(F2_T, 2) void fused_f2_kernel(const float *__restri
 #pragma unroll
         for (int e = 0; e < 16; ++e)
             *reinterpret_cast<floatx2_t *>(vd + (size_t)e * (4 * F2_P * 2)) = floatx2_t{v[0][e], v[1][e]};
-        // u = G g G^T of one filter
-        const bool f_ok = k_ok && step * F2_C + cc < g.C;
+        // u = G g G^T of one filter; zero for filters past K, channels past C and channels an
+        // earlier step has already added
+        const int c = first_channel(step) + cc;
+        const bool f_ok = k_ok && c >= step * F2_C && c < g.C;
         float t[4][3], u[4][4];
 #pragma unroll
         for (int j = 0; j < 3; ++j) {
-            const float col[3] = {f_ok ? r.g[j] : 0.0f, f_ok ? r.g[3 + j] : 0.0f, f_ok ? r.g[6 + j] : 0.0f};
+            const float col[3] = {f_ok ? rg[j] : 0.0f, f_ok ? rg[3 + j] : 0.0f, f_ok ? rg[6 + j] : 0.0f};
             float o[4];
             g_mul<2>(col, o);
 #pragma unroll
@@ -262,12 +272,18 @@ __global__ __launch_bounds__(F2_T, 2) void fused_f2_kernel(const float *__restri
                 }
         }
     };
-    F2Raw r;
-    load_raw(r, step_lo);
+    load_patch(step_lo);
+    load_filter(step_lo);
+    store_patch(Rs);
+    if (step_lo + 1 < step_hi) load_patch(step_lo + 1);
+    f2_lds_barrier();
     for (int step = step_lo; step < step_hi; ++step) {
-        transform_raw(r, step);
+        float *Rcur = Rs + ((step - step_lo) & 1) * F2_R_FLOATS, *Rnext = Rs + ((step - step_lo + 1) & 1) * F2_R_FLOATS;
+        transform(Rcur, step);
+        if (step + 1 < step_hi) store_patch(Rnext);          // requested during the previous multiply phase
         f2_lds_barrier();
-        if (step + 1 < step_hi) load_raw(r, step + 1);      // arrives while the MFMAs run
+        if (step + 2 < step_hi) load_patch(step + 2);          // both arrive while the MFMAs run
+        if (step + 1 < step_hi) load_filter(step + 1);
         multiply();
         f2_lds_barrier();
     }
@@ -289,7 +305,8 @@ __global__ __launch_bounds__(F2_T, 2) void fused_f2_kernel(const float *__restri
             Ts[((wave * 2 + 1) * F2_K + kr) * 32 + li] = t[1];
         }
         __syncthreads();
-        const int b = b0 + blk * 32 + ot;
+        const int tx = F2_BT * bx + blk * 4 + (ot >> 3), ty = F2_BT * by + (ot & 7);
+        const bool t_ok = tx < g.Th && ty < g.Tw;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int kr = okq + 8 * i;
@@ -304,8 +321,8 @@ __global__ __launch_bounds__(F2_T, 2) void fused_f2_kernel(const float *__restri
                 y[2 + q] = o[1];
             }
             if (splits == 1) {
-                if (b < g.P && k0 + kr < g.K) f2_store(g, Y, k0 + kr, b, y);
-            } else if (b < g.P && k0 + kr < g.K) {
+                if (t_ok && k0 + kr < g.K) f2_store(g, Y, k0 + kr, img, tx, ty, y);
+            } else if (t_ok && k0 + kr < g.K) {
                 const size_t blockno = ((size_t)sp * n_tb + tb) * n_kb + kb;
                 float *dst = part + ((blockno * F2_K + kr) * F2_P + blk * 32 + ot) * 4;
                 f2_st_agent(dst, y[0], y[1]);
@@ -325,8 +342,8 @@ __global__ __launch_bounds__(F2_T, 2) void fused_f2_kernel(const float *__restri
     if (!s_last) return;
     for (int idx = tid; idx < F2_K * 32 * nblk; idx += F2_T) {
         const int tile = idx % (32 * nblk), kr = idx / (32 * nblk);
-        const int b = b0 + tile;
-        if (b >= g.P || k0 + kr >= g.K) continue;
+        const int tx = F2_BT * bx + (tile >> 3), ty = F2_BT * by + (tile & 7);
+        if (tx >= g.Th || ty >= g.Tw || k0 + kr >= g.K) continue;
         const size_t sstride = (size_t)n_tb * n_kb * F2_K * F2_P * 4;
         const float *ps = part + ((((size_t)tb * n_kb + kb) * F2_K + kr) * F2_P + tile) * 4;
         floatx4_t y = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -342,24 +359,29 @@ __global__ __launch_bounds__(F2_T, 2) void fused_f2_kernel(const float *__restri
             for (int u = 0; u < 8; ++u)
                 if (s0 + u < splits) y += floatx4_t{lo[u][0], lo[u][1], hi[u][0], hi[u][1]};
         }
-        f2_store(g, Y, k0 + kr, b, y);
+        f2_store(g, Y, k0 + kr, img, tx, ty, y);
     }
     if (tid == 0) __hip_atomic_store(&f2_tickets[tb * n_kb + kb], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Tile blocks of the layer: 8 x 8 tiles of one image each.
+static long long f2_tile_blocks(const Geo &g)
+{
+    return (long long)g.N * ((g.Th + F2_BT - 1) / F2_BT) * ((g.Tw + F2_BT - 1) / F2_BT);
+}
+
 bool fused_f2_eligible(const Geo &g)
 {
-    // 32-bit element offsets into D and G; the grid holds at most 2^31 - 1 workgroups
-    return g.dt == WINO_F32 && g.m == 2 && (long long)g.N * g.C * g.H * g.W < (1LL << 31) &&
-           (long long)g.K * g.C * 9 < (1LL << 31) &&
-           (long long)(g.Kp / F2_K) * ((g.P + F2_P - 1) / F2_P) <= 0x3fffffffLL;
+    // 32-bit element offsets inside an image and into G; the grid holds at most 2^31 - 1 workgroups
+    return g.dt == WINO_F32 && g.m == 2 && (long long)g.C * g.H * g.W < (1LL << 31) &&
+           (long long)g.K * g.C * 9 < (1LL << 31) && (long long)(g.Kp / F2_K) * f2_tile_blocks(g) <= 0x3fffffffLL;
 }
 
 // Channel shares: enough workgroups for two per CU where the channel loop allows it, every share at
 // least one step, output blocks within the ticket array, partial outputs within the workspace.
 static void f2_plan(const Geo &g, size_t workspace_bytes, int *splits, int *per)
 {
-    const long long base = (long long)(g.Kp / F2_K) * ((g.P + F2_P - 1) / F2_P);
+    const long long base = (long long)(g.Kp / F2_K) * f2_tile_blocks(g);
     const int nsteps = (g.C + F2_C - 1) / F2_C;
     long long s = 1;
     if (base < 192) s = (512 + base - 1) / base < 16 ? (512 + base - 1) / base : 16;
@@ -375,7 +397,7 @@ static void f2_plan(const Geo &g, size_t workspace_bytes, int *splits, int *per)
 hipError_t launch_fused_f2(const Geo &g, const float *D, const float *G, float *Y, void *workspace,
                            size_t workspace_bytes, bool bwd, hipStream_t s)
 {
-    const int n_kb = g.Kp / F2_K, n_tb = (g.P + F2_P - 1) / F2_P;
+    const int n_kb = g.Kp / F2_K, n_tb = (int)f2_tile_blocks(g);
     int splits, per;
     f2_plan(g, workspace_bytes, &splits, &per);
     const long long blocks = (long long)n_kb * n_tb * splits;

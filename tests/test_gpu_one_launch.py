@@ -2,7 +2,7 @@
 transform inside; Section 6 of the paper, the variant without separately transformed filters)
 against the fp64 direct-convolution oracle of Eq. (1).  Bound: 1e-5 normwise, as for every fp32
 F(2x2,3x3) path.  Shapes are chosen so that the channel loop runs unsplit, split evenly, and split
-with a shorter last share; tile counts fall on, below and above the 32- and 64-tile block edges."""
+with a shorter last share; tile rows and columns fall on, below and above the edges of the 8 x 8 tile blocks."""
 import numpy as np
 import pytest
 
@@ -17,13 +17,13 @@ SHAPES = [
     (1, 1, 4, 4, 1, 0),
     (2, 3, 5, 7, 4, 1),          # odd extents: half-empty edge tiles
     (1, 19, 13, 29, 70, 1),      # 3 filter blocks, channel steps 8 + 8 + 3
-    (3, 33, 14, 14, 65, 1),      # 147 tiles: blocks of 64, 64, 19
+    (3, 33, 14, 14, 65, 1),      # 7 x 7 tiles per image: one partly filled block each; last step moved back
     (2, 16, 31, 18, 130, 0),
     (5, 130, 9, 9, 40, 1),       # 17 steps shared by many workgroups, last share shorter
     (1, 7, 67, 131, 9, 1),       # many tile blocks: the channel loop stays in one workgroup
-    (2, 64, 8, 8, 32, 1),        # 32 tiles exactly: second tile block empty
-    (1, 64, 16, 16, 32, 1),      # 64 tiles exactly
-    (1, 40, 18, 16, 32, 1),      # 72 tiles: one full workgroup and one with 8 tiles
+    (2, 64, 8, 8, 32, 1),        # 4 x 4 tiles: the second MFMA column block holds no tile
+    (1, 64, 16, 16, 32, 1),      # 8 x 8 tiles exactly
+    (1, 40, 18, 16, 32, 1),      # 9 x 8 tiles: a full block and one with a single tile row
     (1, 512, 14, 14, 512, 1),    # conv5 of Table 3 at batch 1
     (1, 256, 28, 28, 512, 1),    # conv4.1
 ]
@@ -77,6 +77,24 @@ def test_one_launch_repeats_bit_for_bit():
         assert torch.equal(first, again) and torch.equal(first2, again2)
     assert rel_err(first.cpu().numpy(), direct.conv2d_fwd(D, G, pad=1)) <= TOL[("f32", 2)]
     assert rel_err(first2.cpu().numpy(), direct.conv2d_fwd(D2, G2, pad=1)) <= TOL[("f32", 2)]
+
+
+def test_one_launch_partial_outputs_are_fresh():
+    """Two different inputs of one shape alternate through the same workspace: a share that read a
+    partial output of the previous call (same address, other values) would change the result."""
+    torch, w = require_gpu()
+    shape = (1, 256, 14, 14, 96)
+    Da, Ga = synth.make_layer(*shape, seed=301)
+    Db, Gb = synth.make_layer(*shape, seed=302)
+    da, ga, db, gb = to_gpu(Da), to_gpu(Ga), to_gpu(Db), to_gpu(Gb)
+    ws = w.alloc_workspace(1, 256, 14, 14, 96, 1, 2)
+    Ya = w.wino_conv2d_fwd_ex(da, G=ga, pad=1, m=2, workspace=ws, flags=w.FLAG_ONE_LAUNCH).clone()
+    Yb = w.wino_conv2d_fwd_ex(db, G=gb, pad=1, m=2, workspace=ws, flags=w.FLAG_ONE_LAUNCH).clone()
+    assert rel_err(Ya.cpu().numpy(), direct.conv2d_fwd(Da, Ga, pad=1)) <= TOL[("f32", 2)]
+    assert rel_err(Yb.cpu().numpy(), direct.conv2d_fwd(Db, Gb, pad=1)) <= TOL[("f32", 2)]
+    for _ in range(20):
+        assert torch.equal(Ya, w.wino_conv2d_fwd_ex(da, G=ga, pad=1, m=2, workspace=ws, flags=w.FLAG_ONE_LAUNCH))
+        assert torch.equal(Yb, w.wino_conv2d_fwd_ex(db, G=gb, pad=1, m=2, workspace=ws, flags=w.FLAG_ONE_LAUNCH))
 
 
 def test_one_launch_agrees_with_staged_path():
