@@ -188,7 +188,8 @@ def time_stages(torch, w, layers, ws, steps):
                 "output": a2 * L.K * L.P * 4 + L.N * L.K * L.HW * L.HW * 4,
                 "gemm": a2 * (L.K * L.C + L.C * L.P) * s + a2 * L.K * L.P * 4,   # U and V read, M (fp32) written
             }
-            tile = "%d, %d" % (128 if Kp >= 128 else 64, 128 if Pp >= 128 else 64)
+            bm, bn, _ = w.wino_gemm_launch_shape(L.K, L.C, L.P, L.m, L.dt)
+            tile = "%d, %d" % (bm, bn)
             st["kernel"] = ("gemm_f32_kernel<%s, 2, 2, 16>" % tile) if L.dt == w.WINO_F32 else ("gemm_f16_kernel<%s>" % tile)
             del V, M
         res.append(st)
@@ -383,6 +384,8 @@ def main():
     np_dtype = np.float32 if args.dtype == "f32" else np.float16
     cfg_idx = 4 if args.dtype == "f32" else 5
     policy = args.m if args.dtype == "f32" else ("4" if args.m == "auto" else args.m)
+    if args.batch == 1 and args.dtype == "f32" and policy == "auto":
+        policy = "auto_n1"        # the choice the n1 line of the default run makes
 
     layers = make_layers(args.batch, np_dtype, policy, cfg_idx)
     ws = torch.empty(max(L.ws_bytes for L in layers if not L.direct), dtype=torch.uint8, device="cuda")
@@ -421,7 +424,8 @@ def main():
         "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": "vgg16_3x3_conv_stack_N%d_%s" % (args.batch, args.dtype), "batch": args.batch,
                    "layers": 13, "algorithm": "F(4x4,3x3) where 4 divides H, else F(2x2,3x3); conv1.1 direct"
-                   if policy == "auto" else "F(%sx%s,3x3); conv1.1 direct" % (policy, policy),
+                   if policy == "auto" else "F(4x4,3x3) for images of 56x56 and more, else F(2x2,3x3); conv1.1 direct"
+                   if policy == "auto_n1" else "F(%sx%s,3x3); conv1.1 direct" % (policy, policy),
                    "filter_transform": "inside the timed step"},
         "images_per_sec": args.batch / sec,
         "direct_gflop_per_step": total_flops / 1e9,
@@ -491,6 +495,8 @@ def main():
             out["f6x6"] = f6
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers)
+    if args.batch == 1 and args.dtype == "f32":
+        out["one_launch_per_layer"] = time_one_launch(torch, w, layers, max(args.steps, 20), max(args.warmup, 5))
     if not args.no_n1 and args.batch != 1:
         del layers, ws
         torch.cuda.empty_cache()

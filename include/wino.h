@@ -110,6 +110,10 @@ int wino_input_transform(int N, int C, int H, int W, int pad, int m, int dt, con
 /* Loop 3: M^(xi,nu) = U^(xi,nu) V^(xi,nu) for all alpha^2 components (Eq. (13)). */
 int wino_batched_gemm(int K, int C, long long P, int m, int dt, const void *U, const void *V, void *M,
                       void *stream);
+/* Host-side query: the launch shape of loop 3 inside the whole-layer entry points for these extents:
+ * out[0] x out[1] = filters x tiles of M one workgroup computes, out[2] = number of shares the channel sum
+ * is split into (their partial M's are added by loop 4; wino_batched_gemm itself never splits). */
+int wino_gemm_launch_shape(int K, int C, long long P, int m, int dt, int out[3]);
 /* Loop 4: gather m_{k,b} from M, Y_{k,b} = A^T m A, write the outputs that fall inside
  * Ho x Wo.  y_dt is the storage type of Y. */
 int wino_output_transform(int N, int K, int H, int W, int pad, int m, int y_dt, const void *M, void *Y,

@@ -55,6 +55,7 @@ def lib():
             "wino_filter_transform_ex": (i, [i, i, i, i, p, p, p]),
             "wino_input_transform": (i, [i] * 7 + [p, p, p]),
             "wino_batched_gemm": (i, [i, i, ll, i, i, p, p, p, p]),
+            "wino_gemm_launch_shape": (i, [i, i, ll, i, i, ip]),
             "wino_output_transform": (i, [i] * 7 + [p, p, p]),
             "wino_conv2d_fwd": (i, [i] * 7 + [p, p, p, p]),
             "wino_conv2d_fwd_ex": (i, [i] * 9 + [p, p, p, p, p, sz, u, p]),
@@ -76,7 +77,7 @@ def lib():
 EXPORTS = ["wino_status_string", "wino_last_hip_error", "wino_num_tiles", "wino_tile_coords",
            "wino_padded_dims", "wino_u_offset", "wino_v_offset", "wino_m_offset", "wino_filter_bytes",
            "wino_v_bytes", "wino_m_bytes", "wino_workspace_bytes", "wino_filter_transform",
-           "wino_filter_transform_ex", "wino_input_transform", "wino_batched_gemm",
+           "wino_filter_transform_ex", "wino_input_transform", "wino_batched_gemm", "wino_gemm_launch_shape",
            "wino_output_transform", "wino_conv2d_fwd", "wino_conv2d_fwd_ex", "wino_conv2d_variant", "wino_filter_transform_bwd", "wino_conv2d_bwd_data",
            "wino_bwd_filter_workspace_bytes", "wino_conv2d_bwd_filter",
            "direct_conv2d_fwd",
@@ -342,8 +343,15 @@ def wino_conv2d_fwd_ex(D, G=None, U=None, pad=1, m=4, Y=None, y_dtype=None, work
     return Y
 
 
+def wino_gemm_launch_shape(K, C, P, m, dt=WINO_F32):
+    """(filters, tiles) of M per workgroup and the number of channel shares the whole-layer entry points use."""
+    out = (ctypes.c_int * 3)()
+    _check(lib().wino_gemm_launch_shape(K, C, P, m, dt, out), "wino_gemm_launch_shape")
+    return int(out[0]), int(out[1]), int(out[2])
+
+
 def wino_conv2d_variant(N, C, H, W, K, pad, m, dt=WINO_F32, y_dt=WINO_F32, flags=FLAG_AUTO):
-    """FLAG_UNFUSED or FLAG_FUSED: the path wino_conv2d_fwd_ex takes; raises if it would be rejected."""
+    """FLAG_UNFUSED, FLAG_FUSED or FLAG_ONE_LAUNCH: the path wino_conv2d_fwd_ex takes; raises if it would be rejected."""
     v = int(lib().wino_conv2d_variant(N, C, H, W, K, pad, m, dt, y_dt, flags))
     if v < 0:
         raise WinoError(-v, "wino_conv2d_variant")

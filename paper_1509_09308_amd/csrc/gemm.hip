@@ -356,6 +356,12 @@ static GemmShape gemm_shape(const Geo &g)
 
 int gemm_splits(const Geo &g) { return gemm_shape(g).splits; }
 
+void gemm_launch_shape(const Geo &g, int *bm, int *bn, int *splits)
+{
+    const GemmShape sh = gemm_shape(g);
+    *bm = sh.bm, *bn = sh.bn, *splits = sh.splits;
+}
+
 hipError_t launch_batched_gemm(const Geo &g, const void *U, const void *V, float *M, int splits, hipStream_t s)
 {
     if (g.dt == WINO_F16) {

@@ -220,6 +220,16 @@ int wino_batched_gemm(int K, int C, long long P, int m, int dt, const void *U, c
     return e == hipSuccess ? WINO_OK : hip_fail(e);
 }
 
+int wino_gemm_launch_shape(int K, int C, long long P, int m, int dt, int out[3])
+{
+    Geo g;
+    const int st = make_geo_kcp(K, C, P, m, dt, &g);
+    if (st != WINO_OK) return st;
+    if (out == nullptr) return WINO_EINVAL;
+    gemm_launch_shape(g, &out[0], &out[1], &out[2]);
+    return WINO_OK;
+}
+
 int wino_output_transform(int N, int K, int H, int W, int pad, int m, int y_dt, const void *M, void *Y, void *stream)
 {
     Geo g;

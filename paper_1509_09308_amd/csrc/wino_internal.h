@@ -45,6 +45,7 @@ hipError_t launch_filter_transform(const Geo &g, const void *G, void *U, hipStre
 hipError_t launch_filter_transform_bwd(const Geo &g, const void *G, void *U, hipStream_t s);
 hipError_t launch_input_transform(const Geo &g, const void *D, void *V, hipStream_t s);
 int gemm_splits(const Geo &g);
+void gemm_launch_shape(const Geo &g, int *bm, int *bn, int *splits);
 hipError_t launch_batched_gemm(const Geo &g, const void *U, const void *V, float *M, int splits, hipStream_t s);
 hipError_t launch_output_transform(const Geo &g, int y_dt, const float *M, void *Y, int splits, hipStream_t s);
 bool fused_eligible(const Geo &g);

@@ -203,6 +203,18 @@ def test_variant_query_host_only(L):
     assert L.wino_conv2d_variant(1, 512, 14, 14, 512, 1, 2, 0, 0, 4) == -w.WINO_EINVAL
 
 
+def test_gemm_launch_shape_host_only(L):
+    """The block shape and channel shares of the multiply inside a layer call can be asked on the host."""
+    assert w.wino_gemm_launch_shape(512, 512, 64 * 49, 4) == (128, 128, 1)      # conv4.x at N = 64
+    bm, bn, shares = w.wino_gemm_launch_shape(512, 512, 49, 2)                 # conv5.x at N = 1: small blocks, split sum
+    assert (bm, bn) == (64, 64) and shares >= 2
+    assert w.wino_gemm_launch_shape(64, 64, 3136, 4)[:2] == (64, 128)
+    out = (ctypes.c_int * 3)()
+    assert L.wino_gemm_launch_shape(0, 8, 8, 2, 0, out) == w.WINO_EINVAL
+    assert L.wino_gemm_launch_shape(8, 8, 8, 3, 0, out) == w.WINO_EUNSUPPORTED
+    assert L.wino_gemm_launch_shape(8, 8, 8, 2, 0, None) == w.WINO_EINVAL
+
+
 def test_bench_refuses_more_than_one_gpu():
     """bench.py --gpus N > 1 exits with a message before touching any GPU (this build is single-GPU)."""
     import subprocess
