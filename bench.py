@@ -46,9 +46,10 @@ def direct_flops(N, C, H, W, K, R=3, S=3):
 
 
 def choose_m(HW, policy):
-    """F(4x4,3x3) where 4 divides the image, else F(2x2,3x3) ('auto'); 'auto_n1' (the batch-1 stack, for
-    which the workload names no algorithm) takes F(2x2,3x3) for images of 28x28 and below as well: with a
-    handful of tiles the layer is bound by the transformed filters, which are 2.25x smaller; or a fixed m."""
+    """'auto': the algorithms the N=64 workload names -- F(4x4,3x3) where 4 divides the image, else F(2x2,3x3).
+    'auto_n1' (the batch-1 stack, for which the workload names no algorithm) takes F(2x2,3x3) for images of 28x28
+    and below as well: with a handful of tiles the layer is bound by the transformed filters, which are 2.25x
+    smaller.  Or a fixed m."""
     if policy == "auto":
         return 4 if HW % 4 == 0 else 2
     if policy == "auto_n1":
@@ -276,6 +277,28 @@ def time_f6x6(torch, w, layers, layer_ms, steps):
                                           "F(6x6,3x3); context only, not the headline policy"}}
 
 
+def time_all_f4x4(torch, w, layers, steps, warmup):
+    """The same stack with F(4x4,3x3) for the layers whose images 4 does not divide as well (the 14x14 ones: 16 tiles
+    of 36 products per image and channel instead of 49 of 16, edge tiles reaching past the image).  Not the algorithm
+    the workload names for them, so it is reported beside the headline, not as it."""
+    changed = [L for L in layers if not L.direct and L.m != 4]
+    if not changed:
+        return None
+    saved = [(L.m, L.P, L.ws_bytes) for L in changed]
+    for L in changed:
+        L.m = 4
+        L.P = w.wino_num_tiles(L.N, L.HW, L.HW, 1, 4)
+        L.ws_bytes = w.wino_workspace_bytes(L.N, L.C, L.HW, L.HW, L.K, 1, 4, L.dt)
+    ws = torch.empty(max(L.ws_bytes for L in layers if not L.direct), dtype=torch.uint8, device="cuda")
+    sec = time_steps(torch, w, layers, ws, steps, warmup)
+    ms = time_layers(torch, w, changed, ws, steps)
+    res = {"ms_per_step": sec * 1e3, "eff_tflops": sum(L.flops for L in layers) / sec / 1e12,
+           "layers_changed": [{"layer": L.name, "ms": t, "eff_tflops": L.flops / t / 1e9} for L, t in zip(changed, ms)]}
+    for L, (m, P, wsb) in zip(changed, saved):
+        L.m, L.P, L.ws_bytes = m, P, wsb
+    return res
+
+
 def time_one_launch(torch, w, layers, steps, warmup):
     """The batch-1 stack with every Winograd layer as ONE kernel launch: F(2x2,3x3) with the filter
     transform inside the kernel (Section 6 of the paper, the variant without separately transformed
@@ -360,7 +383,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stages", action="store_true")
     ap.add_argument("--no-bwd", action="store_true", help="skip the input- and filter-gradient lines")
-    ap.add_argument("--no-f6", action="store_true", help="skip the F(6x6,3x3) line")
+    ap.add_argument("--no-f6", action="store_true", help="skip the F(6x6,3x3) and all-F(4x4,3x3) lines")
     ap.add_argument("--graph", action="store_true",
                     help="also time the batch-1 stack captured in a HIP graph and replayed (every replay is checked "
                          "against the eager result)")
@@ -489,6 +512,10 @@ def main():
         bf = time_bwd_filter(torch, w, layers, max(3, args.steps // 2))
         if bf:
             out["bwd_filter"] = bf
+    if not args.no_f6 and policy == "auto" and args.dtype == "f32":
+        f4 = time_all_f4x4(torch, w, layers, args.steps, args.warmup)
+        if f4:
+            out["all_f4x4"] = f4
     if not args.no_f6 and policy == "auto":
         f6 = time_f6x6(torch, w, layers, layer_ms, max(3, args.steps // 2))
         if f6:

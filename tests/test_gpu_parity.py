@@ -125,6 +125,24 @@ def test_config4_full_size_sampled(layer):
     assert bool(torch.isfinite(Y).all())
 
 
+def test_f4x4_on_14x14_full_size_sampled():
+    """The all-F(4x4,3x3) line of the benchmark: conv5.3 at N=64 with 4 x 4 tiles on a 14 x 14 image (the last
+    tile row and column reach two outputs past the image)."""
+    torch, w = require_gpu()
+    name, C, HW, K = synth.VGG16_LAYERS[12]
+    N, m = 64, 4
+    D, G = synth.make_layer(N, C, HW, HW, K, synth.layer_seed(4, 12))
+    ws = w.alloc_workspace(N, C, HW, HW, K, 1, m)
+    Y = w.wino_conv2d_fwd_ex(to_gpu(D), G=to_gpu(G), pad=1, m=m, workspace=ws)
+    pts = synth.sample_points((N, K, HW, HW), 4000, seed=12)
+    idx = torch.from_numpy(pts.astype(np.int64)).cuda()
+    got = Y[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy()
+    e = rel_err(got, direct.conv2d_points(D, G, pts, pad=1))
+    print("%s N=64 m=4 sampled rel err %.3e" % (name, e))
+    assert e <= TOL[("f32", 4)]
+    assert bool(torch.isfinite(Y).all())
+
+
 @pytest.mark.parametrize("layer", [3, 5, 9])
 def test_f6x6_full_size_sampled(layer):
     """F(6x6,3x3) at N=64 on VGG shapes whose images 6 does not divide (edge tiles zero-filled)."""
