@@ -66,9 +66,11 @@ typedef enum { WINO_F32 = 0, WINO_F16 = 1 } wino_dtype_t;
                                    * (U must be NULL); WINO_EUNSUPPORTED otherwise.  Meant for small batches.
                                    * When the layer has few output blocks the channel sum is shared between
                                    * workgroups, which meet through arrival counters held inside the library
-                                   * (one set per GPU) and partial outputs in the workspace: two such calls
-                                   * must not run at the same time on one GPU (calls on one stream never do).
-                                   * The result does not depend on the order in which workgroups finish. */
+                                   * and partial outputs in the workspace.  Each of the first 8 streams that
+                                   * make such a call has counters of its own, so calls on different streams
+                                   * may overlap (with different workspaces); calls from further streams run
+                                   * the channel sum unshared (same result, fewer workgroups).  The result
+                                   * does not depend on the order in which workgroups finish. */
 
 const char *wino_status_string(int status);
 /* hipError_t of the most recent failing HIP call made by the calling thread (0 if none). */
@@ -122,8 +124,10 @@ int wino_output_transform(int N, int K, int H, int W, int pad, int m, int y_dt, 
 /* ---- whole layer ------------------------------------------------------------------------ */
 
 /* fp32 layer with F(m x m, 3 x 3): all four loops of Algorithm 1.  Uses a workspace the
- * library allocates on first use and grows when needed (one per process, so calls on
- * different streams must not overlap); released by wino_shutdown(). */
+ * library allocates on first use (hipMalloc: not for callers under stream capture) and replaces by
+ * a larger one when needed; one workspace per (device, stream), so calls on different streams may
+ * overlap.  Never waits for the device: a replaced workspace is kept until wino_shutdown(), which
+ * releases all of them. */
 int wino_conv2d_fwd(int N, int C, int H, int W, int K, int pad, int m, const void *D, const void *G, void *Y,
                     void *stream);
 /* General form.  U may be NULL (then G is transformed into the workspace first) or the output
@@ -167,7 +171,7 @@ int wino_conv2d_variant(int N, int C, int H, int W, int K, int pad, int m, int d
 int direct_conv2d_fwd(int N, int C, int H, int W, int K, int R, int S, int pad, int stride, int dt,
                       const void *D, const void *G, void *Y, void *stream);
 
-/* Frees the cached workspace of wino_conv2d_fwd (synchronises the device first). */
+/* Frees the cached workspaces of wino_conv2d_fwd (synchronises the device first). */
 int wino_shutdown(void);
 
 #ifdef __cplusplus

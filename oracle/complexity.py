@@ -7,12 +7,20 @@
   transform instruction counts stated in Section 4.1 and Section 4.3.
 * Direct-convolution flop count behind Table 3 and the "effective TFLOPS" of Section 7.
 
-Parity pins: tests/test_oracle_complexity.py against tests/golden/*.txt.
+Parity pins: tests/test_oracle_complexity.py against tests/golden/*.txt; Eq. (23) against the stage
+counts of Eq. (19)-(21) expanded by hand at finite sizes; beta and delta against counted
+factorisations of the transform matrices.  Parity unpinned: the filter-transform count gamma of
+F(6x6,3x3) (see TRANSFORM_FLOPS).
 """
 
 # per-tile transform instruction counts (data, filter, inverse), Sections 4.1 and 4.3.  For
-# F(6x6,3x3) the text states no counts; the integers are the only ones that give Table 1's row
-# for tile 8 (6.50, 2.23, 4.38) to its printed decimals.
+# F(6x6,3x3) the text states no counts.  416 and 280 are what a counted straight-line evaluation
+# of this file's neighbour's F(6,3) matrices costs when nested over the 8 x 8 tile (26 and 20
+# instructions per 1-D transform, 16 resp. 14 of them per tile; tests/test_oracle_complexity.py
+# counts them), and they give Table 1's row for tile 8 (6.50, 4.38) to its printed decimals.
+# 143 (= 11 one-dimensional transforms of 13 instructions) is the only integer that rounds to the
+# printed 2.23; the count depends on the row scaling of G, which the paper does not print for this
+# algorithm, so it is taken from the table: PARITY UNPINNED for gamma of F(6x6,3x3) only.
 TRANSFORM_FLOPS = {2: (32, 28, 24), 4: (156, 72, 100), 6: (416, 143, 280)}
 
 

@@ -32,7 +32,7 @@ def lib():
     """The loaded C library (loads it on first use; raises if it has not been built)."""
     global _lib
     if _lib is None:
-        path = os.environ.get("WINO_LIB", _build.LIB_PATH)   # override for tuning experiments
+        path = _build.LIB_PATH
         if not os.path.exists(path):
             raise RuntimeError("libwino.so is not built: run `python -m paper_1509_09308_amd.build`")
         L = ctypes.CDLL(path)

@@ -25,6 +25,8 @@
 // wave = (k half wm) * 4 + (tile group wn) * 2 + (component half h).
 #include <stdlib.h>
 
+#include <mutex>
+
 #include "wino_internal.h"
 #include "transforms.h"
 
@@ -418,8 +420,12 @@ hipError_t launch_fused(const Geo &g, const void *Dv, const void *Uv, float *Y, 
     static_assert(2 * 36 * FC * FK + 2 * 3 * 6 * 64 * 6 <= 8 * 64 * 64, "main-loop LDS fits the exchange area");
     const unsigned d_bytes = (unsigned)((size_t)g.N * g.C * g.H * g.W * 4);
     const bool ragged = !(g.pad == 1 && g.W % 4 == 0);
-    const bool cpad = g.C % FC != 0;
+    // the channel loop runs over Cp (a multiple of 16): every step beyond C must be fetched as zeros, not
+    // from whatever follows the channel planes of this image (the next image, or the end of the tensor)
+    const bool cpad = g.Cp != g.C;
+    static std::mutex attr_mutex;
     static bool attr_set = false;
+    std::lock_guard<std::mutex> attr_lock(attr_mutex);
     if (!attr_set) {
         const void *fns[4] = {(const void *)fused_f4_kernel<false, false>, (const void *)fused_f4_kernel<false, true>,
                               (const void *)fused_f4_kernel<true, false>, (const void *)fused_f4_kernel<true, true>};

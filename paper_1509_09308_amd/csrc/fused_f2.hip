@@ -27,6 +27,8 @@
 // arrives last (an atomic ticket per output block) adds the partial outputs in the order of the
 // shares and writes Y, which keeps the result independent of the arrival order.  Nobody waits for
 // anybody: every workgroup stores, takes a ticket and leaves, or finds it is last and finishes.
+#include <mutex>
+
 #include "wino_internal.h"
 #include "transforms.h"
 
@@ -49,18 +51,26 @@ constexpr int F2_T_FLOATS = 4 * 2 * F2_K * 32;                // epilogue exchan
 constexpr int F2_MAX_BLOCKS = 4096;                           // output blocks a split launch may have
 static_assert(F2_T_FLOATS <= F2_U_FLOATS + F2_V_FLOATS, "the epilogue reuses the operand area");
 
+constexpr int F2_SLOTS = 8;                                   // streams that may run split launches
+
 // Arrival counters of the output blocks of a split launch.  Zero when the library is loaded; the
 // workgroup that finishes a block sets its counter back to zero, so every launch starts from zero.
-// Two split launches that overlap on one GPU (different streams) would share them: see wino.h.
-static __device__ unsigned int f2_tickets[F2_MAX_BLOCKS];
+// Launches on one stream run one after the other and share a set of counters; every stream that
+// asks for a split launch is given a set of its own (f2_ticket_slot), so launches that overlap on
+// one GPU never meet in a counter.  A ninth stream gets none and its layers run unsplit.
+static __device__ unsigned int f2_tickets[F2_SLOTS * F2_MAX_BLOCKS];
 
 // Partial outputs travel between workgroups, which may sit on different XCDs with separate L2
 // caches.  They are written and read with agent-scope atomic accesses (relaxed, 8 bytes): such a
 // store goes through to the level all XCDs share and such a load reads from there, so the
 // hand-over needs no write-back or invalidation of a whole L2, which an agent-scope fence costs
 // on this chip (several hundred nanoseconds per workgroup, serialised).  Order comes from the
-// counters of the wavefront: the stores have completed before the barrier that precedes the
-// ticket, and the loads are issued after the barrier that follows it.
+// memory counter of each wavefront: a store counts in vmcnt until the level that serves its scope
+// has acknowledged it -- for an sc1 store, the memory side all XCDs share -- so every wavefront
+// waits for vmcnt(0) (f2_wait_stores) before the barrier that precedes the ticket: when the
+// ticket is taken, every partial output of this workgroup is where any other XCD's sc1 load will
+// find it.  The loads of the finishing workgroup are issued after the barrier that follows its
+// ticket, which it can only see as last after all other shares have taken theirs.
 __device__ __forceinline__ void f2_st_agent(float *p, float a, float b)
 {
     const floatx2_t v = {a, b};
@@ -72,6 +82,12 @@ __device__ __forceinline__ floatx2_t f2_ld_agent(const float *p)
     const unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED,
                                                    __HIP_MEMORY_SCOPE_AGENT);
     return __builtin_bit_cast(floatx2_t, u);
+}
+
+// Waits until every vector-memory access of this wavefront, stores included, has been acknowledged.
+__device__ __forceinline__ void f2_wait_stores()
+{
+    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0); expcnt and lgkmcnt left alone
 }
 
 // Writes the rows and columns of the 2 x 2 output of tile (tx, ty) that are inside the image.
@@ -108,7 +124,7 @@ __device__ __forceinline__ void f2_lds_barrier()
 template <bool BWD>
 __global__ __launch_bounds__(F2_T, 2) void fused_f2_kernel(const float *__restrict__ D, const float *__restrict__ G,
                                                            float *Y, float *part, Geo g, int n_kb, int n_tb,
-                                                           int splits, int steps_per_split)
+                                                           int splits, int steps_per_split, int slot)
 {
     __shared__ float smem[F2_U_FLOATS + F2_V_FLOATS + 2 * F2_R_FLOATS];
     __shared__ int s_last;
@@ -334,10 +350,11 @@ __global__ __launch_bounds__(F2_T, 2) void fused_f2_kernel(const float *__restri
     if (splits == 1) return;
 
     // ---- the last share to arrive adds the partial outputs ---------------------------------------
-    __syncthreads();                          // every wavefront has waited for its stores
+    unsigned int *const ticket = &f2_tickets[slot * F2_MAX_BLOCKS + tb * n_kb + kb];
+    f2_wait_stores();                         // this wavefront's partial outputs have been acknowledged ...
+    __syncthreads();                          // ... and so have those of the other three
     if (tid == 0)
-        s_last = __hip_atomic_fetch_add(&f2_tickets[tb * n_kb + kb], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-                 (unsigned)(splits - 1);
+        s_last = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(splits - 1);
     __syncthreads();
     if (!s_last) return;
     for (int idx = tid; idx < F2_K * 32 * nblk; idx += F2_T) {
@@ -361,7 +378,7 @@ __global__ __launch_bounds__(F2_T, 2) void fused_f2_kernel(const float *__restri
         }
         f2_store(g, Y, k0 + kr, img, tx, ty, y);
     }
-    if (tid == 0) __hip_atomic_store(&f2_tickets[tb * n_kb + kb], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Tile blocks of the layer: 8 x 8 tiles of one image each.
@@ -379,7 +396,7 @@ bool fused_f2_eligible(const Geo &g)
 
 // Channel shares: enough workgroups for two per CU where the channel loop allows it, every share at
 // least one step, output blocks within the ticket array, partial outputs within the workspace.
-static void f2_plan(const Geo &g, size_t workspace_bytes, int *splits, int *per)
+static void f2_plan(const Geo &g, size_t workspace_bytes, bool may_split, int *splits, int *per)
 {
     const long long base = (long long)(g.Kp / F2_K) * f2_tile_blocks(g);
     const int nsteps = (g.C + F2_C - 1) / F2_C;
@@ -389,9 +406,24 @@ static void f2_plan(const Geo &g, size_t workspace_bytes, int *splits, int *per)
     const long long fit = (long long)(workspace_bytes / ((size_t)base * F2_K * F2_P * 4 * sizeof(float)));
     if (s > fit) s = fit;
     if (s > nsteps) s = nsteps;
-    if (s < 2 || base > F2_MAX_BLOCKS) s = 1;
+    if (s < 2 || base > F2_MAX_BLOCKS || !may_split) s = 1;
     *per = (int)((nsteps + s - 1) / s);
     *splits = (nsteps + *per - 1) / *per;
+}
+
+// The set of arrival counters of stream `s`: the first F2_SLOTS streams that ask get one each, for as long as
+// the library is loaded; -1 for any further stream.
+static int f2_ticket_slot(hipStream_t s)
+{
+    static std::mutex mu;
+    static hipStream_t owner[F2_SLOTS];
+    static int used = 0;
+    std::lock_guard<std::mutex> lock(mu);
+    for (int i = 0; i < used; ++i)
+        if (owner[i] == s) return i;
+    if (used == F2_SLOTS) return -1;
+    owner[used] = s;
+    return used++;
 }
 
 hipError_t launch_fused_f2(const Geo &g, const float *D, const float *G, float *Y, void *workspace,
@@ -399,15 +431,20 @@ hipError_t launch_fused_f2(const Geo &g, const float *D, const float *G, float *
 {
     const int n_kb = g.Kp / F2_K, n_tb = (int)f2_tile_blocks(g);
     int splits, per;
-    f2_plan(g, workspace_bytes, &splits, &per);
+    f2_plan(g, workspace_bytes, true, &splits, &per);
+    int slot = 0;
+    if (splits > 1 && (slot = f2_ticket_slot(s)) < 0) {
+        f2_plan(g, workspace_bytes, false, &splits, &per);
+        slot = 0;
+    }
     const long long blocks = (long long)n_kb * n_tb * splits;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     if (bwd)
         fused_f2_kernel<true><<<dim3((unsigned)blocks), dim3(F2_T), 0, s>>>(D, G, Y, (float *)workspace, g, n_kb, n_tb,
-                                                                            splits, per);
+                                                                            splits, per, slot);
     else
         fused_f2_kernel<false><<<dim3((unsigned)blocks), dim3(F2_T), 0, s>>>(D, G, Y, (float *)workspace, g, n_kb, n_tb,
-                                                                             splits, per);
+                                                                             splits, per, slot);
     return hipGetLastError();
 }
 

@@ -1,6 +1,7 @@
 // The C ABI of libwino: argument checking, buffer-size and layout queries, stage entry
 // points and the whole-layer drivers.  Declarations and contracts are in include/wino.h.
 #include <mutex>
+#include <vector>
 
 #include <stdlib.h>
 
@@ -68,11 +69,20 @@ size_t v_bytes(const Geo &g) { return (size_t)g.a2 * g.Cp * g.Pp * elem_size(g.d
 size_t m_bytes(const Geo &g) { return (size_t)g.a2 * g.Kp * g.Pp * sizeof(float); }
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// Cached workspace of the short-form entry point.
+// Cached workspaces of the short-form entry point, one per (device, stream): work that uses a buffer is
+// always queued on the stream the buffer belongs to, so calls on different streams never share one.
+// A buffer that has become too small is not freed when a larger one replaces it (work queued earlier may
+// still use it, and hipFree would wait for the device): it is kept until wino_shutdown().  Buffers grow by
+// at least a factor of two, so the retired ones add up to less than the live one.
+struct CachedWs {
+    hipStream_t stream;
+    int device;
+    void *ptr;
+    size_t bytes;
+};
 std::mutex g_ws_mutex;
-void *g_ws = nullptr;
-size_t g_ws_bytes = 0;
-int g_ws_device = -1;
+std::vector<CachedWs> g_ws;
+std::vector<void *> g_ws_retired;
 
 }  // namespace
 
@@ -334,7 +344,7 @@ int wino_conv2d_bwd_data(int N, int C, int H, int W, int K, int pad, int m, int 
                          const void *G, const void *U, void *dD, void *workspace, size_t workspace_bytes,
                          unsigned flags, void *stream)
 {
-    if (pad != 1) return (pad == 0) ? WINO_EUNSUPPORTED : WINO_EUNSUPPORTED;   // pad 0 would need pad 2 here
+    if (pad != 1) return WINO_EUNSUPPORTED;   // pad 0 would need pad 2 in the exchanged layer
     Geo g;
     const int st = make_geo(N, K, H, W, C, 1, m, dt, &g);   // error tensor in, K channels; C outputs
     if (st != WINO_OK) return st;
@@ -368,26 +378,32 @@ int wino_conv2d_fwd(int N, int C, int H, int W, int K, int pad, int m, const voi
     if (st != WINO_OK) return st;
     if (bad_ptr(D) || bad_ptr(G) || bad_ptr(Y)) return WINO_EINVAL;
     const size_t need = wino_workspace_bytes(N, C, H, W, K, pad, m, WINO_F32);
-    std::lock_guard<std::mutex> lock(g_ws_mutex);
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return hip_fail(e);
-    if (g_ws == nullptr || g_ws_bytes < need || g_ws_device != dev) {
-        if (g_ws != nullptr) {
-            // work queued earlier may still read the old buffer
-            if ((e = hipDeviceSynchronize()) != hipSuccess) return hip_fail(e);
-            (void)hipFree(g_ws);
-            g_ws = nullptr;
-            g_ws_bytes = 0;
+    void *ws = nullptr;
+    size_t ws_bytes = 0;
+    {
+        std::lock_guard<std::mutex> lock(g_ws_mutex);
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return hip_fail(e);
+        CachedWs *slot = nullptr;
+        for (CachedWs &c : g_ws)
+            if (c.stream == (hipStream_t)stream && c.device == dev) slot = &c;
+        if (slot == nullptr) {
+            g_ws.push_back(CachedWs{(hipStream_t)stream, dev, nullptr, 0});
+            slot = &g_ws.back();
         }
-        if ((e = hipMalloc(&g_ws, need)) != hipSuccess) {
-            g_ws = nullptr;
-            return hip_fail(e);
+        if (slot->bytes < need) {
+            const size_t want = need > 2 * slot->bytes ? need : 2 * slot->bytes;
+            void *fresh = nullptr;
+            if ((e = hipMalloc(&fresh, want)) != hipSuccess) return hip_fail(e);
+            if (slot->ptr != nullptr) g_ws_retired.push_back(slot->ptr);
+            slot->ptr = fresh;
+            slot->bytes = want;
         }
-        g_ws_bytes = need;
-        g_ws_device = dev;
+        ws = slot->ptr;
+        ws_bytes = slot->bytes;
     }
-    return wino_conv2d_fwd_ex(N, C, H, W, K, pad, m, WINO_F32, WINO_F32, D, G, nullptr, Y, g_ws, g_ws_bytes,
+    return wino_conv2d_fwd_ex(N, C, H, W, K, pad, m, WINO_F32, WINO_F32, D, G, nullptr, Y, ws, ws_bytes,
                               WINO_FLAG_AUTO, stream);
 }
 
@@ -409,15 +425,17 @@ int direct_conv2d_fwd(int N, int C, int H, int W, int K, int R, int S, int pad, 
 int wino_shutdown(void)
 {
     std::lock_guard<std::mutex> lock(g_ws_mutex);
-    if (g_ws != nullptr) {
-        hipError_t e = hipDeviceSynchronize();
-        if (e != hipSuccess) return hip_fail(e);
-        if ((e = hipFree(g_ws)) != hipSuccess) return hip_fail(e);
-        g_ws = nullptr;
-        g_ws_bytes = 0;
-        g_ws_device = -1;
-    }
-    return WINO_OK;
+    if (g_ws.empty() && g_ws_retired.empty()) return WINO_OK;
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) return hip_fail(e);
+    int status = WINO_OK;
+    for (CachedWs &c : g_ws)
+        if (c.ptr != nullptr && (e = hipFree(c.ptr)) != hipSuccess) status = hip_fail(e);
+    for (void *p : g_ws_retired)
+        if ((e = hipFree(p)) != hipSuccess) status = hip_fail(e);
+    g_ws.clear();
+    g_ws_retired.clear();
+    return status;
 }
 
 }  // extern "C"

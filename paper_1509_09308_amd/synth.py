@@ -56,10 +56,23 @@ def make_integer_layer(N, C, H, W, K, seed, dmax=8, gmax=4, gscale=1.0):
     return D, G
 
 
-def sample_points(shape, n, seed):
-    """n random (i, k, x, y) output coordinates of a tensor of ``shape``, plus its corners."""
+def sample_points(shape, n, seed, edge=0, planes=3):
+    """n random (i, k, x, y) output coordinates of a tensor of ``shape``, plus its corners; with
+    ``edge`` > 0 also every element of the last ``edge`` rows and the last ``edge`` columns (the
+    last tile row and column of an algorithm with ``edge`` x ``edge`` output tiles) of ``planes``
+    (i, k) planes: the first, the last and random ones."""
     rng = np.random.default_rng(seed)
     pts = np.stack([rng.integers(0, s, n) for s in shape], axis=1).astype(np.int32)
     corners = np.array([[a, b, c, d] for a in (0, shape[0] - 1) for b in (0, shape[1] - 1)
                         for c in (0, shape[2] - 1) for d in (0, shape[3] - 1)], dtype=np.int32)
-    return np.concatenate([corners, pts], axis=0)
+    parts = [corners, pts]
+    if edge > 0:
+        N, K, H, W = shape
+        ik = [(0, 0), (N - 1, K - 1)] + [(int(rng.integers(0, N)), int(rng.integers(0, K)))
+                                         for _ in range(max(planes - 2, 0))]
+        x0, y0 = max(H - edge, 0), max(W - edge, 0)
+        for i, k in ik[:planes]:
+            rows = [[i, k, x, y] for x in range(x0, H) for y in range(W)]
+            cols = [[i, k, x, y] for x in range(x0) for y in range(y0, W)]
+            parts.append(np.array(rows + cols, dtype=np.int32).reshape(-1, 4))
+    return np.concatenate(parts, axis=0)

@@ -6,7 +6,7 @@ import pytest
 
 from oracle import direct
 from paper_1509_09308_amd import synth
-from gpu_util import TOL, require_gpu, rel_err, to_gpu
+from gpu_util import TOL, check_close, require_gpu, rel_err, to_gpu
 
 pytestmark = pytest.mark.gpu
 
@@ -26,9 +26,9 @@ def test_config1_small_layer():
     ref = direct.conv2d_fwd(D, G, pad=1)
     for pre in (True, False):
         Y = _run_full(w, D, G, 1, 2, pre)
-        assert rel_err(Y, ref) <= TOL[("f32", 2)]
+        check_close(Y, ref, TOL[("f32", 2)], "config 1, filters pre-transformed: %s" % pre, 2)
     Y = w.wino_conv2d_fwd(to_gpu(D), to_gpu(G), pad=1, m=2).cpu().numpy()
-    assert rel_err(Y, ref) <= TOL[("f32", 2)]
+    check_close(Y, ref, TOL[("f32", 2)], "config 1, short entry point", 2)
 
 
 @pytest.mark.parametrize("m", [2, 4, 6])
@@ -38,9 +38,8 @@ def test_config2_vgg_layer(m):
     D, G = synth.make_layer(8, 512, 28, 28, 512, synth.layer_seed(2, 0))
     ref = direct.conv2d_fwd(D, G, pad=1)
     Y = _run_full(w, D, G, 1, m)
-    e = rel_err(Y, ref)
-    print("config2 m=%d rel err %.3e" % (m, e))
-    assert e <= TOL[("f32", m)]
+    e, worst = check_close(Y, ref, TOL[("f32", m)], "config 2 m=%d" % m, m)
+    print("config2 m=%d rel err %.3e max abs err %.3e" % (m, e, worst))
 
 
 @pytest.mark.parametrize("m", [2, 4, 6])
@@ -55,9 +54,8 @@ def test_ragged_and_degenerate_shapes(m, shape):
     ref = direct.conv2d_fwd(D, G, pad=pad)
     Y = _run_full(w, D, G, pad, m)
     assert Y.shape == ref.shape
-    e = rel_err(Y, ref)
-    print("ragged %s m=%d rel err %.3e" % (shape, m, e))
-    assert e <= TOL[("f32", m)]
+    e, worst = check_close(Y, ref, TOL[("f32", m)], "ragged %s m=%d" % (shape, m), m)
+    print("ragged %s m=%d rel err %.3e max abs err %.3e" % (shape, m, e, worst))
 
 
 @pytest.mark.parametrize("shape", [(1, 1024, 14, 14, 1024, 1), (2, 768, 9, 23, 40, 1), (1, 48, 7, 250, 1030, 0)])
@@ -87,9 +85,8 @@ def test_config3_vgg16_stack_n1(layer):
     D, G = synth.make_layer(1, C, HW, HW, K, synth.layer_seed(3, layer))
     ref = direct.conv2d_fwd(D, G, pad=1)
     for m in (2, 4):
-        e = rel_err(_run_full(w, D, G, 1, m), ref)
-        print("%s m=%d rel err %.3e" % (name, m, e))
-        assert e <= TOL[("f32", m)]
+        e, worst = check_close(_run_full(w, D, G, 1, m), ref, TOL[("f32", m)], "%s N=1 m=%d" % (name, m), m)
+        print("%s m=%d rel err %.3e max abs err %.3e" % (name, m, e, worst))
 
 
 def test_config3_first_layer_direct():
@@ -98,14 +95,49 @@ def test_config3_first_layer_direct():
     D, G = synth.make_layer(1, C, HW, HW, K, synth.layer_seed(3, 0))
     ref = direct.conv2d_fwd(D, G, pad=1)
     Y = w.direct_conv2d_fwd(to_gpu(D), to_gpu(G), pad=1).cpu().numpy()
-    assert rel_err(Y, ref) <= 1e-5
+    check_close(Y, ref, 1e-5, "conv1.1 N=1 direct")
 
 
-@pytest.mark.parametrize("layer", [1, 3, 6, 9, 12])
+def _sampled_check(torch, Y, D, G, pts, tol, what, m=1):
+    """Outputs of the GPU tensor Y at ``pts`` against the oracle's one-by-one values: normwise and element-wise."""
+    idx = torch.from_numpy(pts.astype(np.int64)).cuda()
+    got = Y[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].float().cpu().numpy()
+    ref = direct.conv2d_points(D, G, pts, pad=1)
+    e, worst = check_close(got, ref, tol, what, m)
+    print("%s: %d sampled outputs, rel err %.3e, max abs err %.3e" % (what, len(pts), e, worst))
+    assert bool(torch.isfinite(Y).all())
+
+
+@pytest.mark.parametrize("layer", range(13))
 def test_config4_full_size_sampled(layer):
-    """N=64 fp32 at the benchmark's launch configuration (pre-transformed filters, caller
-    workspace; F(4x4) where 4 divides the image, F(2x2) for 14x14): outputs sampled at random
-    and at the tensor corners are recomputed one by one by the oracle."""
+    """N=64 fp32, every layer of the stack, exactly as the benchmark step launches it (untransformed
+    filters, caller workspace, the library's own choice of variant; F(4x4) where 4 divides the image,
+    F(2x2) for 14x14; conv1.1 through the direct kernel): outputs sampled at random, at the tensor
+    corners and over the whole last tile row and column of a few (image, filter) planes are recomputed
+    one by one by the oracle."""
+    torch, w = require_gpu()
+    name, C, HW, K = synth.VGG16_LAYERS[layer]
+    N = 64
+    D, G = synth.make_layer(N, C, HW, HW, K, synth.layer_seed(4, layer))
+    d, g = to_gpu(D), to_gpu(G)
+    if C < 16:
+        Y = w.direct_conv2d_fwd(d, g, pad=1)
+        m, tol, what = 1, 1e-5, "%s N=64 direct" % name
+    else:
+        m = 4 if HW % 4 == 0 else 2
+        ws = w.alloc_workspace(N, C, HW, HW, K, 1, m)
+        Y = w.wino_conv2d_fwd_ex(d, G=g, pad=1, m=m, workspace=ws)
+        variant = w.wino_conv2d_variant(N, C, HW, HW, K, 1, m)
+        tol, what = TOL[("f32", m)], "%s N=64 m=%d variant %d" % (name, m, variant)
+    pts = synth.sample_points((N, K, HW, HW), 4000, seed=layer, edge=max(m, 2))
+    _sampled_check(torch, Y, D, G, pts, tol, what, m)
+
+
+@pytest.mark.parametrize("layer", [1, 2, 3, 6, 9, 12])
+def test_config4_full_size_sampled_pretransformed_filters(layer):
+    """The same layers with the filter transform taken out of the call (Section 6, "FX": U is computed once by
+    wino_filter_transform and passed in), which for the layers with few filters selects the other one-kernel
+    design."""
     torch, w = require_gpu()
     name, C, HW, K = synth.VGG16_LAYERS[layer]
     N = 64
@@ -115,14 +147,8 @@ def test_config4_full_size_sampled(layer):
     U = w.wino_filter_transform(g, m)
     ws = w.alloc_workspace(N, C, HW, HW, K, 1, m)
     Y = w.wino_conv2d_fwd_ex(d, U=U, K=K, pad=1, m=m, workspace=ws)
-    pts = synth.sample_points((N, K, HW, HW), 4000, seed=layer)
-    idx = torch.from_numpy(pts.astype(np.int64)).cuda()
-    got = Y[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy()
-    ref = direct.conv2d_points(D, G, pts, pad=1)
-    e = rel_err(got, ref)
-    print("%s N=64 m=%d sampled rel err %.3e" % (name, m, e))
-    assert e <= TOL[("f32", m)]
-    assert bool(torch.isfinite(Y).all())
+    pts = synth.sample_points((N, K, HW, HW), 4000, seed=100 + layer, edge=m)
+    _sampled_check(torch, Y, D, G, pts, TOL[("f32", m)], "%s N=64 m=%d, U given" % (name, m), m)
 
 
 def test_f4x4_on_14x14_full_size_sampled():
@@ -134,13 +160,8 @@ def test_f4x4_on_14x14_full_size_sampled():
     D, G = synth.make_layer(N, C, HW, HW, K, synth.layer_seed(4, 12))
     ws = w.alloc_workspace(N, C, HW, HW, K, 1, m)
     Y = w.wino_conv2d_fwd_ex(to_gpu(D), G=to_gpu(G), pad=1, m=m, workspace=ws)
-    pts = synth.sample_points((N, K, HW, HW), 4000, seed=12)
-    idx = torch.from_numpy(pts.astype(np.int64)).cuda()
-    got = Y[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy()
-    e = rel_err(got, direct.conv2d_points(D, G, pts, pad=1))
-    print("%s N=64 m=4 sampled rel err %.3e" % (name, e))
-    assert e <= TOL[("f32", 4)]
-    assert bool(torch.isfinite(Y).all())
+    pts = synth.sample_points((N, K, HW, HW), 4000, seed=12, edge=m)
+    _sampled_check(torch, Y, D, G, pts, TOL[("f32", 4)], "%s N=64 m=4" % name, 4)
 
 
 @pytest.mark.parametrize("layer", [3, 5, 9])
@@ -153,14 +174,8 @@ def test_f6x6_full_size_sampled(layer):
     d, g = to_gpu(D), to_gpu(G)
     ws = w.alloc_workspace(N, C, HW, HW, K, 1, m)
     Y = w.wino_conv2d_fwd_ex(d, G=g, pad=1, m=m, workspace=ws)
-    pts = synth.sample_points((N, K, HW, HW), 4000, seed=layer)
-    idx = torch.from_numpy(pts.astype(np.int64)).cuda()
-    got = Y[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy()
-    ref = direct.conv2d_points(D, G, pts, pad=1)
-    e = rel_err(got, ref)
-    print("%s N=64 m=6 sampled rel err %.3e" % (name, e))
-    assert e <= TOL[("f32", 6)]
-    assert bool(torch.isfinite(Y).all())
+    pts = synth.sample_points((N, K, HW, HW), 4000, seed=layer, edge=m)
+    _sampled_check(torch, Y, D, G, pts, TOL[("f32", 6)], "%s N=64 m=6" % name, 6)
 
 
 def test_f6x6_rejects_f16_storage():
@@ -185,9 +200,8 @@ def test_f16_storage_layers(m, shape):
     d, g = to_gpu(D), to_gpu(G)
     Y = w.wino_conv2d_fwd_ex(d, G=g, pad=pad, m=m)
     assert Y.dtype == torch.float32
-    e = rel_err(Y.cpu().numpy(), ref)
-    print("fp16 %s m=%d rel err %.3e" % (shape, m, e))
-    assert e <= TOL[("f16", m)]
+    e, worst = check_close(Y.cpu().numpy(), ref, TOL[("f16", m)], "fp16 %s m=%d" % (shape, m), m)
+    print("fp16 %s m=%d rel err %.3e max abs err %.3e" % (shape, m, e, worst))
 
 
 @pytest.mark.parametrize("shape", [(2, 32, 28, 28, 48), (1, 19, 13, 28, 70), (3, 130, 14, 16, 65), (2, 16, 31, 20, 130),
@@ -203,9 +217,8 @@ def test_f16_fused_path_matches_oracle(shape):
     assert w.wino_conv2d_variant(N, C, H, W, K, 1, 4, w.WINO_F16, flags=w.FLAG_FUSED) == w.FLAG_FUSED
     Yf = w.wino_conv2d_fwd_ex(d, G=g, pad=1, m=4, flags=w.FLAG_FUSED).cpu().numpy()
     Yu = w.wino_conv2d_fwd_ex(d, G=g, pad=1, m=4, flags=w.FLAG_UNFUSED).cpu().numpy()
-    e = rel_err(Yf, ref)
-    print("fp16 fused %s rel err %.3e (unfused %.3e)" % (shape, e, rel_err(Yu, ref)))
-    assert e <= TOL[("f16", 4)]
+    e, worst = check_close(Yf, ref, TOL[("f16", 4)], "fp16 fused %s" % (shape,), 4)
+    print("fp16 fused %s rel err %.3e (unfused %.3e) max abs err %.3e" % (shape, e, rel_err(Yu, ref), worst))
     # same fp16 operands, same fp32 accumulation: the two paths differ only in summation order
     assert rel_err(Yf, Yu) <= 5e-4   # v = B^T (d B) here, (B^T d) B there: an fp16 rounding of V can flip
 
@@ -223,24 +236,25 @@ def test_f16_fused_exact_on_integers():
     assert e < 1e-6
 
 
-@pytest.mark.parametrize("layer", [1, 4, 9, 12])
+@pytest.mark.parametrize("layer", range(13))
 def test_config5_full_size_sampled(layer):
-    """N=32, fp16 storage, F(4x4,3x3) on every layer (ragged at 14x14), benchmark launch shape."""
+    """N=32, fp16 storage, every layer as the benchmark launches it: F(4x4,3x3) everywhere (ragged at 14x14),
+    conv1.1 through the direct kernel; the oracle reads the same stored fp16 values."""
     torch, w = require_gpu()
     name, C, HW, K = synth.VGG16_LAYERS[layer]
     N, m = 32, 4
     D, G = synth.make_layer(N, C, HW, HW, K, synth.layer_seed(5, layer), dtype=np.float16)
     d, g = to_gpu(D), to_gpu(G)
-    ws = w.alloc_workspace(N, C, HW, HW, K, 1, m, w.WINO_F16)
-    Y = w.wino_conv2d_fwd_ex(d, G=g, pad=1, m=m, workspace=ws)
-    pts = synth.sample_points((N, K, HW, HW), 4000, seed=layer)
-    idx = torch.from_numpy(pts.astype(np.int64)).cuda()
-    got = Y[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy()
-    ref = direct.conv2d_points(D.astype(np.float32), G.astype(np.float32), pts, pad=1)
-    e = rel_err(got, ref)
-    print("%s N=32 fp16 m=4 sampled rel err %.3e" % (name, e))
-    assert e <= TOL[("f16", 4)]
-    assert bool(torch.isfinite(Y).all())
+    mm = m
+    if C < 16:
+        Y = w.direct_conv2d_fwd(d, g, pad=1)
+        what, mm = "%s N=32 fp16 direct" % name, 1
+    else:
+        ws = w.alloc_workspace(N, C, HW, HW, K, 1, m, w.WINO_F16)
+        Y = w.wino_conv2d_fwd_ex(d, G=g, pad=1, m=m, workspace=ws)
+        what = "%s N=32 fp16 m=4 variant %d" % (name, w.wino_conv2d_variant(N, C, HW, HW, K, 1, m, w.WINO_F16))
+    pts = synth.sample_points((N, K, HW, HW), 4000, seed=layer, edge=m)
+    _sampled_check(torch, Y, D.astype(np.float32), G.astype(np.float32), pts, TOL[("f16", 4)], what, mm)
 
 
 # ---- the one-kernel path (gather + data transform + multiply + inverse transform fused) ----------
@@ -258,9 +272,8 @@ def test_fused_path_matches_oracle(shape):
     ref = direct.conv2d_fwd(D, G, pad=pad)
     Y = w.wino_conv2d_fwd_ex(to_gpu(D), G=to_gpu(G), pad=pad, m=4, flags=w.FLAG_FUSED).cpu().numpy()
     assert Y.shape == ref.shape
-    e = rel_err(Y, ref)
-    print("fused %s rel err %.3e" % (shape, e))
-    assert e <= TOL[("f32", 4)]
+    e, worst = check_close(Y, ref, TOL[("f32", 4)], "fused %s" % (shape,), 4)
+    print("fused %s rel err %.3e max abs err %.3e" % (shape, e, worst))
 
 
 def test_fused_path_exact_on_integers_and_equals_unfused_bookkeeping():
@@ -274,6 +287,29 @@ def test_fused_path_exact_on_integers_and_equals_unfused_bookkeeping():
     Yu = w.wino_conv2d_fwd_ex(d, G=g, pad=1, m=4, flags=w.FLAG_UNFUSED).cpu().numpy()
     assert rel_err(Yf, ref) < 1e-6 and rel_err(Yu, ref) < 1e-6
     assert np.abs(Yf - Yu).max() <= 1e-5 * np.abs(ref).max()
+
+
+@pytest.mark.parametrize("C", [8, 24, 3, 16])
+@pytest.mark.parametrize("given", ["G", "U"])
+def test_fused_path_never_uses_memory_behind_the_input(C, given):
+    """The channel loop of the one-kernel path runs over the padded channel count: channels past C must come
+    in as zeros, not from whatever follows the input in memory.  D ends where a block of NaNs begins (0 * NaN
+    would poison the sums of the last image); both one-kernel designs (untransformed filters / U given)."""
+    torch, w = require_gpu()
+    N, H, W, K = 2, 12, 16, 40
+    D, G = synth.make_layer(N, C, H, W, K, seed=77 + C)
+    ref = direct.conv2d_fwd(D, G, pad=1)
+    n = D.size
+    buf = torch.full((n + 64 * H * W,), float("nan"), dtype=torch.float32, device="cuda")
+    buf[:n] = to_gpu(D).reshape(-1)
+    d = buf[:n].view(N, C, H, W)
+    g = to_gpu(G)
+    if given == "G":
+        Y = w.wino_conv2d_fwd_ex(d, G=g, pad=1, m=4, flags=w.FLAG_FUSED)
+    else:
+        Y = w.wino_conv2d_fwd_ex(d, U=w.wino_filter_transform(g, 4), K=K, pad=1, m=4, flags=w.FLAG_FUSED)
+    assert bool(torch.isfinite(Y).all())
+    check_close(Y.cpu().numpy(), ref, TOL[("f32", 4)], "C=%d, %s given" % (C, given), 4)
 
 
 def test_fused_flag_rejected_where_unsupported():
