@@ -130,6 +130,19 @@ int wino_output_transform(int N, int K, int H, int W, int pad, int m, int y_dt, 
  * releases all of them. */
 int wino_conv2d_fwd(int N, int C, int H, int W, int K, int pad, int m, const void *D, const void *G, void *Y,
                     void *stream);
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): wino_conv2d_fwd with the workspace in a buffer that is part of the
+ * library's image on every GPU (WINO_STATIC_WORKSPACE_BYTES, held from load to exit).  Calls no hipMalloc,
+ * hipFree or other allocating routine.  Same arguments, same kernels and same results as wino_conv2d_fwd.
+ * A layer that needs more (wino_workspace_bytes(N, C, H, W, K, pad, m, WINO_F32) >
+ * WINO_STATIC_WORKSPACE_BYTES) is rejected with WINO_EWORKSPACE before any GPU call; the limit holds e.g.
+ * every layer of the VGG stack at batch 1 with F(4x4,3x3).  All calls on one GPU share the one buffer, which
+ * keeps the last call's contents (nothing in it needs clearing between calls): calls that may overlap on one
+ * GPU -- different streams without an event between them -- race; calls on one stream never do.  The first
+ * call on a GPU looks the buffer's address up (hipGetSymbolAddress), so make it outside stream capture. */
+#define WINO_STATIC_WORKSPACE_BYTES (64u << 20)
+int wino_conv2d_fwd_noalloc(int N, int C, int H, int W, int K, int pad, int m, const void *D, const void *G,
+                            void *Y, void *stream);
 /* General form.  U may be NULL (then G is transformed into the workspace first) or the output
  * of wino_filter_transform_ex for the same (K, C, m, dt) (then G may be NULL).  Never
  * allocates.  `workspace` must hold wino_workspace_bytes() bytes. */

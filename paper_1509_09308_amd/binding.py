@@ -58,6 +58,7 @@ def lib():
             "wino_gemm_launch_shape": (i, [i, i, ll, i, i, ip]),
             "wino_output_transform": (i, [i] * 7 + [p, p, p]),
             "wino_conv2d_fwd": (i, [i] * 7 + [p, p, p, p]),
+            "wino_conv2d_fwd_noalloc": (i, [i] * 7 + [p, p, p, p]),
             "wino_conv2d_fwd_ex": (i, [i] * 9 + [p, p, p, p, p, sz, u, p]),
             "wino_conv2d_variant": (i, [i] * 9 + [u]),
             "wino_filter_transform_bwd": (i, [i, i, i, i, p, p, p]),
@@ -78,7 +79,7 @@ EXPORTS = ["wino_status_string", "wino_last_hip_error", "wino_num_tiles", "wino_
            "wino_padded_dims", "wino_u_offset", "wino_v_offset", "wino_m_offset", "wino_filter_bytes",
            "wino_v_bytes", "wino_m_bytes", "wino_workspace_bytes", "wino_filter_transform",
            "wino_filter_transform_ex", "wino_input_transform", "wino_batched_gemm", "wino_gemm_launch_shape",
-           "wino_output_transform", "wino_conv2d_fwd", "wino_conv2d_fwd_ex", "wino_conv2d_variant", "wino_filter_transform_bwd", "wino_conv2d_bwd_data",
+           "wino_output_transform", "wino_conv2d_fwd", "wino_conv2d_fwd_noalloc", "wino_conv2d_fwd_ex", "wino_conv2d_variant", "wino_filter_transform_bwd", "wino_conv2d_bwd_data",
            "wino_bwd_filter_workspace_bytes", "wino_conv2d_bwd_filter",
            "direct_conv2d_fwd",
            "wino_shutdown"]
@@ -319,6 +320,21 @@ def wino_conv2d_fwd(D, G, pad=1, m=4, Y=None, stream=None):
         Y = torch.empty((N, K, H + 2 * pad - 2, W + 2 * pad - 2), dtype=torch.float32, device=D.device)
     _check(lib().wino_conv2d_fwd(N, C, H, W, K, pad, m, _ptr(D), _ptr(G), _ptr(Y), _stream(stream)),
            "wino_conv2d_fwd")
+    return Y
+
+
+STATIC_WORKSPACE_BYTES = 64 << 20
+
+
+def wino_conv2d_fwd_noalloc(D, G, Y, pad=1, m=4, stream=None):
+    """fp32 layer through the workspace built into the library: the C call allocates nothing (Y is the caller's)."""
+    _dense_cuda(D, "D"), _dense_cuda(G, "G"), _dense_cuda(Y, "Y")
+    N, C, H, W = D.shape
+    K = G.shape[0]
+    if tuple(Y.shape) != (N, K, H + 2 * pad - 2, W + 2 * pad - 2) or _dt(Y) != WINO_F32:
+        raise ValueError("Y must be float32 of shape [N, K, Ho, Wo]")
+    _check(lib().wino_conv2d_fwd_noalloc(N, C, H, W, K, pad, m, _ptr(D), _ptr(G), _ptr(Y), _stream(stream)),
+           "wino_conv2d_fwd_noalloc")
     return Y
 
 

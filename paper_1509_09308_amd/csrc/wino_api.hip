@@ -9,6 +9,11 @@
 
 using namespace wino;
 
+// Workspace of wino_conv2d_fwd_noalloc: part of the library's image on every GPU, so using it needs no
+// allocation.  In host code the array's name is only a handle for hipGetSymbolAddress; kernels are given the
+// device address that call returns (one per GPU, looked up once with that GPU current).
+static __device__ __align__(256) unsigned char scratch[WINO_STATIC_WORKSPACE_BYTES];
+
 namespace {
 
 thread_local int g_last_hip_error = 0;
@@ -83,6 +88,10 @@ struct CachedWs {
 std::mutex g_ws_mutex;
 std::vector<CachedWs> g_ws;
 std::vector<void *> g_ws_retired;
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
 
 }  // namespace
 
@@ -405,6 +414,36 @@ int wino_conv2d_fwd(int N, int C, int H, int W, int K, int pad, int m, const voi
     }
     return wino_conv2d_fwd_ex(N, C, H, W, K, pad, m, WINO_F32, WINO_F32, D, G, nullptr, Y, ws, ws_bytes,
                               WINO_FLAG_AUTO, stream);
+}
+
+int wino_conv2d_fwd_noalloc(int N, int C, int H, int W, int K, int pad, int m, const void *D, const void *G, void *Y,
+                            void *stream)
+{
+    Geo g;
+    const int st = make_geo(N, C, H, W, K, pad, m, WINO_F32, &g);
+    if (st != WINO_OK) return st;
+    if (bad_ptr(D) || bad_ptr(G) || bad_ptr(Y)) return WINO_EINVAL;
+    if (wino_workspace_bytes(N, C, H, W, K, pad, m, WINO_F32) > (size_t)WINO_STATIC_WORKSPACE_BYTES)
+        return WINO_EWORKSPACE;   // the layer needs more than the built-in workspace holds
+    void *ws = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return hip_fail(e);
+        if (dev < 0 || dev >= kMaxDevices) return WINO_EUNSUPPORTED;
+        if (g_scratch_ptr[dev] == nullptr) {
+            void *p = nullptr;
+            if ((e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) != hipSuccess) return hip_fail(e);
+            if (p == nullptr) return hip_fail(hipErrorInvalidSymbol);
+            g_scratch_ptr[dev] = p;
+        }
+        ws = g_scratch_ptr[dev];
+    }
+    // Nothing in the workspace has to start at zero: the transforms write every element of U and V that the
+    // multiply reads (padding included), and the multiply writes every element of M the inverse transform reads.
+    return run_layer(g, WINO_F32, D, G, nullptr, Y, ws, (size_t)WINO_STATIC_WORKSPACE_BYTES, WINO_FLAG_AUTO, false,
+                     (hipStream_t)stream);
 }
 
 int direct_conv2d_fwd(int N, int C, int H, int W, int K, int R, int S, int pad, int stride, int dt, const void *D,

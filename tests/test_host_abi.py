@@ -59,6 +59,12 @@ def test_argument_validation_without_gpu(L):
     assert L.wino_output_transform(1, 4, 8, 8, 1, 2, 0, fake, odd, null) == w.WINO_EINVAL
     assert L.direct_conv2d_fwd(1, 3, 8, 8, 4, 3, 3, 1, 0, 0, fake, fake, fake, null) == w.WINO_EINVAL
     assert L.direct_conv2d_fwd(1, 3, 2, 2, 4, 5, 5, 0, 1, 0, fake, fake, fake, null) == w.WINO_EUNSUPPORTED
+    # the entry point with the built-in workspace: same argument checks, and a layer that does not fit it
+    assert L.wino_conv2d_fwd_noalloc(0, 4, 8, 8, 4, 1, 2, fake, fake, fake, null) == w.WINO_EINVAL
+    assert L.wino_conv2d_fwd_noalloc(1, 4, 8, 8, 4, 1, 2, fake, odd, fake, null) == w.WINO_EINVAL
+    assert L.wino_conv2d_fwd_noalloc(1, 4, 8, 8, 4, 1, 5, fake, fake, fake, null) == w.WINO_EUNSUPPORTED
+    assert L.wino_workspace_bytes(64, 64, 224, 224, 64, 1, 4, 0) > w.STATIC_WORKSPACE_BYTES
+    assert L.wino_conv2d_fwd_noalloc(64, 64, 224, 224, 64, 1, 4, fake, fake, fake, null) == w.WINO_EWORKSPACE
     # workspace too small / both G and U missing
     need = L.wino_workspace_bytes(1, 4, 8, 8, 4, 1, 2, 0)
     assert need > 0
