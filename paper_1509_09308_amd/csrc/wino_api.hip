@@ -298,15 +298,6 @@ static int run_layer(const Geo &g, int y_dt, const void *D, const void *G, const
     }
     if (flags == WINO_FLAG_AUTO && y_dt == WINO_F32 && fused_preferred(g)) flags = WINO_FLAG_FUSED;
     bool v_done = false;
-    {
-        // fp32, filters given untransformed: the two-workgroups-per-CU kernel with its own filter order
-        const char *tune = tuning_env("WINO_FUSED_PAIR");   // tuning only: 0 = off
-        if (flags == WINO_FLAG_FUSED && U == nullptr && fused_pair_eligible(g) && !(tune && tune[0] == '0')) {
-            if ((e = launch_filter_transform_pair(g, (const float *)G, (float *)Uw, bwd, s)) != hipSuccess) return hip_fail(e);
-            if ((e = launch_fused_pair(g, (const float *)D, (const float *)Uw, (float *)Y, s)) != hipSuccess) return hip_fail(e);
-            return WINO_OK;
-        }
-    }
     if (U == nullptr) {
         if (!bwd && flags != WINO_FLAG_FUSED && prep_eligible(g)) {
             // filters and input tiles are transformed by one launch
@@ -319,7 +310,10 @@ static int run_layer(const Geo &g, int y_dt, const void *D, const void *G, const
         U = Uw;
     }
     if (flags == WINO_FLAG_FUSED) {
-        if ((e = launch_fused(g, D, U, (float *)Y, s)) != hipSuccess) return hip_fail(e);
+        // fp32 with pad 1 and W % 4 == 0: the design with two workgroups per CU; otherwise the general one
+        e = fused_lds_eligible(g) ? launch_fused_lds(g, (const float *)D, (const float *)U, (float *)Y, s)
+                                  : launch_fused(g, D, U, (float *)Y, s);
+        if (e != hipSuccess) return hip_fail(e);
         return WINO_OK;
     }
     if (!v_done && (e = launch_input_transform(g, D, Vw, s)) != hipSuccess) return hip_fail(e);

@@ -52,9 +52,8 @@ bool fused_eligible(const Geo &g);
 bool fused_preferred(const Geo &g);
 hipError_t launch_fused(const Geo &g, const void *D, const void *U, float *Y, hipStream_t s);
 bool fused_f16_eligible(const Geo &g);
-bool fused_pair_eligible(const Geo &g);
-hipError_t launch_filter_transform_pair(const Geo &g, const float *G, float *U2, bool bwd, hipStream_t s);
-hipError_t launch_fused_pair(const Geo &g, const float *D, const float *U2, float *Y, hipStream_t s);
+bool fused_lds_eligible(const Geo &g);
+hipError_t launch_fused_lds(const Geo &g, const float *D, const float *U, float *Y, hipStream_t s);
 hipError_t launch_fused_f16(const Geo &g, const void *D, const void *U, float *Y, hipStream_t s);
 bool fused_f2_eligible(const Geo &g);
 hipError_t launch_fused_f2(const Geo &g, const float *D, const float *G, float *Y, void *workspace,
