@@ -395,17 +395,18 @@ bool fused_eligible(const Geo &g)
     return bytes < (1ull << 31) - 65536;
 }
 
-// Where the one-kernel path beats the four-stage path (measured on MI355X): layers whose V and M
-// traffic dominates, i.e. few filters per tile, and enough workgroups to fill the 256 CUs.
+// Where the one-kernel path beats the four-stage path (measured on MI355X at N = 64).  The one-kernel path
+// repeats the data transform for every 32 filters, the four-stage path writes and re-reads V (C rows per tile) and
+// M (K rows per tile): the first wins while K C / (K + C) is small -- 43 to 85 for the VGG layers with 64 to 128
+// channels (1.15x to 2x faster), a tie at 128 (256 -> 256 channels), a loss from 170 up (256 -> 512) -- and there
+// are enough workgroups to fill the 256 CUs.
 bool fused_preferred(const Geo &g)
 {
     if (!fused_eligible(g)) return false;
     const long long blocks = (long long)((g.P + FP - 1) / FP) * ((g.K + FK - 1) / FK);
-    if (g.dt == WINO_F16) {
-        const char *tune = tuning_env("WINO_FUSED_F16_MAXK");   // tuning only
-        return g.K <= (tune ? atoi(tune) : 128) && blocks >= 512;
-    }
-    return g.K <= 128 && blocks >= 512;
+    if (g.dt == WINO_F16) return g.K <= 128 && blocks >= 512;
+    if (!fused_lds_eligible(g)) return g.K <= 128 && blocks >= 512;
+    return (long long)g.K * g.C <= 100LL * (g.K + g.C) && blocks >= 512;
 }
 
 hipError_t launch_fused(const Geo &g, const void *Dv, const void *Uv, float *Y, hipStream_t s)
