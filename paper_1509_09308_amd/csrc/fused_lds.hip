@@ -42,15 +42,6 @@ static_assert(FL_M_FLOATS <= FL_U_FLOATS + FL_V_FLOATS, "the epilogue reuses the
 #define WINO_L_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 #define WINO_L_GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 
-__device__ __forceinline__ int xcd_group_l(int bid, int nblocks)
-{
-    // workgroups are dealt to the 8 XCDs round-robin; make logically consecutive blocks (which share
-    // input tiles) share an XCD and its L2
-    const int per = nblocks / 8;
-    if (bid >= per * 8) return bid;
-    return (bid % 8) * per + bid / 8;
-}
-
 // Barrier that orders LDS traffic only: global loads requested earlier stay in flight across it.
 __device__ __forceinline__ void fl_lds_barrier()
 {
@@ -72,16 +63,23 @@ __device__ __forceinline__ void fl_reads_done_barrier()
 // CPAD: the channel count is not a multiple of 8, so the last step holds channel slots past the last channel.
 template <bool CPAD>
 __global__ __launch_bounds__(FL_T, 2) void fused_lds_kernel(const float *__restrict__ D, const float *__restrict__ U,
-                                                            float *__restrict__ Y, Geo g, int n_kb)
+                                                            float *__restrict__ Y, Geo g, int n_kb, int n_items)
 {
     __shared__ __attribute__((aligned(16))) float smem[FL_U_FLOATS + FL_V_FLOATS];
     float *Us = smem;
     float *Vs = smem + FL_U_FLOATS;
-
-    const int bid = xcd_group_l(blockIdx.x, gridDim.x);
-    const int kb = bid % n_kb, tb = bid / n_kb;
-    const int k0 = kb * FL_K, b0 = tb * FL_P;
     const int tid = threadIdx.x;
+
+    // A workgroup stays on its CU and walks a list of (tile block, filter block) items: the output stores of one
+    // item drain while the next one is computed, and launch and index set-up are paid once.  Workgroups are dealt
+    // to the 8 XCDs round-robin; each XCD takes one contiguous eighth of the items and its resident workgroups
+    // stride through it together, so the filter blocks of one tile block (which read the same input) meet in one L2.
+    const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8, slots = gridDim.x / 8;
+    const int per_xcd = (n_items + 7) / 8;
+    const int item_end = min((xcd + 1) * per_xcd, n_items);
+    for (int item = xcd * per_xcd + slot; item < item_end; item += slots) {
+    const int kb = item % n_kb, tb = item / n_kb;
+    const int k0 = kb * FL_K, b0 = tb * FL_P;
 
     // ---- transform-phase role: (tile, channel slot of the step) ---------------------------------
     const int tl = tid & 31, cl = tid >> 5;
@@ -260,10 +258,12 @@ __global__ __launch_bounds__(FL_T, 2) void fused_lds_kernel(const float *__restr
 #pragma unroll
             for (int p = 0; p < 4; ++p)
                 if (orow + p < g.Ho)
-                    *reinterpret_cast<floatx4_l *>(dst + (size_t)p * g.Wo) = floatx4_l{y[p][0], y[p][1], y[p][2], y[p][3]};
+                    __builtin_nontemporal_store(floatx4_l{y[p][0], y[p][1], y[p][2], y[p][3]},
+                                                reinterpret_cast<floatx4_l *>(dst + (size_t)p * g.Wo));
         }
         __syncthreads();
     }
+    }   // items
 }
 
 bool fused_lds_eligible(const Geo &g)
@@ -279,12 +279,14 @@ bool fused_lds_eligible(const Geo &g)
 hipError_t launch_fused_lds(const Geo &g, const float *D, const float *U, float *Y, hipStream_t s)
 {
     const int n_kb = g.Kp / FL_K;
-    const long long blocks = (long long)((g.P + FL_P - 1) / FL_P) * n_kb;
-    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const long long items = (long long)((g.P + FL_P - 1) / FL_P) * n_kb;
+    if (items > 0x7fffffffLL) return hipErrorInvalidValue;
+    // two workgroups per CU (what registers and LDS allow) on 256 CUs, in multiples of the 8 XCDs
+    const unsigned grid = (unsigned)(items >= 512 ? 512 : (items + 7) / 8 * 8);
     if (g.C % FL_C != 0)
-        fused_lds_kernel<true><<<dim3((unsigned)blocks), dim3(FL_T), 0, s>>>(D, U, Y, g, n_kb);
+        fused_lds_kernel<true><<<dim3(grid), dim3(FL_T), 0, s>>>(D, U, Y, g, n_kb, (int)items);
     else
-        fused_lds_kernel<false><<<dim3((unsigned)blocks), dim3(FL_T), 0, s>>>(D, U, Y, g, n_kb);
+        fused_lds_kernel<false><<<dim3(grid), dim3(FL_T), 0, s>>>(D, U, Y, g, n_kb, (int)items);
     return hipGetLastError();
 }
 
