@@ -100,13 +100,6 @@ def make_layers(N, np_dtype, policy, config_idx, shapes=None):
     return layers
 
 
-def fx_takes_u(w, L):
-    """In the FX step a layer is given pre-transformed filters, except an fp32 layer on the one-kernel path:
-    its kernel reads filters in an order of its own that only the call itself produces, so its (5-10 us)
-    filter transform stays inside."""
-    return not (L.variant == w.FLAG_FUSED and L.dt == w.WINO_F32)
-
-
 def run_step(w, layers, ws, fx=False):
     for L in layers:
         if L.direct:
@@ -192,19 +185,12 @@ def stage_plan(torch, w, L, ws, sets):
     Ys = [L.Y] + [torch.empty_like(L.Y) for _ in range(sets - 1)]
     plans = []
     if L.variant == w.FLAG_FUSED:
-        f32 = L.dt == w.WINO_F32
         for d, y in zip(Ds, Ys):
-            if f32:
-                # the call transforms the filters itself (into the channel-pair order its kernel reads): the
-                # filter transform (a 5-10 us launch) cannot be separated and is inside "fused"
-                plans.append([("fused", (lambda d=d, y=y: w.wino_conv2d_fwd_ex(d, G=L.G, pad=1, m=L.m, Y=y, workspace=ws,
-                                                                               flags=w.FLAG_FUSED)))])
-            else:
-                plans.append([("filter", lambda: w.wino_filter_transform(L.G, L.m, U=U)),
-                              ("fused", (lambda d=d, y=y: w.wino_conv2d_fwd_ex(d, U=U, K=L.K, pad=1, m=L.m, Y=y, workspace=ws,
-                                                                               flags=w.FLAG_FUSED)))])
+            plans.append([("filter", lambda: w.wino_filter_transform(L.G, L.m, U=U)),
+                          ("fused", (lambda d=d, y=y: w.wino_conv2d_fwd_ex(d, U=U, K=L.K, pad=1, m=L.m, Y=y, workspace=ws,
+                                                                           flags=w.FLAG_FUSED)))])
         nbytes = {"filter": 9 * L.K * L.C * s + nU, "fused": nD + nU + nY}
-        kernel = "fused_pair_kernel" if f32 else "fused_f16_kernel"
+        kernel = "fused_lds_kernel<%s>" % ("false" if L.C % 8 == 0 else "true") if L.dt == w.WINO_F32 else "fused_f16_kernel"
     else:
         Vs = [w.alloc_v(L.C, L.P, L.m, L.dt) for _ in range(sets)]
         Ms = [w.alloc_m(L.K, L.P, L.m) for _ in range(sets)]
@@ -605,12 +591,11 @@ def stack_leg(torch, w, args, N, dtype, policy, cfg_idx, steps, warmup, cold=Tru
 
     # FX (Section 6): filters transformed once, ahead of the step
     for L in layers:
-        if not L.direct and fx_takes_u(w, L):
+        if not L.direct:
             L.U = w.wino_filter_transform(L.G, L.m)
     torch.cuda.synchronize()
     fsec = time_steps(torch, w, layers, ws, steps, warmup, fx=True)
     out["fx"] = {"ms_per_step": fsec * 1e3, "eff_tflops": total_flops / fsec / 1e12, "images_per_sec": N / fsec,
-                 "layers_with_filter_transform_still_inside": [L.name for L in layers if not L.direct and L.U is None],
                  "note": "filters pre-transformed by wino_filter_transform outside the timed region"}
 
     if not args.no_stages:

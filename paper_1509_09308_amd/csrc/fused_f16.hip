@@ -39,45 +39,71 @@ static_assert(HF_U_WORDS % 64 == 0, "filters are copied in chunks of one 16-byte
 #define WINO_H_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 #define WINO_H_GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 
-__device__ __forceinline__ int xcd_group(int bid, int nblocks)
+// Barrier that orders LDS traffic only (global loads requested earlier stay in flight across it).
+__device__ __forceinline__ void hf_lds_barrier()
 {
-    // workgroups are dealt to the 8 XCDs round-robin; make logically consecutive blocks (which share
-    // input tiles) share an XCD and its L2
-    const int per = nblocks / 8;
-    if (bid >= per * 8) return bid;
-    return (bid % 8) * per + bid / 8;
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
 }
 
+constexpr unsigned HF_MAX_BYTES = 0x40000000u;                     // longest stretch of D one workgroup's buffer covers
+constexpr unsigned HF_ROW_OOB = 0x80000000u, HF_COL_OOB = 0x40000000u;   // offset markers of taps outside the image
+
+// CPAD: the channel loop (over the padded count Cp) holds channel slots past the last channel.
+template <bool CPAD>
 __global__ __launch_bounds__(HF_T, 2) void fused_f16_kernel(const __half *__restrict__ D, const uint4 *__restrict__ U,
-                                                        float *__restrict__ Y, Geo g, int n_kb)
+                                                            float *__restrict__ Y, Geo g, int n_kb, int n_items)
 {
     __shared__ uint4 smem[HF_LDS_WORDS];
     uint4 *Us = smem;                                               // buffer b at + b * HF_U_WORDS
     __half *Vs = reinterpret_cast<__half *>(smem + 2 * HF_U_WORDS);
     const uint4 *Vw = smem + 2 * HF_U_WORDS;
-
-    const int bid = xcd_group(blockIdx.x, gridDim.x);
-    const int kb = bid % n_kb, tb = bid / n_kb;
-    const int k0 = kb * HF_K, b0 = tb * HF_P;
     const int tid = threadIdx.x;
+
+    // A workgroup stays on its CU and walks a list of (tile block, filter block) items: the output stores of one
+    // item drain while the next one is computed.  Each XCD takes one contiguous eighth of the items and its
+    // resident workgroups stride through it together, so the filter blocks of one tile block meet in one L2.
+    const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8, slots = gridDim.x / 8;
+    const int per_xcd = (n_items + 7) / 8;
+    const int item_end = min((xcd + 1) * per_xcd, n_items);
+    for (int item = xcd * per_xcd + slot; item < item_end; item += slots) {
+    const int kb = item % n_kb, tb = item / n_kb;
+    const int k0 = kb * HF_K, b0 = tb * HF_P;
 
     // ---- transform-phase role: (tile, channel of the step) ------------------------------------
     const int tl = tid & 31, cl = tid >> 5;
     const int b = b0 + tl;
     const bool tile_ok = b < g.P;
-    int x0 = 0, y0 = 0;
-    const __half *src = D;
+    // The taps are loaded through a buffer that starts at the first image this workgroup touches.  A row outside the
+    // image gets the offset HF_ROW_OOB, a column outside gets HF_COL_OOB added instead of its distance from the
+    // middle piece: with the offsets of valid taps below 2^30 (see fused_f16_eligible) every sum with a marker in
+    // it lies beyond the buffer, where a load returns 0 -- the implicit zero padding of Section 6 without a compare.
+    const int tiles_per_image = g.Th * g.Tw;
+    const int img0 = b0 / tiles_per_image;                     // uniform
+    unsigned vo_m[6];                                          // byte offset of columns 1..4 of row p, channel slot cl, step 0
+    unsigned adj_l, adj_r;
     {
-        const int bb = tile_ok ? b : 0;
+        const int bb = tile_ok ? b : b0;
         const int ty = bb % g.Tw;
         const int t2 = bb / g.Tw;
         const int tx = t2 % g.Th;
         const int i = t2 / g.Th;
-        x0 = 4 * tx - 1;
-        y0 = 4 * ty - 1;
-        src = D + (size_t)i * g.C * g.H * g.W;
+        const int x0 = 4 * tx - 1, y0 = 4 * ty - 1;
+        adj_l = (y0 >= 0) ? 0xfffffffeu : HF_COL_OOB;              // -2 bytes
+        adj_r = (y0 + 5 < g.W) ? 8u : HF_COL_OOB;
+        const unsigned plane0 = (unsigned)((i - img0) * g.C + cl) * (unsigned)(g.H * g.W);
+#pragma unroll
+        for (int p = 0; p < 6; ++p) {
+            const int x = x0 + p;
+            const bool rok = tile_ok && x >= 0 && x < g.H;
+            vo_m[p] = rok ? (plane0 + (unsigned)(x * g.W + y0 + 1)) * 2u : HF_ROW_OOB;   // column y0 + 1 = 4 ty
+        }
     }
-    const size_t plane = (size_t)g.H * g.W;
+    const unsigned step_bytes = (unsigned)(HF_C * g.H * g.W) * 2u;
+    const size_t image_halves = (size_t)g.C * g.H * g.W;
+    const size_t left = ((size_t)g.N - img0) * image_halves * 2;
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(D + (size_t)img0 * image_halves), 0, (unsigned)(left < HF_MAX_BYTES ? left : HF_MAX_BYTES), 0x00020000);
 
     // ---- multiply-phase role -------------------------------------------------------------------
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -94,64 +120,61 @@ __global__ __launch_bounds__(HF_T, 2) void fused_f16_kernel(const __half *__rest
     // raw fp16 taps of one tile: per row the four middle columns (8 bytes) and the two outer ones.
     // They are requested one step ahead: the loads of step s+1 are issued as soon as step s has
     // unpacked its own, and stay in flight during the transform, the multiply and the next filter copy.
-    uint2 rmid[6];
-    __half rl[6], rr[6];
+    typedef unsigned uintx2_h __attribute__((ext_vector_type(2)));
+    uintx2_h rmid[6];
+    unsigned short rl[6], rr[6];
     auto load_raw = [&](int step) {
-        const int c = step * HF_C + cl;
-        const __half *pc = src + (size_t)min(c, g.C - 1) * plane;
+        const unsigned so = (unsigned)step * step_bytes;
+        const bool ch_ok = !CPAD || (step * HF_C + cl < g.C);
 #pragma unroll
         for (int p = 0; p < 6; ++p) {
-            const __half *row = pc + (size_t)min(max(x0 + p, 0), g.H - 1) * g.W + y0;
-            rmid[p] = *reinterpret_cast<const uint2 *>(row + 1);
-            rl[p] = row[y0 >= 0 ? 0 : 1];
-            rr[p] = row[y0 + 5 < g.W ? 5 : 4];
+            const unsigned om = ch_ok ? vo_m[p] : HF_ROW_OOB;
+            rmid[p] = __builtin_amdgcn_raw_buffer_load_b64(rsrc, om, so, 0);
+            rl[p] = __builtin_amdgcn_raw_buffer_load_b16(rsrc, om + adj_l, so, 0);
+            rr[p] = __builtin_amdgcn_raw_buffer_load_b16(rsrc, om + adj_r, so, 0);
         }
     };
     // Transformed filters of a step, [e][c8 = step][k] -> Us[e * 32 + k]: direct global -> LDS loads of
-    // 16 bytes per lane (no registers), one step ahead into the other buffer.  A wavefront's loads
-    // return in order and the taps of a step are requested after that step's filters, so once a
-    // wavefront has its taps the filters it requested are in LDS; the barrier extends that to all.
+    // 16 bytes per lane (no registers), one step ahead into the other buffer; a step waits for all of its own
+    // requests (vmcnt(0)) before the barrier that precedes its multiply phase.
     constexpr int NCH = (HF_U_WORDS / 64 + 3) / 4;   // chunks of 64 words per wavefront
-    unsigned uoff[NCH];                              // word offset of this lane's word in step 0
+    unsigned uoff[NCH];                              // byte offset of this lane's word in step 0
 #pragma unroll
     for (int j = 0; j < NCH; ++j) {
         const int w = min(wave + 4 * j, HF_U_WORDS / 64 - 1) * 64 + lane;
-        uoff[j] = (unsigned)((w / HF_K) * nsteps) * g.Kp + min(k0 + w % HF_K, g.Kp - 1);
+        uoff[j] = ((unsigned)((w / HF_K) * nsteps) * g.Kp + min(k0 + w % HF_K, g.Kp - 1)) * 16u;
     }
+    const __amdgpu_buffer_rsrc_t rsrc_u =
+        __builtin_amdgcn_make_buffer_rsrc((void *)U, 0, (unsigned)((size_t)36 * nsteps * g.Kp * 16), 0x00020000);
     auto load_u = [&](int buf, int step) {
-        const uint4 *ub = U + (size_t)step * g.Kp;
+        const unsigned so = (unsigned)step * (unsigned)g.Kp * 16u;
 #pragma unroll
         for (int j = 0; j < NCH; ++j) {
             const int chunk = wave + 4 * j;
             if (chunk < HF_U_WORDS / 64)
-                __builtin_amdgcn_global_load_lds(WINO_H_GLB_PTR(ub + uoff[j]),
-                                                 WINO_H_LDS_PTR(Us + buf * HF_U_WORDS + chunk * 64), 16, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_u, WINO_H_LDS_PTR(Us + buf * HF_U_WORDS + chunk * 64), 16,
+                                                         uoff[j], so, 0, 0);
         }
     };
-    load_u(0, 0);
     load_raw(0);
+    load_u(0, 0);
     for (int step = 0; step < nsteps; ++step) {
         const uint4 *Ub = Us + (step & 1) * HF_U_WORDS;
-        if (step + 1 < nsteps) load_u((step + 1) & 1, step + 1);
+        const bool more = step + 1 < nsteps;
+        // the filters of the next step, into the buffer the previous multiply phase has finished with
+        if (more) load_u((step + 1) & 1, step + 1);
         // 1. one input tile: unpack, transform rows then columns (v = B^T (d B)), round, scatter
         {
-            const bool ok = tile_ok && step * HF_C + cl < g.C;
             float t[6][6];
 #pragma unroll
             for (int p = 0; p < 6; ++p) {
-                const int x = x0 + p;
-                const bool rok = ok && x >= 0 && x < g.H;
-                const __half2 h01 = *reinterpret_cast<const __half2 *>(&rmid[p].x);
-                const __half2 h23 = *reinterpret_cast<const __half2 *>(&rmid[p].y);
-                const float d[6] = {(rok && y0 >= 0) ? __half2float(rl[p]) : 0.0f,
-                                    rok ? __low2float(h01) : 0.0f,
-                                    rok ? __high2float(h01) : 0.0f,
-                                    rok ? __low2float(h23) : 0.0f,
-                                    rok ? __high2float(h23) : 0.0f,
-                                    (rok && y0 + 5 < g.W) ? __half2float(rr[p]) : 0.0f};
+                const unsigned w01 = rmid[p][0], w23 = rmid[p][1];      // (a bit cast wants a scalar object, not a vector element)
+                const __half2 h01 = __builtin_bit_cast(__half2, w01);
+                const __half2 h23 = __builtin_bit_cast(__half2, w23);
+                const float d[6] = {__half2float(__builtin_bit_cast(__half, rl[p])), __low2float(h01), __high2float(h01),
+                                    __low2float(h23), __high2float(h23), __half2float(__builtin_bit_cast(__half, rr[p]))};
                 bt_mul<4>(d, t[p]);
             }
-            if (step + 1 < nsteps) load_raw(step + 1);
             __half *dst = Vs + ((size_t)(cl >> 2) * HF_P + tl) * 4 + (cl & 3);   // [e][c / 4][tile][c % 4]
 #pragma unroll
             for (int q = 0; q < 6; ++q) {
@@ -162,8 +185,12 @@ __global__ __launch_bounds__(HF_T, 2) void fused_f16_kernel(const __half *__rest
                 for (int p = 0; p < 6; ++p) dst[(size_t)(p * 6 + q) * (HF_P * 8)] = __float2half_rn(o[p]);
             }
         }
-        __builtin_amdgcn_s_waitcnt(0xc07f);   // LDS writes done; the global loads stay in flight
+        // this step's filters (requested a step ago) and the LDS stores above must have landed; the next step's
+        // filters, requested at the top of this step, are waited for as well (they had the transform to arrive)
+        __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
+        // the taps of the next step: in flight during the multiply phase below
+        if (more) load_raw(step + 1);
         // 2. nine components x (32 filters x 32 tiles x 8 channels); lane (li, lg) feeds channels 4 lg .. 4 lg + 3
 #pragma unroll
         for (int e = 0; e < 9; ++e) {
@@ -173,8 +200,7 @@ __global__ __launch_bounds__(HF_T, 2) void fused_f16_kernel(const __half *__rest
             acc[e] = __builtin_amdgcn_mfma_f32_32x32x8f16(*reinterpret_cast<const halfx4_h *>(&ua),
                                                           *reinterpret_cast<const halfx4_h *>(&vb), acc[e], 0, 0, 0);
         }
-        __builtin_amdgcn_s_waitcnt(0xc07f);
-        __builtin_amdgcn_s_barrier();
+        hf_lds_barrier();
     }
     __syncthreads();
 
@@ -219,23 +245,34 @@ __global__ __launch_bounds__(HF_T, 2) void fused_f16_kernel(const __half *__rest
 #pragma unroll
             for (int p = 0; p < 4; ++p)
                 if (orow + p < g.Ho)
-                    *reinterpret_cast<floatx4_h *>(dst + (size_t)p * g.Wo) = floatx4_h{y[p][0], y[p][1], y[p][2], y[p][3]};
+                    __builtin_nontemporal_store(floatx4_h{y[p][0], y[p][1], y[p][2], y[p][3]},
+                                                reinterpret_cast<floatx4_h *>(dst + (size_t)p * g.Wo));
         }
         __syncthreads();
     }
+    }   // items
 }
 
 bool fused_f16_eligible(const Geo &g)
 {
-    return g.dt == WINO_F16 && g.m == 4 && g.pad == 1 && g.W % 4 == 0;
+    // the tiles of one workgroup span at most `span` images; their byte offsets from the first must stay below 2^30
+    const unsigned long long tiles = (unsigned long long)g.Th * g.Tw;
+    const unsigned long long span = (HF_P + tiles - 2) / tiles + 1;
+    const unsigned long long image_bytes = (unsigned long long)g.C * g.H * g.W * 2ull;
+    return g.dt == WINO_F16 && g.m == 4 && g.pad == 1 && g.W % 4 == 0 && span * image_bytes + 65536 < HF_MAX_BYTES;
 }
 
 hipError_t launch_fused_f16(const Geo &g, const void *D, const void *U, float *Y, hipStream_t s)
 {
     const int n_kb = (g.Kp + HF_K - 1) / HF_K;
-    const long long blocks = (long long)((g.P + HF_P - 1) / HF_P) * n_kb;
-    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    fused_f16_kernel<<<dim3((unsigned)blocks), dim3(HF_T), 0, s>>>((const __half *)D, (const uint4 *)U, Y, g, n_kb);
+    const long long items = (long long)((g.P + HF_P - 1) / HF_P) * n_kb;
+    if (items > 0x7fffffffLL) return hipErrorInvalidValue;
+    // two workgroups per CU (what registers and LDS allow) on 256 CUs, in multiples of the 8 XCDs
+    const unsigned grid = (unsigned)(items >= 512 ? 512 : (items + 7) / 8 * 8);
+    if (g.Cp != g.C)   // the channel loop runs over Cp: slots past C must be fetched as zeros
+        fused_f16_kernel<true><<<dim3(grid), dim3(HF_T), 0, s>>>((const __half *)D, (const uint4 *)U, Y, g, n_kb, (int)items);
+    else
+        fused_f16_kernel<false><<<dim3(grid), dim3(HF_T), 0, s>>>((const __half *)D, (const uint4 *)U, Y, g, n_kb, (int)items);
     return hipGetLastError();
 }
 
