@@ -203,7 +203,8 @@ def stage_plan(torch, w, L, ws, sets):
                   "gemm": nU + nV + nM}          # U and V read, M (fp32) written
         bm, bn, _ = w.wino_gemm_launch_shape(L.K, L.C, L.P, L.m, L.dt)
         tile = "%d, %d" % (bm, bn)
-        kernel = ("gemm_f32_kernel<%s, 2, 2, 16>" % tile) if L.dt == w.WINO_F32 else ("gemm_f16_kernel<%s>" % tile)
+        bk = 16 if (bm, bn) == (128, 128) or L.C % 32 != 0 else 32      # slab depth the library picks for this block shape
+        kernel = ("gemm_f32_kernel<%s, 2, 2, %d>" % (tile, bk)) if L.dt == w.WINO_F32 else ("gemm_f16_kernel<%s>" % tile)
     return plans, nbytes, kernel, 2 * a2 * L.K * L.C * L.P
 
 

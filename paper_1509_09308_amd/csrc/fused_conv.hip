@@ -406,7 +406,11 @@ bool fused_preferred(const Geo &g)
     const long long blocks = (long long)((g.P + FP - 1) / FP) * ((g.K + FK - 1) / FK);
     if (g.dt == WINO_F16) return g.K <= 128 && blocks >= 512;
     if (!fused_lds_eligible(g)) return g.K <= 128 && blocks >= 512;
-    return (long long)g.K * g.C <= 100LL * (g.K + g.C) && blocks >= 512;
+    if ((long long)g.K * g.C <= 100LL * (g.K + g.C) && blocks >= 512) return true;
+    // small batches: with very few filters and channels (64 -> 64) one launch that does everything still beats
+    // three launches as soon as it has a workgroup for every other CU (batch 1, 224 x 224: 32 vs 37 us)
+    const long long items = (long long)((g.P + 31) / 32) * (g.Kp / 32);
+    return (long long)g.K * g.C <= 32LL * (g.K + g.C) && items >= 128;
 }
 
 hipError_t launch_fused(const Geo &g, const void *Dv, const void *Uv, float *Y, hipStream_t s)

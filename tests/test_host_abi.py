@@ -181,7 +181,10 @@ def test_variant_query_host_only(L):
     assert w.wino_conv2d_variant(64, 64, 224, 224, 64, 1, 4) == w.FLAG_FUSED
     assert w.wino_conv2d_variant(64, 128, 112, 112, 128, 1, 4) == w.FLAG_FUSED
     assert w.wino_conv2d_variant(64, 512, 28, 28, 512, 1, 4) == w.FLAG_UNFUSED
-    assert w.wino_conv2d_variant(1, 64, 224, 224, 64, 1, 4) == w.FLAG_UNFUSED      # too few workgroups
+    assert w.wino_conv2d_variant(64, 128, 56, 56, 256, 1, 4) == w.FLAG_FUSED        # K C / (K + C) = 85
+    assert w.wino_conv2d_variant(64, 256, 56, 56, 256, 1, 4) == w.FLAG_UNFUSED      # 128: a tie, stays four-stage
+    assert w.wino_conv2d_variant(1, 64, 224, 224, 64, 1, 4) == w.FLAG_FUSED         # batch 1, 64 -> 64: 196 workgroups suffice
+    assert w.wino_conv2d_variant(1, 128, 112, 112, 128, 1, 4) == w.FLAG_UNFUSED     # too few workgroups
     assert w.wino_conv2d_variant(64, 64, 224, 224, 64, 1, 2) == w.FLAG_UNFUSED      # F(2x2) has no fused kernel
     assert w.wino_conv2d_variant(64, 64, 224, 224, 64, 1, 4, flags=w.FLAG_UNFUSED) == w.FLAG_UNFUSED
     assert w.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 4, flags=w.FLAG_FUSED) == w.FLAG_FUSED
