@@ -404,7 +404,8 @@ bool fused_preferred(const Geo &g)
 {
     if (!fused_eligible(g)) return false;
     const long long blocks = (long long)((g.P + FP - 1) / FP) * ((g.K + FK - 1) / FK);
-    if (g.dt == WINO_F16) return g.K <= 128 && blocks >= 512;
+    if (g.dt == WINO_F16)   // same crossover as in fp32 (N = 32: 128 -> 256 channels 0.139 vs 0.155 ms, 256 -> 256 0.249 vs 0.197)
+        return (long long)g.K * g.C <= 100LL * (g.K + g.C) && (long long)((g.P + 31) / 32) * ((g.K + 63) / 64) >= 256;
     if (!fused_lds_eligible(g)) return g.K <= 128 && blocks >= 512;
     if ((long long)g.K * g.C <= 100LL * (g.K + g.C) && blocks >= 512) return true;
     // small batches: with very few filters and channels (64 -> 64) one launch that does everything still beats

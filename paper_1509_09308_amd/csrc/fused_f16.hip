@@ -5,22 +5,25 @@
 // all 36 components of a 64-filter x 32-tile block in registers and the layer costs one read of D
 // and one write of Y.
 //
-// Workgroup = 4 wavefronts owning 32 filters x 32 tiles, small enough in registers and LDS for two
-// workgroups per CU: the phases below alternate inside a workgroup, so a second one is what keeps
-// the memory system busy while the first computes or stores.  Per step of 8 channels:
-//   1. transform phase: every thread unpacks the 6 x 6 fp16 tile of one (tile, channel) pair (per row
+// Workgroup = 4 KH wavefronts owning 32 KH filters x 32 tiles.  KH = 1 is small enough in registers and
+// LDS for two workgroups per CU.  KH = 2 (one workgroup per CU, used when the layer has more than 32
+// filters) lets a second set of four wavefronts multiply the same transformed tiles with 32 more filters:
+// the input transform, which costs a wavefront four times what its share of the multiply does, is then
+// done once per 64 filters instead of once per 32.  Per step of 8 channels:
+//   1. transform phase: every thread of the first four wavefronts unpacks the 6 x 6 fp16 tile of one (tile, channel) pair (per row
 //      one aligned 8-byte load and the two outer columns, requested one step ahead; zeros outside
 //      the image), computes v = B^T (d B) in fp32, rounds once to fp16 and writes the 36 values to
 //      LDS in the operand order of the MFMA, [e][c / 4][tile][c % 4]; the 36 x 32 x 8 transformed filters
 //      of the step are copied from U (same order, [e][c / 8][k][c % 8]) with 16-byte loads;
 //   2. multiply phase: wavefront cg owns components 9 cg .. 9 cg + 8: one v_mfma_f32_32x32x8_f16
 //      per component, both operands one 8-byte LDS read per lane, fp32 accumulation.
-// After the last step the accumulators go through LDS in four pieces of 8 filters, every thread
+// After the last step the accumulators go through LDS in four pieces of 8 KH filters, every thread
 // gathers the 36 components of one (filter, tile) pair, applies Y = A^T m A and writes the 4 x 4
 // outputs that are inside the image as 16-byte rows.
 // Needs m = 4, pad = 1, W % 4 == 0 (aligned 8-byte loads and 16-byte stores), fp32 Y.
 #include "wino_internal.h"
 #include "transforms.h"
+#include <mutex>
 
 namespace wino {
 
@@ -28,13 +31,13 @@ typedef float floatx16_h __attribute__((ext_vector_type(16)));
 typedef float floatx4_h __attribute__((ext_vector_type(4)));
 typedef _Float16 halfx4_h __attribute__((ext_vector_type(4)));
 
-constexpr int HF_K = 32, HF_P = 32, HF_C = 8, HF_T = 256;         // filters, tiles, channels per step, threads
-constexpr int HF_U_WORDS = 36 * HF_K;                             // 16-byte words of U per step
+constexpr int HF_P = 32, HF_C = 8;                                // tiles per workgroup, channels per step
 constexpr int HF_V_WORDS = 36 * HF_P;                             // 16-byte words of V per step
-constexpr int HF_M_FLOATS = 36 * 8 * HF_P;                        // one piece of M in the epilogue
-constexpr int HF_LDS_WORDS = 2 * HF_U_WORDS + HF_V_WORDS;           // two filter buffers and one for V
-static_assert(HF_M_FLOATS * 4 <= HF_LDS_WORDS * 16, "the epilogue reuses the operand area");
-static_assert(HF_U_WORDS % 64 == 0, "filters are copied in chunks of one 16-byte word per lane");
+constexpr int hf_u_words(int KH) { return 36 * 32 * KH; }         // 16-byte words of U per step
+constexpr int hf_lds_words(int KH) { return 2 * hf_u_words(KH) + HF_V_WORDS; }   // two filter buffers and one for V
+constexpr int hf_m_floats(int KH) { return 36 * 8 * KH * HF_P; }  // one piece of M in the epilogue
+static_assert(hf_m_floats(1) * 4 <= hf_lds_words(1) * 16 && hf_m_floats(2) * 4 <= hf_lds_words(2) * 16,
+              "the epilogue reuses the operand area");
 
 #define WINO_H_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 #define WINO_H_GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
@@ -46,15 +49,24 @@ __device__ __forceinline__ void hf_lds_barrier()
     __builtin_amdgcn_s_barrier();
 }
 
+// 16 bytes per lane from a buffer straight into LDS: lane l of the wavefront fills lds + 16 l.  (Kept out of the
+// kernel template: the host pass of the compiler cannot check this builtin in a context that depends on a
+// template parameter and would drop the kernel without a diagnostic.)
+__device__ __forceinline__ void hf_copy16_to_lds(__amdgpu_buffer_rsrc_t rsrc, uint4 *lds, unsigned voffset, unsigned soffset)
+{
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, WINO_H_LDS_PTR(lds), 16, voffset, soffset, 0, 0);
+}
+
 constexpr unsigned HF_MAX_BYTES = 0x40000000u;                     // longest stretch of D one workgroup's buffer covers
 constexpr unsigned HF_ROW_OOB = 0x80000000u, HF_COL_OOB = 0x40000000u;   // offset markers of taps outside the image
 
 // CPAD: the channel loop (over the padded count Cp) holds channel slots past the last channel.
-template <bool CPAD>
-__global__ __launch_bounds__(HF_T, 2) void fused_f16_kernel(const __half *__restrict__ D, const uint4 *__restrict__ U,
-                                                            float *__restrict__ Y, Geo g, int n_kb, int n_items)
+template <bool CPAD, int KH>
+__global__ __launch_bounds__(256 * KH, 3 - KH) void fused_f16_kernel(const __half *__restrict__ D, const uint4 *__restrict__ U,
+                                                                     float *__restrict__ Y, Geo g, int n_kb, int n_items)
 {
-    __shared__ uint4 smem[HF_LDS_WORDS];
+    constexpr int HF_K = 32 * KH, HF_U_WORDS = hf_u_words(KH), WAVES = 4 * KH;
+    extern __shared__ uint4 smem[];                                 // hf_lds_words(KH) words
     uint4 *Us = smem;                                               // buffer b at + b * HF_U_WORDS
     __half *Vs = reinterpret_cast<__half *>(smem + 2 * HF_U_WORDS);
     const uint4 *Vw = smem + 2 * HF_U_WORDS;
@@ -71,7 +83,7 @@ __global__ __launch_bounds__(HF_T, 2) void fused_f16_kernel(const __half *__rest
     const int k0 = kb * HF_K, b0 = tb * HF_P;
 
     // ---- transform-phase role: (tile, channel of the step) ------------------------------------
-    const int tl = tid & 31, cl = tid >> 5;
+    const int tl = tid & 31, cl = (tid >> 5) & 7;
     const int b = b0 + tl;
     const bool tile_ok = b < g.P;
     // The taps are loaded through a buffer that starts at the first image this workgroup touches.  A row outside the
@@ -107,7 +119,8 @@ __global__ __launch_bounds__(HF_T, 2) void fused_f16_kernel(const __half *__rest
 
     // ---- multiply-phase role -------------------------------------------------------------------
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    const int cg = wave;
+    const int cg = wave & 3, kh = wave >> 2;                   // nine components, 32 filters
+    const bool xf = KH == 1 || wave < 4;                       // takes part in the transform phase
     const int li = lane & 31, lg = lane >> 5;
     floatx16_h acc[9];
 #pragma unroll
@@ -118,8 +131,7 @@ __global__ __launch_bounds__(HF_T, 2) void fused_f16_kernel(const __half *__rest
     const int nsteps = g.Cp / HF_C;
 
     // raw fp16 taps of one tile: per row the four middle columns (8 bytes) and the two outer ones.
-    // They are requested one step ahead: the loads of step s+1 are issued as soon as step s has
-    // unpacked its own, and stay in flight during the transform, the multiply and the next filter copy.
+    // They are requested one step ahead, at the start of the multiply phase of the step before.
     typedef unsigned uintx2_h __attribute__((ext_vector_type(2)));
     uintx2_h rmid[6];
     unsigned short rl[6], rr[6];
@@ -137,26 +149,24 @@ __global__ __launch_bounds__(HF_T, 2) void fused_f16_kernel(const __half *__rest
     // Transformed filters of a step, [e][c8 = step][k] -> Us[e * 32 + k]: direct global -> LDS loads of
     // 16 bytes per lane (no registers), one step ahead into the other buffer; a step waits for all of its own
     // requests (vmcnt(0)) before the barrier that precedes its multiply phase.
-    constexpr int NCH = (HF_U_WORDS / 64 + 3) / 4;   // chunks of 64 words per wavefront
-    unsigned uoff[NCH];                              // byte offset of this lane's word in step 0
-#pragma unroll
-    for (int j = 0; j < NCH; ++j) {
-        const int w = min(wave + 4 * j, HF_U_WORDS / 64 - 1) * 64 + lane;
-        uoff[j] = ((unsigned)((w / HF_K) * nsteps) * g.Kp + min(k0 + w % HF_K, g.Kp - 1)) * 16u;
-    }
+    constexpr int NCH = (HF_U_WORDS / 64 + WAVES - 1) / WAVES;   // chunks of 64 words per wavefront
+    // chunk wave + WAVES j holds components (64 / HF_K)(wave + WAVES j) ..: the lane's word of chunk j lies a fixed
+    // number of bytes behind its word of chunk 0
+    const int w0 = wave * 64 + lane;
+    const unsigned uoff = ((unsigned)((w0 / HF_K) * nsteps) * g.Kp + min(k0 + w0 % HF_K, g.Kp - 1)) * 16u;   // step 0
+    const unsigned uj_bytes = (unsigned)(WAVES * 64 / HF_K) * (unsigned)nsteps * (unsigned)g.Kp * 16u;
     const __amdgpu_buffer_rsrc_t rsrc_u =
         __builtin_amdgcn_make_buffer_rsrc((void *)U, 0, (unsigned)((size_t)36 * nsteps * g.Kp * 16), 0x00020000);
     auto load_u = [&](int buf, int step) {
         const unsigned so = (unsigned)step * (unsigned)g.Kp * 16u;
 #pragma unroll
         for (int j = 0; j < NCH; ++j) {
-            const int chunk = wave + 4 * j;
+            const int chunk = wave + WAVES * j;
             if (chunk < HF_U_WORDS / 64)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_u, WINO_H_LDS_PTR(Us + buf * HF_U_WORDS + chunk * 64), 16,
-                                                         uoff[j], so, 0, 0);
+                hf_copy16_to_lds(rsrc_u, Us + buf * HF_U_WORDS + chunk * 64, uoff, so + j * uj_bytes);
         }
     };
-    load_raw(0);
+    if (xf) load_raw(0);
     load_u(0, 0);
     for (int step = 0; step < nsteps; ++step) {
         const uint4 *Ub = Us + (step & 1) * HF_U_WORDS;
@@ -164,7 +174,7 @@ __global__ __launch_bounds__(HF_T, 2) void fused_f16_kernel(const __half *__rest
         // the filters of the next step, into the buffer the previous multiply phase has finished with
         if (more) load_u((step + 1) & 1, step + 1);
         // 1. one input tile: unpack, transform rows then columns (v = B^T (d B)), round, scatter
-        {
+        if (xf) {
             float t[6][6];
 #pragma unroll
             for (int p = 0; p < 6; ++p) {
@@ -190,12 +200,12 @@ __global__ __launch_bounds__(HF_T, 2) void fused_f16_kernel(const __half *__rest
         __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
         // the taps of the next step: in flight during the multiply phase below
-        if (more) load_raw(step + 1);
+        if (xf && more) load_raw(step + 1);
         // 2. nine components x (32 filters x 32 tiles x 8 channels); lane (li, lg) feeds channels 4 lg .. 4 lg + 3
 #pragma unroll
         for (int e = 0; e < 9; ++e) {
             const int ee = cg * 9 + e;
-            const uint2 ua = reinterpret_cast<const uint2 *>(Ub)[(ee * HF_K + li) * 2 + lg];
+            const uint2 ua = reinterpret_cast<const uint2 *>(Ub)[(ee * HF_K + kh * 32 + li) * 2 + lg];
             const uint2 vb = reinterpret_cast<const uint2 *>(Vw)[(ee * 2 + lg) * HF_P + li];
             acc[e] = __builtin_amdgcn_mfma_f32_32x32x8f16(*reinterpret_cast<const halfx4_h *>(&ua),
                                                           *reinterpret_cast<const halfx4_h *>(&vb), acc[e], 0, 0, 0);
@@ -204,9 +214,9 @@ __global__ __launch_bounds__(HF_T, 2) void fused_f16_kernel(const __half *__rest
     }
     __syncthreads();
 
-    // ---- inverse transform: four pieces of 8 filters -------------------------------------------
+    // ---- inverse transform: four pieces of 8 filters of every 32 ---------------------------------
     float *Ms = reinterpret_cast<float *>(smem);
-    const int frow = tid >> 5;                 // 0..7: filter row of the piece handled in the gather
+    const int frow = tid >> 5;                 // 0 .. 8 KH - 1: filter row of the piece handled in the gather
     const int ot = tid & 31;                   // tile of the gather (same tile as in the transform phase)
     float *ybase = Y;
     int orow = 0;
@@ -222,15 +232,16 @@ __global__ __launch_bounds__(HF_T, 2) void fused_f16_kernel(const __half *__rest
 #pragma unroll
         for (int e = 0; e < 9; ++e)
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) Ms[((cg * 9 + e) * 8 + 4 * lg + rr) * HF_P + li] = acc[e][4 * q + rr];
+            for (int rr = 0; rr < 4; ++rr)
+                Ms[((cg * 9 + e) * (8 * KH) + 8 * kh + 4 * lg + rr) * HF_P + li] = acc[e][4 * q + rr];
         __syncthreads();
-        const int k = k0 + 8 * q + frow;
+        const int k = k0 + 32 * (frow >> 3) + 8 * q + (frow & 7);
         if (tile_ok && k < g.K) {
             float m[6][6], tt[4][6], y[4][4];
 #pragma unroll
             for (int xi = 0; xi < 6; ++xi)
 #pragma unroll
-                for (int nu = 0; nu < 6; ++nu) m[xi][nu] = Ms[((xi * 6 + nu) * 8 + frow) * HF_P + ot];
+                for (int nu = 0; nu < 6; ++nu) m[xi][nu] = Ms[((xi * 6 + nu) * (8 * KH) + frow) * HF_P + ot];
 #pragma unroll
             for (int nu = 0; nu < 6; ++nu) {
                 const float col[6] = {m[0][nu], m[1][nu], m[2][nu], m[3][nu], m[4][nu], m[5][nu]};
@@ -262,18 +273,40 @@ bool fused_f16_eligible(const Geo &g)
     return g.dt == WINO_F16 && g.m == 4 && g.pad == 1 && g.W % 4 == 0 && span * image_bytes + 65536 < HF_MAX_BYTES;
 }
 
-hipError_t launch_fused_f16(const Geo &g, const void *D, const void *U, float *Y, hipStream_t s)
+template <bool CPAD, int KH>
+static hipError_t launch_one(const Geo &g, const void *D, const void *U, float *Y, hipStream_t s)
 {
+    constexpr int HF_K = 32 * KH;
+    constexpr size_t lds = (size_t)hf_lds_words(KH) * 16;
     const int n_kb = (g.Kp + HF_K - 1) / HF_K;
     const long long items = (long long)((g.P + HF_P - 1) / HF_P) * n_kb;
     if (items > 0x7fffffffLL) return hipErrorInvalidValue;
-    // two workgroups per CU (what registers and LDS allow) on 256 CUs, in multiples of the 8 XCDs
-    const unsigned grid = (unsigned)(items >= 512 ? 512 : (items + 7) / 8 * 8);
-    if (g.Cp != g.C)   // the channel loop runs over Cp: slots past C must be fetched as zeros
-        fused_f16_kernel<true><<<dim3(grid), dim3(HF_T), 0, s>>>((const __half *)D, (const uint4 *)U, Y, g, n_kb, (int)items);
-    else
-        fused_f16_kernel<false><<<dim3(grid), dim3(HF_T), 0, s>>>((const __half *)D, (const uint4 *)U, Y, g, n_kb, (int)items);
+    if (lds > 65536) {   // beyond the default limit of a launch: raised once per device
+        static std::mutex mu;
+        static bool done[64] = {};
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+        std::lock_guard<std::mutex> lock(mu);
+        if (!done[dev]) {
+            e = hipFuncSetAttribute((const void *)fused_f16_kernel<CPAD, KH>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            done[dev] = true;
+        }
+    }
+    // as many workgroups as stay resident on 256 CUs (registers and LDS allow 3 - KH per CU), in multiples of the 8 XCDs
+    const long long resident = 256 * (3 - KH);
+    const unsigned grid = (unsigned)(items >= resident ? resident : (items + 7) / 8 * 8);
+    fused_f16_kernel<CPAD, KH><<<dim3(grid), dim3(256 * KH), lds, s>>>((const __half *)D, (const uint4 *)U, Y, g, n_kb, (int)items);
     return hipGetLastError();
+}
+
+hipError_t launch_fused_f16(const Geo &g, const void *D, const void *U, float *Y, hipStream_t s)
+{
+    const bool cpad = g.Cp != g.C;   // the channel loop runs over Cp: slots past C must be fetched as zeros
+    if (g.Kp > 32) return cpad ? launch_one<true, 2>(g, D, U, Y, s) : launch_one<false, 2>(g, D, U, Y, s);
+    return cpad ? launch_one<true, 1>(g, D, U, Y, s) : launch_one<false, 1>(g, D, U, Y, s);
 }
 
 }  // namespace wino
