@@ -190,7 +190,9 @@ def stage_plan(torch, w, L, ws, sets):
                           ("fused", (lambda d=d, y=y: w.wino_conv2d_fwd_ex(d, U=U, K=L.K, pad=1, m=L.m, Y=y, workspace=ws,
                                                                            flags=w.FLAG_FUSED)))])
         nbytes = {"filter": 9 * L.K * L.C * s + nU, "fused": nD + nU + nY}
-        kernel = "fused_lds_kernel<%s>" % ("false" if L.C % 8 == 0 else "true") if L.dt == w.WINO_F32 else "fused_f16_kernel"
+        cpad = "false" if L.C % 8 == 0 else "true"
+        kernel = ("fused_lds_kernel<%s>" % cpad if L.dt == w.WINO_F32 else
+                  "fused_f16_kernel<%s, %d>" % (cpad, 2 if L.K > 32 else 1))
     else:
         Vs = [w.alloc_v(L.C, L.P, L.m, L.dt) for _ in range(sets)]
         Ms = [w.alloc_m(L.K, L.P, L.m) for _ in range(sets)]

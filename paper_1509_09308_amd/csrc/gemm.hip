@@ -198,7 +198,7 @@ __global__ __launch_bounds__(256) void gemm_f16_kernel(const uint4 *__restrict__
     __shared__ uint4 As[2][A4];
     __shared__ uint4 Bs[2][B4];
 
-    int bid = blockIdx.x;
+    int bid = xcd_remap(blockIdx.x, gridDim.x);   // the filter blocks that share a run of V meet in one L2
     const int tm_i = bid % tiles_m;
     bid /= tiles_m;
     const int tn_i = bid % tiles_n;
