@@ -24,8 +24,6 @@ def build(verbose=False):
     """Always recompiles; returns the path of the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     flags = list(HIPCC_FLAGS)
-    if os.environ.get("WINO_TUNING") == "1":
-        flags.append("-DWINO_TUNING")       # lets WINO_* environment variables override launch choices (sweeps)
     cmd = [hipcc] + flags + ["-o", LIB_PATH] + sources()
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
@@ -33,7 +31,7 @@ def build(verbose=False):
     if verbose:
         print(res.stderr)
     with open(HASH_PATH, "w") as fh:
-        fh.write(("tuning-" if "-DWINO_TUNING" in flags else "") + source_hash() + "\n")
+        fh.write(source_hash() + "\n")
     return LIB_PATH
 
 

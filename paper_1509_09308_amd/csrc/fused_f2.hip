@@ -402,7 +402,6 @@ static void f2_plan(const Geo &g, size_t workspace_bytes, bool may_split, int *s
     const int nsteps = (g.C + F2_C - 1) / F2_C;
     long long s = 1;
     if (base < 192) s = (512 + base - 1) / base < 16 ? (512 + base - 1) / base : 16;
-    if (const char *t = tuning_env("WINO_F2_SPLITS")) s = atoi(t);     // tuning only
     const long long fit = (long long)(workspace_bytes / ((size_t)base * F2_K * F2_P * 4 * sizeof(float)));
     if (s > fit) s = fit;
     if (s > nsteps) s = nsteps;

@@ -331,23 +331,9 @@ static GemmShape gemm_shape(const Geo &g)
     auto blocks = [&](int bm, int bn) {
         return (long long)((g.Kp + bm - 1) / bm) * ((g.Pp + bn - 1) / bn) * g.a2;
     };
-    const char *tile = tuning_env("WINO_GEMM_TILE");   // tuning sweeps only: 1 = 64x64, 2 = 128x64, 3 = 64x128
-    if (tile) {
-        const int t = atoi(tile);
-        if (t == 1) { sh.bm = 64; sh.bn = 64; }
-        if (t == 2) { sh.bm = 128; sh.bn = 64; }
-        if (t == 3) { sh.bm = 64; sh.bn = 128; }
-    } else {
-        if (blocks(sh.bm, sh.bn) < 512 && sh.bn == 128) sh.bn = 64;
-        if (blocks(sh.bm, sh.bn) < 512 && sh.bm == 128) sh.bm = 64;
-    }
+    if (blocks(sh.bm, sh.bn) < 512 && sh.bn == 128) sh.bn = 64;
+    if (blocks(sh.bm, sh.bn) < 512 && sh.bm == 128) sh.bm = 64;
     const int nk = g.Cp / 16;
-    const char *tune = tuning_env("WINO_GEMM_SPLITS");   // tuning sweeps only
-    if (tune) {
-        const int want = atoi(tune);
-        while (sh.splits < want && nk % (sh.splits * 2) == 0) sh.splits *= 2;
-        return sh;
-    }
     const long long b = blocks(sh.bm, sh.bn);
     while (sh.splits < 8 && b * sh.splits * 2 <= 256 && nk % (sh.splits * 2) == 0 && nk / (sh.splits * 2) >= 2)
         sh.splits *= 2;

@@ -103,8 +103,7 @@ __global__ __launch_bounds__(512) void input_transform_f16_kernel(const __half *
 hipError_t launch_input_transform(const Geo &g, const void *D, void *V, hipStream_t s)
 {
     dim3 grid((g.Pp + 255) / 256, g.Cp), block(256);
-    const char *tune = tuning_env("WINO_IT_PAIR");   // tuning only
-    if (g.dt == WINO_F32 && g.m == 4 && g.pad == 1 && g.W % 8 == 0 && !(tune && tune[0] == '0')) {
+    if (g.dt == WINO_F32 && g.m == 4 && g.pad == 1 && g.W % 8 == 0) {
         dim3 grid2((g.Pp / 2 + 255) / 256, g.Cp);
         input_transform_pair_kernel<4><<<grid2, block, 0, s>>>((const float *)D, (float *)V, g);
         return hipGetLastError();

@@ -33,9 +33,8 @@ hipError_t launch_prep(const Geo &g, const float *G, float *U, const float *D, f
 {
     const int ft_gx = (g.Kp + FT_KT - 1) / FT_KT, ft_gy = (g.Cp + FT_CT - 1) / FT_CT;
     const long long ft_blocks = (long long)ft_gx * ft_gy;
-    const char *tune = tuning_env("WINO_IT_PAIR");   // tuning only
     int it = 0;
-    if (g.m == 4 && g.pad == 1 && g.W % 8 == 0 && !(tune && tune[0] == '0')) it = 2;
+    if (g.m == 4 && g.pad == 1 && g.W % 8 == 0) it = 2;
     else if (g.m == 4 && g.pad == 1 && g.W % 4 == 0) it = 1;
     const int it_gx = it == 2 ? (g.Pp / 2 + 255) / 256 : (g.Pp + 255) / 256;
     const long long blocks = ft_blocks + (long long)it_gx * g.Cp;

@@ -622,10 +622,8 @@ static void wgrad_shape(const WgradGeo &g, int *bm, int *bn, int *shares, int *n
 // (every 64 x 64 block of M repeats both transforms, so their cost grows with K * C).
 static bool wgrad_fused_ok(const WgradGeo &g)
 {
-    const char *tune = tuning_env("WINO_WGRAD_FUSED");   // tuning only: 0 = never, 1 = whenever possible
     if (g.W % 4 != 0) return false;
     if ((long long)g.N * (g.K > g.C ? g.K : g.C) * g.H * g.W >= (1LL << 31)) return false;   // 32-bit offsets
-    if (tune) return tune[0] == '1';
     return g.K <= 256 && g.C <= 256;   // measured at N=64: faster up to 256 x 256, slower at 512 x 512
 }
 

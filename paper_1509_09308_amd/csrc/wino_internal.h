@@ -10,18 +10,6 @@
 
 namespace wino {
 
-// Environment variables that override launch choices exist for tuning sweeps only: they are read only by a
-// library built with -DWINO_TUNING (build.py with WINO_TUNING=1 in the environment); a normal build ignores them.
-inline const char *tuning_env(const char *name)
-{
-#ifdef WINO_TUNING
-    return getenv(name);
-#else
-    (void)name;
-    return nullptr;
-#endif
-}
-
 
 // Problem geometry and the padded extents of the transform-domain buffers.
 struct Geo {
