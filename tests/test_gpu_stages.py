@@ -136,7 +136,13 @@ def test_integer_layer_end_to_end_exact(m):
 
 @pytest.mark.parametrize("shape", [(1, 3, 20, 20, 8, 3, 3, 1, 1), (2, 3, 17, 23, 5, 5, 5, 2, 2),
                                    (1, 20, 9, 9, 33, 1, 1, 0, 1), (2, 4, 12, 10, 16, 3, 2, 1, 1),
-                                   (1, 3, 224, 224, 64, 3, 3, 1, 1)])
+                                   (1, 3, 224, 224, 64, 3, 3, 1, 1),
+                                   # 3 x 3, stride 1, 1-4 channels (matrix-unit form): ragged row bands, column blocks
+                                   # and filter blocks, both pads
+                                   (2, 1, 9, 12, 70, 3, 3, 1, 1), (1, 2, 10, 36, 33, 3, 3, 0, 1),
+                                   (2, 4, 7, 40, 64, 3, 3, 1, 1), (1, 3, 6, 260, 5, 3, 3, 1, 1),
+                                   (1, 3, 3, 4, 130, 3, 3, 0, 1),
+                                   (40, 3, 50, 36, 70, 3, 3, 1, 1)])   # enough workgroups for four-row bands
 def test_direct_fallback(shape):
     torch, w = require_gpu()
     N, C, H, W, K, R, S, pad, stride = shape
@@ -153,7 +159,8 @@ def test_direct_fallback(shape):
 
 
 @pytest.mark.parametrize("shape", [(1, 3, 20, 20, 8, 3, 3, 1, 1), (2, 3, 17, 23, 5, 3, 3, 1, 1), (2, 5, 12, 16, 33, 3, 3, 0, 1),
-                                   (1, 4, 9, 11, 6, 5, 3, 2, 2), (2, 3, 224, 224, 64, 3, 3, 1, 1)])
+                                   (1, 4, 9, 11, 6, 5, 3, 2, 2), (2, 3, 224, 224, 64, 3, 3, 1, 1),
+                                   (2, 4, 9, 36, 70, 3, 3, 0, 1), (1, 1, 5, 8, 3, 3, 3, 1, 1)])
 def test_direct_fallback_f16_storage(shape):
     """fp16 D, G and Y, fp32 accumulation: within one fp16 rounding of the oracle on the same stored values,
     and exact where the result is representable."""
