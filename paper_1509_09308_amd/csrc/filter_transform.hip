@@ -14,55 +14,13 @@ __global__ __launch_bounds__(256) void filter_transform_kernel(const T *__restri
     filter_transform_block<M, T>(G, U, K, C, Kp, Cp, blockIdx.x, blockIdx.y, gs);
 }
 
-// fp16 storage.  U is laid out [e][c/8][k][c%8] (the 8 channels a lane feeds to one fp16 MFMA are 16 bytes), so a
-// (k, c) thread owns isolated 2-byte elements of U.  A workgroup therefore takes 64 filters x 8 channels (their
-// 72 source values per filter are contiguous in G), transforms in fp32, rounds once to fp16, collects the results
-// in LDS and writes U in 16-byte units: 1 KB contiguous per component and wavefront instead of 64 scattered
-// 2-byte stores.
+// fp16 storage: see filter_transform_f16_block.
 template <int M>
 __global__ __launch_bounds__(256) void filter_transform_f16_kernel(const __half *__restrict__ G, __half *__restrict__ U,
                                                                    int K, int C, int Kp, int Cp)
 {
-    constexpr int A = M + 2, A2 = A * A, KT = 64, CT = 8, ROW = CT * 9 + 1;
-    __shared__ float gs[KT * ROW];
-    __shared__ __attribute__((aligned(16))) __half us[A2 * KT * CT];
-    const int k0 = blockIdx.x * KT, c0 = blockIdx.y * CT;
-    for (int idx = threadIdx.x; idx < KT * CT * 9; idx += 256) {
-        const int kl = idx / (CT * 9), j = idx % (CT * 9);
-        const int k = k0 + kl, c = c0 + j / 9;
-        gs[kl * ROW + j] = (k < K && c < C) ? __half2float(G[((size_t)k * C + c0) * 9 + j]) : 0.0f;
-    }
-    __syncthreads();
-    const int kl = threadIdx.x % KT;
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int cl = threadIdx.x / KT + 4 * h;
-        float g[3][3], t[A][3], u[A][A];
-#pragma unroll
-        for (int i = 0; i < 3; ++i)
-#pragma unroll
-            for (int j = 0; j < 3; ++j) g[i][j] = gs[kl * ROW + cl * 9 + i * 3 + j];
-#pragma unroll
-        for (int j = 0; j < 3; ++j) {
-            float col[3] = {g[0][j], g[1][j], g[2][j]}, o[A];
-            g_mul<M>(col, o);
-#pragma unroll
-            for (int i = 0; i < A; ++i) t[i][j] = o[i];
-        }
-#pragma unroll
-        for (int i = 0; i < A; ++i) g_mul<M>(t[i], u[i]);
-#pragma unroll
-        for (int xi = 0; xi < A; ++xi)
-#pragma unroll
-            for (int nu = 0; nu < A; ++nu) us[((xi * A + nu) * KT + kl) * CT + cl] = __float2half_rn(u[xi][nu]);
-    }
-    __syncthreads();
-    const uint4 *in = reinterpret_cast<const uint4 *>(us);
-    uint4 *out = reinterpret_cast<uint4 *>(U);
-    for (int w = threadIdx.x; w < A2 * KT; w += 256) {
-        const int e = w / KT, k = k0 + w % KT;
-        if (k < Kp) out[((size_t)e * (Cp / 8) + blockIdx.y) * Kp + k] = in[w];
-    }
+    __shared__ __attribute__((aligned(16))) unsigned char smem[f16_stage_bytes(M)];
+    filter_transform_f16_block<M, 256>(G, U, K, C, Kp, Cp, blockIdx.x, blockIdx.y, smem);
 }
 
 // Filter transform for the gradient with respect to the input (Section 4.2 of the paper): that

@@ -1,4 +1,4 @@
-// Bodies of the filter transform (loop 1 of Algorithm 1) and of the fp32 input transform (loop 2)
+// Bodies of the filter transform (loop 1 of Algorithm 1) and of the input transform (loop 2)
 // as device functions of a block index, so that they can run as kernels of their own or side by
 // side in one launch (the two loops are independent of each other).
 #pragma once
@@ -207,6 +207,146 @@ __device__ __forceinline__ void input_transform_pair_block(const float *__restri
             *reinterpret_cast<floatx2_it *>(V + ((size_t)e * g.Cp + c) * g.Pp + b0) =
                 floatx2_it{v[0][xi][nu], v[1][xi][nu]};
         }
+}
+
+// ---- fp16 storage ------------------------------------------------------------------------------
+// Both bodies transform in fp32, round once to fp16, collect the results of a block in LDS and write 16-byte units
+// (one of them is the 8 channels a lane feeds to the fp16 MFMA); `smem` must hold f16_stage_bytes(M) bytes.
+constexpr int F16_KT = 64, F16_CT = 8, F16_ROW = F16_CT * 9 + 1, F16_TB = 64;
+constexpr int f16_stage_bytes(int M)
+{
+    const int collect = (M + 2) * (M + 2) * 64 * 8 * 2, taps = F16_KT * F16_ROW * 4;
+    return collect > taps ? collect : taps;
+}
+
+// Filter transform.  U is laid out [e][c/8][k][c%8], so a (k, c) thread owns isolated 2-byte elements of U.  A block
+// therefore takes 64 filters x 8 channels (their 72 source values per filter are contiguous in G) and writes U as
+// 1 KB contiguous per component and wavefront instead of 64 scattered 2-byte stores.  NT threads (256 or 512).
+template <int M, int NT>
+__device__ __forceinline__ void filter_transform_f16_block(const __half *__restrict__ G, __half *__restrict__ U, int K,
+                                                           int C, int Kp, int Cp, int bx, int by, void *smem)
+{
+    constexpr int A = M + 2, A2 = A * A, KT = F16_KT, CT = F16_CT, ROW = F16_ROW, PAIRS = KT * CT / NT;
+    float *gs = reinterpret_cast<float *>(smem);       // the taps of the block ...
+    __half *us = reinterpret_cast<__half *>(smem);     // ... and, once every thread holds its taps, the results
+    const int tid = threadIdx.x;
+    const int k0 = bx * KT, c0 = by * CT;
+    for (int idx = tid; idx < KT * CT * 9; idx += NT) {
+        const int kl = idx / (CT * 9), j = idx % (CT * 9);
+        const int k = k0 + kl, c = c0 + j / 9;
+        gs[kl * ROW + j] = (k < K && c < C) ? __half2float(G[((size_t)k * C + c0) * 9 + j]) : 0.0f;
+    }
+    __syncthreads();
+    const int kl = tid % KT;
+    float g[PAIRS][3][3];
+#pragma unroll
+    for (int h = 0; h < PAIRS; ++h) {
+        const int cl = tid / KT + (NT / KT) * h;
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+#pragma unroll
+            for (int j = 0; j < 3; ++j) g[h][i][j] = gs[kl * ROW + cl * 9 + i * 3 + j];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < PAIRS; ++h) {
+        const int cl = tid / KT + (NT / KT) * h;
+        float t[A][3], u[A][A];
+#pragma unroll
+        for (int j = 0; j < 3; ++j) {
+            float col[3] = {g[h][0][j], g[h][1][j], g[h][2][j]}, o[A];
+            g_mul<M>(col, o);
+#pragma unroll
+            for (int i = 0; i < A; ++i) t[i][j] = o[i];
+        }
+#pragma unroll
+        for (int i = 0; i < A; ++i) g_mul<M>(t[i], u[i]);
+#pragma unroll
+        for (int xi = 0; xi < A; ++xi)
+#pragma unroll
+            for (int nu = 0; nu < A; ++nu) us[((xi * A + nu) * KT + kl) * CT + cl] = __float2half_rn(u[xi][nu]);
+    }
+    __syncthreads();
+    const uint4 *in = reinterpret_cast<const uint4 *>(us);
+    uint4 *out = reinterpret_cast<uint4 *>(U);
+    for (int w = tid; w < A2 * KT; w += NT) {
+        const int e = w / KT, k = k0 + w % KT;
+        if (k < Kp) out[((size_t)e * (Cp / 8) + by) * Kp + k] = in[w];
+    }
+}
+
+// Input transform.  V is laid out [e][c/8][b][c%8]; a block takes 8 channels x 64 tiles (512 threads) and writes V as
+// 1 KB contiguous per component and wavefront.  VEC: pad 1, W a multiple of 4, M = 4 (columns 1..4 of a tile row are
+// one aligned 8-byte load).
+template <int M, bool VEC>
+__device__ __forceinline__ void input_transform_f16_block(const __half *__restrict__ D, __half *__restrict__ V,
+                                                          const Geo &g, int bx, int by, void *smem)
+{
+    constexpr int A = M + 2, A2 = A * A, TB = F16_TB;
+    __half *stage = reinterpret_cast<__half *>(smem);
+    const int bl = threadIdx.x % TB, cl = threadIdx.x / TB;
+    const int b = bx * TB + bl;
+    const int c = by * 8 + cl;
+    float d[A][A];
+#pragma unroll
+    for (int p = 0; p < A; ++p)
+#pragma unroll
+        for (int q = 0; q < A; ++q) d[p][q] = 0.0f;
+    if (c < g.C && b < g.P) {
+        const int ty = b % g.Tw;
+        const int t2 = b / g.Tw;
+        const int tx = t2 % g.Th;
+        const int i = t2 / g.Th;
+        const int x0 = M * tx - g.pad, y0 = M * ty - g.pad;
+        const __half *src = D + ((size_t)i * g.C + c) * g.H * g.W;
+#pragma unroll
+        for (int p = 0; p < A; ++p) {
+            const int x = x0 + p;
+            if (x >= 0 && x < g.H) {
+                const __half *row = src + (size_t)x * g.W + y0;
+                if constexpr (VEC) {
+                    const uint2 mid = *reinterpret_cast<const uint2 *>(row + 1);
+                    const __half2 h01 = *reinterpret_cast<const __half2 *>(&mid.x);
+                    const __half2 h23 = *reinterpret_cast<const __half2 *>(&mid.y);
+                    d[p][1] = __low2float(h01);
+                    d[p][2] = __high2float(h01);
+                    d[p][3] = __low2float(h23);
+                    d[p][4] = __high2float(h23);
+                    if (y0 >= 0) d[p][0] = __half2float(row[0]);
+                    if (y0 + 5 < g.W) d[p][5] = __half2float(row[5]);
+                } else {
+#pragma unroll
+                    for (int q = 0; q < A; ++q) {
+                        const int y = y0 + q;
+                        if (y >= 0 && y < g.W) d[p][q] = __half2float(row[q]);
+                    }
+                }
+            }
+        }
+    }
+    float t[A][A], v[A][A];
+#pragma unroll
+    for (int q = 0; q < A; ++q) {
+        float col[A], o[A];
+#pragma unroll
+        for (int p = 0; p < A; ++p) col[p] = d[p][q];
+        bt_mul<M>(col, o);
+#pragma unroll
+        for (int p = 0; p < A; ++p) t[p][q] = o[p];
+    }
+#pragma unroll
+    for (int p = 0; p < A; ++p) bt_mul<M>(t[p], v[p]);
+#pragma unroll
+    for (int xi = 0; xi < A; ++xi)
+#pragma unroll
+        for (int nu = 0; nu < A; ++nu) stage[((xi * A + nu) * TB + bl) * 8 + cl] = __float2half_rn(v[xi][nu]);
+    __syncthreads();
+    uint4 *out = reinterpret_cast<uint4 *>(V);
+    const uint4 *in = reinterpret_cast<const uint4 *>(stage);
+    for (int u = threadIdx.x; u < A2 * TB; u += 512) {
+        const int e = u / TB, ub = bx * TB + u % TB;
+        if (ub < g.Pp) out[((size_t)e * (g.Cp / 8) + by) * g.Pp + ub] = in[u];
+    }
 }
 
 }  // namespace wino

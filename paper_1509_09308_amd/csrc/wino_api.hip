@@ -301,7 +301,7 @@ static int run_layer(const Geo &g, int y_dt, const void *D, const void *G, const
     if (U == nullptr) {
         if (!bwd && flags != WINO_FLAG_FUSED && prep_eligible(g)) {
             // filters and input tiles are transformed by one launch
-            e = launch_prep(g, (const float *)G, (float *)Uw, (const float *)D, (float *)Vw, s);
+            e = launch_prep(g, G, Uw, D, Vw, s);
             v_done = true;
         } else {
             e = bwd ? launch_filter_transform_bwd(g, G, Uw, s) : launch_filter_transform(g, G, Uw, s);

@@ -47,7 +47,7 @@ bool fused_f2_eligible(const Geo &g);
 hipError_t launch_fused_f2(const Geo &g, const float *D, const float *G, float *Y, void *workspace,
                            size_t workspace_bytes, bool bwd, hipStream_t s);
 bool prep_eligible(const Geo &g);
-hipError_t launch_prep(const Geo &g, const float *G, float *U, const float *D, float *V, hipStream_t s);
+hipError_t launch_prep(const Geo &g, const void *G, void *U, const void *D, void *V, hipStream_t s);
 bool wgrad_supported(long long N, long long C, long long H, long long W, long long K);
 size_t wgrad_workspace_bytes(int N, int C, int H, int W, int K);
 hipError_t launch_wgrad(int N, int C, int H, int W, int K, const float *D, const float *E, float *dG, void *workspace,
