@@ -180,7 +180,13 @@ int wino_conv2d_bwd_filter(int N, int C, int H, int W, int K, int pad, int dt, c
  * wino_status_t (e.g. -WINO_EUNSUPPORTED) if the call would be rejected. */
 int wino_conv2d_variant(int N, int C, int H, int W, int K, int pad, int m, int dt, int y_dt, unsigned flags);
 /* Eq. (1) evaluated directly on the GPU: any R x S filter, stride and padding; for layers the
- * fast algorithm does not cover (e.g. the 3-channel first layer of Table 3). */
+ * fast algorithm does not cover (e.g. the 3-channel first layer of Table 3).
+ * D[N][C][H][W], G[K][C][R][S] -> Y[N][K][Ho][Wo] with Ho = (H + 2 pad - R) / stride + 1 (Wo alike); D, G and Y
+ * are device pointers of element type `dt` (fp32, or fp16 with fp32 accumulation), caller-owned; Y is
+ * overwritten.  Asynchronous on `stream`, never allocates.  3 x 3, stride 1 layers with at most 4 channels and
+ * W % 4 == 0 run on the matrix units, everything else on the vector ALUs.
+ * WINO_EINVAL for null pointers or non-positive extents, WINO_EUNSUPPORTED for an empty output or extents
+ * beyond the launch limits (N or K / 16 above 65535, R S above 512). */
 int direct_conv2d_fwd(int N, int C, int H, int W, int K, int R, int S, int pad, int stride, int dt,
                       const void *D, const void *G, void *Y, void *stream);
 
