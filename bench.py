@@ -605,6 +605,16 @@ def stack_leg(torch, w, args, N, dtype, policy, cfg_idx, steps, warmup, cold=Tru
     out["fx"] = {"ms_per_step": fsec * 1e3, "eff_tflops": total_flops / fsec / 1e12, "images_per_sec": N / fsec,
                  "note": "filters pre-transformed by wino_filter_transform outside the timed region"}
 
+    if dtype == "f16":
+        # the same step with fp16 outputs (the workload's definition keeps Y in fp32; this is the other reading)
+        keep = [L.Y for L in layers]
+        for L in layers:
+            L.Y = torch.empty_like(L.Y, dtype=torch.float16)
+        ysec = time_steps(torch, w, layers, ws, steps, warmup)
+        out["fp16_outputs"] = {"ms_per_step": ysec * 1e3, "eff_tflops": total_flops / ysec / 1e12,
+                               "note": "Y stored in fp16 instead of fp32 (one rounding more; not the headline of this leg)"}
+        for L, y in zip(layers, keep):
+            L.Y = y
     if not args.no_stages:
         stages = time_stages(torch, w, layers, ws, max(5, steps), cold=cold)
         out.update(summarize_stages(w, layers, stages, dtype, workload))

@@ -58,8 +58,8 @@ typedef enum { WINO_F32 = 0, WINO_F16 = 1 } wino_dtype_t;
 #define WINO_FLAG_AUTO 0u
 #define WINO_FLAG_UNFUSED 1u      /* four separate stages exactly as in Algorithm 1 */
 #define WINO_FLAG_FUSED 2u        /* loops 2-4 of Algorithm 1 in one kernel: V and M never reach memory
-                                   * (F(4x4,3x3) with fp32 Y; fp16 storage needs pad 1 and W % 4 == 0 as well;
-                                   * WINO_EUNSUPPORTED otherwise) */
+                                   * (F(4x4,3x3); fp32 storage writes fp32 Y; fp16 storage needs pad 1 and
+                                   * W % 4 == 0 and writes fp32 or fp16 Y; WINO_EUNSUPPORTED otherwise) */
 #define WINO_FLAG_ONE_LAUNCH 3u   /* all four loops of Algorithm 1 in ONE kernel launch, the filter transform
                                    * computed inside the kernel (the variant of Section 6 without separately
                                    * transformed filters): F(2x2,3x3), fp32 D, G and Y, untransformed filters G

@@ -414,9 +414,11 @@ bool fused_preferred(const Geo &g)
     return (long long)g.K * g.C <= 32LL * (g.K + g.C) && items >= 128;
 }
 
-hipError_t launch_fused(const Geo &g, const void *Dv, const void *Uv, float *Y, hipStream_t s)
+hipError_t launch_fused(const Geo &g, const void *Dv, const void *Uv, void *Yv, int y_dt, hipStream_t s)
 {
-    if (g.dt == WINO_F16) return launch_fused_f16(g, Dv, Uv, Y, s);
+    if (g.dt == WINO_F16) return launch_fused_f16(g, Dv, Uv, Yv, y_dt, s);
+    if (y_dt != WINO_F32) return hipErrorNotSupported;
+    float *Y = (float *)Yv;
     const float *D = (const float *)Dv, *U = (const float *)Uv;
     const int n_pt = (g.P + FP - 1) / FP, n_kb = (g.K + FK - 1) / FK;
     const long long blocks = (long long)n_pt * n_kb;

@@ -20,7 +20,7 @@
 // After the last step the accumulators go through LDS in four pieces of 8 KH filters, every thread
 // gathers the 36 components of one (filter, tile) pair, applies Y = A^T m A and writes the 4 x 4
 // outputs that are inside the image as 16-byte rows.
-// Needs m = 4, pad = 1, W % 4 == 0 (aligned 8-byte loads and 16-byte stores), fp32 Y.
+// Needs m = 4, pad = 1, W % 4 == 0 (aligned 8-byte loads, 16- or 8-byte stores); Y in fp32 or fp16.
 #include "wino_internal.h"
 #include "transforms.h"
 #include <mutex>
@@ -61,9 +61,22 @@ constexpr unsigned HF_MAX_BYTES = 0x40000000u;                     // longest st
 constexpr unsigned HF_ROW_OOB = 0x80000000u, HF_COL_OOB = 0x40000000u;   // offset markers of taps outside the image
 
 // CPAD: the channel loop (over the padded count Cp) holds channel slots past the last channel.
-template <bool CPAD, int KH>
+// four neighbouring outputs of a row, not kept in the caches; fp32 or rounded once to fp16
+__device__ __forceinline__ void hf_store4(float *p, floatx4_h v)
+{
+    __builtin_nontemporal_store(v, reinterpret_cast<floatx4_h *>(p));
+}
+__device__ __forceinline__ void hf_store4(__half *p, floatx4_h v)
+{
+    typedef unsigned uintx2_s __attribute__((ext_vector_type(2)));
+    const __half2 a = __floats2half2_rn(v[0], v[1]), b = __floats2half2_rn(v[2], v[3]);
+    __builtin_nontemporal_store(uintx2_s{__builtin_bit_cast(unsigned, a), __builtin_bit_cast(unsigned, b)},
+                                reinterpret_cast<uintx2_s *>(p));
+}
+
+template <bool CPAD, int KH, typename YT>
 __global__ __launch_bounds__(256 * KH, 3 - KH) void fused_f16_kernel(const __half *__restrict__ D, const uint4 *__restrict__ U,
-                                                                     float *__restrict__ Y, Geo g, int n_kb, int n_items)
+                                                                     YT *__restrict__ Y, Geo g, int n_kb, int n_items)
 {
     constexpr int HF_K = 32 * KH, HF_U_WORDS = hf_u_words(KH), WAVES = 4 * KH;
     extern __shared__ uint4 smem[];                                 // hf_lds_words(KH) words
@@ -218,7 +231,7 @@ __global__ __launch_bounds__(256 * KH, 3 - KH) void fused_f16_kernel(const __hal
     float *Ms = reinterpret_cast<float *>(smem);
     const int frow = tid >> 5;                 // 0 .. 8 KH - 1: filter row of the piece handled in the gather
     const int ot = tid & 31;                   // tile of the gather (same tile as in the transform phase)
-    float *ybase = Y;
+    YT *ybase = Y;
     int orow = 0;
     {
         const int bb = tile_ok ? b : 0;
@@ -252,12 +265,10 @@ __global__ __launch_bounds__(256 * KH, 3 - KH) void fused_f16_kernel(const __hal
             }
 #pragma unroll
             for (int p = 0; p < 4; ++p) at_mul<4>(tt[p], y[p]);
-            float *dst = ybase + (size_t)k * g.Ho * g.Wo;
+            YT *dst = ybase + (size_t)k * g.Ho * g.Wo;
 #pragma unroll
             for (int p = 0; p < 4; ++p)
-                if (orow + p < g.Ho)
-                    __builtin_nontemporal_store(floatx4_h{y[p][0], y[p][1], y[p][2], y[p][3]},
-                                                reinterpret_cast<floatx4_h *>(dst + (size_t)p * g.Wo));
+                if (orow + p < g.Ho) hf_store4(dst + (size_t)p * g.Wo, floatx4_h{y[p][0], y[p][1], y[p][2], y[p][3]});
         }
         __syncthreads();
     }
@@ -273,8 +284,8 @@ bool fused_f16_eligible(const Geo &g)
     return g.dt == WINO_F16 && g.m == 4 && g.pad == 1 && g.W % 4 == 0 && span * image_bytes + 65536 < HF_MAX_BYTES;
 }
 
-template <bool CPAD, int KH>
-static hipError_t launch_one(const Geo &g, const void *D, const void *U, float *Y, hipStream_t s)
+template <bool CPAD, int KH, typename YT>
+static hipError_t launch_one(const Geo &g, const void *D, const void *U, YT *Y, hipStream_t s)
 {
     constexpr int HF_K = 32 * KH;
     constexpr size_t lds = (size_t)hf_lds_words(KH) * 16;
@@ -290,7 +301,7 @@ static hipError_t launch_one(const Geo &g, const void *D, const void *U, float *
         if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
         std::lock_guard<std::mutex> lock(mu);
         if (!done[dev]) {
-            e = hipFuncSetAttribute((const void *)fused_f16_kernel<CPAD, KH>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            e = hipFuncSetAttribute((const void *)fused_f16_kernel<CPAD, KH, YT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
             done[dev] = true;
         }
@@ -298,15 +309,22 @@ static hipError_t launch_one(const Geo &g, const void *D, const void *U, float *
     // as many workgroups as stay resident on 256 CUs (registers and LDS allow 3 - KH per CU), in multiples of the 8 XCDs
     const long long resident = 256 * (3 - KH);
     const unsigned grid = (unsigned)(items >= resident ? resident : (items + 7) / 8 * 8);
-    fused_f16_kernel<CPAD, KH><<<dim3(grid), dim3(256 * KH), lds, s>>>((const __half *)D, (const uint4 *)U, Y, g, n_kb, (int)items);
+    fused_f16_kernel<CPAD, KH, YT><<<dim3(grid), dim3(256 * KH), lds, s>>>((const __half *)D, (const uint4 *)U, Y, g, n_kb, (int)items);
     return hipGetLastError();
 }
 
-hipError_t launch_fused_f16(const Geo &g, const void *D, const void *U, float *Y, hipStream_t s)
+template <typename YT>
+static hipError_t launch_typed(const Geo &g, const void *D, const void *U, YT *Y, hipStream_t s)
 {
     const bool cpad = g.Cp != g.C;   // the channel loop runs over Cp: slots past C must be fetched as zeros
     if (g.Kp > 32) return cpad ? launch_one<true, 2>(g, D, U, Y, s) : launch_one<false, 2>(g, D, U, Y, s);
     return cpad ? launch_one<true, 1>(g, D, U, Y, s) : launch_one<false, 1>(g, D, U, Y, s);
+}
+
+// Y is fp32 or fp16 (y_dt)
+hipError_t launch_fused_f16(const Geo &g, const void *D, const void *U, void *Y, int y_dt, hipStream_t s)
+{
+    return y_dt == WINO_F16 ? launch_typed(g, D, U, (__half *)Y, s) : launch_typed(g, D, U, (float *)Y, s);
 }
 
 }  // namespace wino

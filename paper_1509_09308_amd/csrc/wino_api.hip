@@ -260,6 +260,9 @@ int wino_output_transform(int N, int K, int H, int W, int pad, int m, int y_dt, 
     return e == hipSuccess ? WINO_OK : hip_fail(e);
 }
 
+// The one-kernel paths write fp32 outputs; the fp16-storage one also writes fp16.
+static bool fused_y_ok(const Geo &g, int y_dt) { return y_dt == WINO_F32 || g.dt == WINO_F16; }
+
 int wino_conv2d_variant(int N, int C, int H, int W, int K, int pad, int m, int dt, int y_dt, unsigned flags)
 {
     Geo g;
@@ -268,8 +271,8 @@ int wino_conv2d_variant(int N, int C, int H, int W, int K, int pad, int m, int d
     if (bad_dtype(y_dt) || flags > WINO_FLAG_ONE_LAUNCH) return -WINO_EINVAL;
     if (flags == WINO_FLAG_ONE_LAUNCH)
         return (fused_f2_eligible(g) && y_dt == WINO_F32) ? (int)WINO_FLAG_ONE_LAUNCH : -WINO_EUNSUPPORTED;
-    if (flags == WINO_FLAG_FUSED) return (fused_eligible(g) && y_dt == WINO_F32) ? (int)WINO_FLAG_FUSED : -WINO_EUNSUPPORTED;
-    if (flags == WINO_FLAG_AUTO && y_dt == WINO_F32 && fused_preferred(g)) return WINO_FLAG_FUSED;
+    if (flags == WINO_FLAG_FUSED) return (fused_eligible(g) && fused_y_ok(g, y_dt)) ? (int)WINO_FLAG_FUSED : -WINO_EUNSUPPORTED;
+    if (flags == WINO_FLAG_AUTO && fused_y_ok(g, y_dt) && fused_preferred(g)) return WINO_FLAG_FUSED;
     return WINO_FLAG_UNFUSED;
 }
 
@@ -280,7 +283,7 @@ static int run_layer(const Geo &g, int y_dt, const void *D, const void *G, const
 {
     if (bad_dtype(y_dt)) return WINO_EINVAL;
     if (flags > WINO_FLAG_ONE_LAUNCH) return WINO_EINVAL;
-    if (flags == WINO_FLAG_FUSED && (!fused_eligible(g) || y_dt != WINO_F32)) return WINO_EUNSUPPORTED;
+    if (flags == WINO_FLAG_FUSED && (!fused_eligible(g) || !fused_y_ok(g, y_dt))) return WINO_EUNSUPPORTED;
     if (flags == WINO_FLAG_ONE_LAUNCH && (!fused_f2_eligible(g) || y_dt != WINO_F32 || U != nullptr))
         return WINO_EUNSUPPORTED;
     if (bad_ptr(D) || bad_ptr(Y) || bad_ptr(workspace)) return WINO_EINVAL;
@@ -296,7 +299,7 @@ static int run_layer(const Geo &g, int y_dt, const void *D, const void *G, const
         e = launch_fused_f2(g, (const float *)D, (const float *)G, (float *)Y, workspace, workspace_bytes, bwd, s);
         return e == hipSuccess ? WINO_OK : hip_fail(e);
     }
-    if (flags == WINO_FLAG_AUTO && y_dt == WINO_F32 && fused_preferred(g)) flags = WINO_FLAG_FUSED;
+    if (flags == WINO_FLAG_AUTO && fused_y_ok(g, y_dt) && fused_preferred(g)) flags = WINO_FLAG_FUSED;
     bool v_done = false;
     if (U == nullptr) {
         if (!bwd && flags != WINO_FLAG_FUSED && prep_eligible(g)) {
@@ -312,7 +315,7 @@ static int run_layer(const Geo &g, int y_dt, const void *D, const void *G, const
     if (flags == WINO_FLAG_FUSED) {
         // fp32 with pad 1 and W % 4 == 0: the design with two workgroups per CU; otherwise the general one
         e = fused_lds_eligible(g) ? launch_fused_lds(g, (const float *)D, (const float *)U, (float *)Y, s)
-                                  : launch_fused(g, D, U, (float *)Y, s);
+                                  : launch_fused(g, D, U, Y, y_dt, s);
         if (e != hipSuccess) return hip_fail(e);
         return WINO_OK;
     }

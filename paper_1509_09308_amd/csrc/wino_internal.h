@@ -38,11 +38,11 @@ hipError_t launch_batched_gemm(const Geo &g, const void *U, const void *V, float
 hipError_t launch_output_transform(const Geo &g, int y_dt, const float *M, void *Y, int splits, hipStream_t s);
 bool fused_eligible(const Geo &g);
 bool fused_preferred(const Geo &g);
-hipError_t launch_fused(const Geo &g, const void *D, const void *U, float *Y, hipStream_t s);
+hipError_t launch_fused(const Geo &g, const void *D, const void *U, void *Y, int y_dt, hipStream_t s);
 bool fused_f16_eligible(const Geo &g);
 bool fused_lds_eligible(const Geo &g);
 hipError_t launch_fused_lds(const Geo &g, const float *D, const float *U, float *Y, hipStream_t s);
-hipError_t launch_fused_f16(const Geo &g, const void *D, const void *U, float *Y, hipStream_t s);
+hipError_t launch_fused_f16(const Geo &g, const void *D, const void *U, void *Y, int y_dt, hipStream_t s);
 bool fused_f2_eligible(const Geo &g);
 hipError_t launch_fused_f2(const Geo &g, const float *D, const float *G, float *Y, void *workspace,
                            size_t workspace_bytes, bool bwd, hipStream_t s);

@@ -223,6 +223,23 @@ def test_f16_fused_path_matches_oracle(shape):
     assert rel_err(Yf, Yu) <= 5e-4   # v = B^T (d B) here, (B^T d) B there: an fp16 rounding of V can flip
 
 
+@pytest.mark.parametrize("shape", [(2, 32, 28, 28, 48), (1, 19, 13, 28, 70), (2, 64, 56, 56, 64), (1, 8, 6, 8, 16)])
+def test_f16_fused_path_writes_fp16_outputs(shape):
+    """fp16 Y from the one-kernel path: the fp32 result of the same path, rounded once."""
+    torch, w = require_gpu()
+    N, C, H, W, K = shape
+    D, G = synth.make_layer(N, C, H, W, K, seed=sum(shape) + 5, dtype=np.float16)
+    d, g = to_gpu(D), to_gpu(G)
+    assert w.wino_conv2d_variant(N, C, H, W, K, 1, 4, w.WINO_F16, y_dt=w.WINO_F16, flags=w.FLAG_FUSED) == w.FLAG_FUSED
+    Y32 = w.wino_conv2d_fwd_ex(d, G=g, pad=1, m=4, flags=w.FLAG_FUSED)
+    Y16 = w.wino_conv2d_fwd_ex(d, G=g, pad=1, m=4, flags=w.FLAG_FUSED, y_dtype=torch.float16)
+    assert Y16.dtype == torch.float16
+    # (the two instantiations may contract the inverse transform's multiply-adds differently: within half an
+    # fp16 unit of the fp32 result, not necessarily the identical rounding)
+    assert torch.allclose(Y16.float(), Y32, rtol=6e-4, atol=1e-4)
+    check_close(Y16.float().cpu().numpy(), direct.conv2d_fwd(D, G, pad=1), TOL[("f16", 4)], "fp16 fused, fp16 Y %s" % (shape,), 4)
+
+
 def test_f16_fused_exact_on_integers():
     """Small integers and filters scaled by 576 / 4: every fp16 rounding is exact except those of the
     1/6-type constants; every output position must be the right one."""

@@ -193,7 +193,8 @@ def test_variant_query_host_only(L):
     assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 4, 1, 0, w.FLAG_FUSED) == w.FLAG_FUSED
     assert L.wino_conv2d_variant(2, 8, 8, 10, 8, 1, 4, 1, 0, w.FLAG_FUSED) == -w.WINO_EUNSUPPORTED
     assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 0, 4, 1, 0, w.FLAG_FUSED) == -w.WINO_EUNSUPPORTED
-    assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 4, 1, 1, w.FLAG_FUSED) == -w.WINO_EUNSUPPORTED   # fp16 Y
+    assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 4, 1, 1, w.FLAG_FUSED) == w.FLAG_FUSED           # fp16 storage, fp16 Y
+    assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 4, 0, 1, w.FLAG_FUSED) == -w.WINO_EUNSUPPORTED   # fp32 storage, fp16 Y
     assert L.wino_conv2d_variant(32, 64, 224, 224, 64, 1, 4, 1, 0, 0) == w.FLAG_FUSED
     assert L.wino_conv2d_variant(32, 512, 28, 28, 512, 1, 4, 1, 0, 0) == w.FLAG_UNFUSED
     assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 3, 0, 0, 0) == -w.WINO_EUNSUPPORTED
