@@ -41,10 +41,10 @@ PEAK = {"hbm_GBs": 8000.0, "mfma_f32_TFs": 157.3, "mfma_f16_TFs": 2500.0}
 # `bench.py --probe` (summaries under profiles/); keyed by (workload, kernel).  None until measured.
 MEASURED_TRAFFIC = {
     # profiles/vgg16_n64_fp32_hbm_traffic.md (algorithmic: 487.7 MB resp. 850.0 MB per launch)
-    ("vgg16_3x3_conv_stack_N64_f32", "gemm_f32_kernel<128, 128, 2, 2, 16>"): 513.6e6,
-    ("vgg16_3x3_conv_stack_N64_f32", "fused_lds_kernel<false>"): 1053.0e6,
+    ("vgg16_3x3_conv_stack_N64_f32", "gemm_f32_kernel<128, 128, 2, 2, 16>"): 514.1e6,
+    ("vgg16_3x3_conv_stack_N64_f32", "fused_lds_kernel<false>"): 1051.7e6,
     # profiles/vgg16_n32_fp16_hbm_traffic.md (algorithmic: 328.7 MB resp. 183.5 MB per launch)
-    ("vgg16_3x3_conv_stack_N32_f16", "fused_f16_kernel<false, 2>"): 354.6e6,
+    ("vgg16_3x3_conv_stack_N32_f16", "fused_f16_kernel<false, 2, float>"): 354.4e6,
     ("vgg16_3x3_conv_stack_N32_f16", "gemm_f16_kernel<128, 128>"): 187.3e6,
 }
 # Titan X (Maxwell) numbers of the paper, F(2x2,3x3), VGG network E (Tables 5 and 6): context only.
@@ -196,7 +196,7 @@ def stage_plan(torch, w, L, ws, sets):
         nbytes = {"filter": 9 * L.K * L.C * s + nU, "fused": nD + nU + nY}
         cpad = "false" if L.C % 8 == 0 else "true"
         kernel = ("fused_lds_kernel<%s>" % cpad if L.dt == w.WINO_F32 else
-                  "fused_f16_kernel<%s, %d>" % (cpad, 2 if L.K > 32 else 1))
+                  "fused_f16_kernel<%s, %d, float>" % (cpad, 2 if L.K > 32 else 1))
     else:
         Vs = [w.alloc_v(L.C, L.P, L.m, L.dt) for _ in range(sets)]
         Ms = [w.alloc_m(L.K, L.P, L.m) for _ in range(sets)]
