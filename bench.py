@@ -700,6 +700,8 @@ def main():
     ap.add_argument("--no-f6", action="store_true", help="skip the F(6x6,3x3) and all-F(4x4,3x3) lines")
     ap.add_argument("--steps-only", action="store_true",
                     help="for rocprofv3 --kernel-trace --stats: warm-up and timed steps of the chosen leg, nothing else")
+    ap.add_argument("--grads", action="store_true",
+                    help="with --steps-only: the input- and filter-gradient steps of the leg instead of forward steps")
     ap.add_argument("--probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 1 GiB device copy (counter calibration), then every "
                          "kernel of one step of the chosen leg twice; prints the algorithmic bytes per kernel and exits")
@@ -737,6 +739,11 @@ def main():
         ws = torch.empty(max(L.ws_bytes for L in layers if not L.direct), dtype=torch.uint8, device="cuda")
         if args.probe:
             probe(torch, w, layers, ws)
+        elif args.grads:
+            run_step(w, layers, ws)   # the error tensors of the gradient steps are the forward outputs
+            bd = time_bwd_data(torch, w, layers, ws.numel(), args.steps)
+            bf = time_bwd_filter(torch, w, layers, args.steps)
+            print(json.dumps({"steps_only": True, "grads": True, "bwd_data": bd, "bwd_filter": bf}))
         else:
             sec = time_steps(torch, w, layers, ws, args.steps, args.warmup)
             print(json.dumps({"steps_only": True, "ms_per_step": sec * 1e3, "steps": args.steps, "warmup": args.warmup,
