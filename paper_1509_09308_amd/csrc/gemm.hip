@@ -67,31 +67,39 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_f32_kernel(const float *__r
     const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, lg = lane >> 5;
 
-    const float *pa[AL], *pb[BL];
+    // Operands are fetched through buffers that start at this block's first channel row of U^(e) and V^(e): the
+    // per-thread byte offsets are fixed for the kernel and the slab advances in a scalar register, so the loop holds
+    // no 64-bit address arithmetic (one component's Cp x Kp or Cp x Pp floats stay below 4 GB: see the launcher).
+    unsigned oa[AL], ob[BL];
 #pragma unroll
     for (int j = 0; j < AL; ++j) {
         const int idx = tid + j * NT;
         const int row = idx / (BM / 4), col = min(k0 + (idx % (BM / 4)) * 4, Kp - 4);
-        pa[j] = Ue + (size_t)row * Kp + col;
+        oa[j] = (unsigned)(row * Kp + col) * 4u;
     }
 #pragma unroll
     for (int j = 0; j < BL; ++j) {
         const int idx = tid + j * NT;
         const int row = idx / (BN / 4), col = min(p0 + (idx % (BN / 4)) * 4, Pp - 4);
-        pb[j] = Ve + (size_t)row * Pp + col;
+        ob[j] = (unsigned)(row * Pp + col) * 4u;
     }
+    const int c_rows = Cp - c_first;
+    const __amdgpu_buffer_rsrc_t rsrc_a =
+        __builtin_amdgcn_make_buffer_rsrc((void *)Ue, 0, (unsigned)((size_t)c_rows * Kp * 4), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_b =
+        __builtin_amdgcn_make_buffer_rsrc((void *)Ve, 0, (unsigned)((size_t)c_rows * Pp * 4), 0x00020000);
+    unsigned sa = 0, sb = 0;                            // byte offset of the next slab
     floatx4 ra[AL], rb[BL];
+    typedef unsigned uintx4_g __attribute__((ext_vector_type(4)));
     auto load_global = [&]() {
 #pragma unroll
-        for (int j = 0; j < AL; ++j) {
-            ra[j] = *reinterpret_cast<const floatx4 *>(pa[j]);
-            pa[j] += (size_t)BK * Kp;
-        }
+        for (int j = 0; j < AL; ++j)
+            ra[j] = __builtin_bit_cast(floatx4, (uintx4_g)__builtin_amdgcn_raw_buffer_load_b128(rsrc_a, oa[j], sa, 0));
 #pragma unroll
-        for (int j = 0; j < BL; ++j) {
-            rb[j] = *reinterpret_cast<const floatx4 *>(pb[j]);
-            pb[j] += (size_t)BK * Pp;
-        }
+        for (int j = 0; j < BL; ++j)
+            rb[j] = __builtin_bit_cast(floatx4, (uintx4_g)__builtin_amdgcn_raw_buffer_load_b128(rsrc_b, ob[j], sb, 0));
+        sa += (unsigned)(BK * Kp) * 4u;
+        sb += (unsigned)(BK * Pp) * 4u;
     };
     auto store_lds = [&](int buf) {
 #pragma unroll
@@ -174,6 +182,9 @@ static hipError_t launch_f32(const Geo &g, const float *U, const float *V, float
     if (used != splits) return hipErrorInvalidValue;
     const long long blocks = (long long)tiles_m * tiles_n * g.a2 * splits;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    // 32-bit byte offsets inside one component of U and of V
+    if ((unsigned long long)g.Cp * g.Pp * 4ull >= (1ull << 32) || (unsigned long long)g.Cp * g.Kp * 4ull >= (1ull << 32))
+        return hipErrorNotSupported;
     gemm_f32_kernel<BM, BN, WM, WN, BK><<<dim3((unsigned)blocks), dim3(64 * WM * WN), 0, s>>>(
         U, V, M, g.Kp, g.Cp, g.Pp, tiles_m, tiles_n, g.a2, nk_split);
     return hipGetLastError();
