@@ -142,9 +142,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_f32_kernel(const float *__r
     store_lds(0);
     __syncthreads();
     lds_load(0, 0, a0, b0);
-    // all slabs but the last: fetch the next slab while multiplying the current one
-    for (int kt = 0; kt + 1 < nk; ++kt) {
-        const int cur = kt & 1;
+    // all slabs but the last: fetch the next slab while multiplying the current one.  Two slabs per trip, so that
+    // the LDS buffer of every access is known at compile time and its address is a per-lane base plus a constant
+    // (with a buffer index computed in the loop, every LDS read cost a vector add in the MFMA issue slot).
+    auto slab = [&](int cur) {
         load_global();
         lds_load(cur, 1, a1, b1);
         mma(a0, b0);
@@ -152,8 +153,18 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_f32_kernel(const float *__r
         __syncthreads();
         lds_load(cur ^ 1, 0, a0, b0);
         mma(a1, b1);
+    };
+    int kt = 0;
+    for (; kt + 2 < nk; kt += 2) {
+        slab(0);
+        slab(1);
     }
-    lds_load((nk - 1) & 1, 1, a1, b1);
+    if (kt + 1 < nk) {   // one more full iteration: the last slab then sits in buffer 1
+        slab(0);
+        lds_load(1, 1, a1, b1);
+    } else {
+        lds_load(0, 1, a1, b1);
+    }
     mma(a0, b0);
     mma(a1, b1);
 
