@@ -20,13 +20,34 @@ __device__ __forceinline__ int xcd_remap(int bid, int nblocks)
     return (bid % XCDS) * per + bid / XCDS;
 }
 
+// 16 bytes per lane from a buffer straight into LDS: lane l of the wavefront fills LDS bytes lds + 16 l ..
+// (lds the same in all lanes).  Written as assembly on purpose: while a copy into LDS that the compiler knows of
+// may be in flight, it puts a wait for ALL outstanding memory requests in front of every LDS read, which would
+// serialise the copy of the next slab with the multiply of the current one.  The kernel waits for its copies itself.
+typedef int intx4_g __attribute__((ext_vector_type(4)));
+#define WINO_G_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+__device__ __forceinline__ intx4_g gemm_buffer(const void *base, unsigned bytes)
+{
+    const unsigned long long a = (unsigned long long)base;
+    return intx4_g{__builtin_amdgcn_readfirstlane((int)(unsigned)a),
+                   __builtin_amdgcn_readfirstlane((int)((unsigned)(a >> 32) & 0xffffu)),
+                   __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000};
+}
+__device__ __forceinline__ void gemm_copy16_to_lds(intx4_g rsrc, unsigned lds, unsigned voffset, unsigned soffset)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds), "v"(voffset), "s"(rsrc), "s"(soffset)
+                 : "memory");   // (m0 is not a register the compiler keeps values in)
+}
+
 // fp32 operands, v_mfma_f32_32x32x2_f32.  A workgroup of WM x WN wavefronts owns a BM x BN
 // block of one M^(e); every wavefront owns TM x TN MFMA tiles of 32 x 32.  Both operands are
 // stored reduction-index-major (U[e][c][k], V[e][c][b]), so a BK-deep slab is BK contiguous row
 // segments: loaded with 16-byte accesses, kept in LDS as [c][k] / [c][b], and read by the MFMA
 // lanes (lane = column + 32 * (c & 1)) without bank conflicts.
 //
-// Pipeline: two LDS slabs (the global loads of slab t+1 are in flight while slab t is
+// Pipeline: two LDS slabs (slab t+1 is copied from memory straight into LDS while slab t is
 // multiplied) and two register sets per wavefront holding half a slab of MFMA operands each,
 // so LDS reads for the next half overlap the MFMAs of the current one; one barrier per slab.
 //
@@ -84,29 +105,25 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_f32_kernel(const float *__r
         ob[j] = (unsigned)(row * Pp + col) * 4u;
     }
     const int c_rows = Cp - c_first;
-    const __amdgpu_buffer_rsrc_t rsrc_a =
-        __builtin_amdgcn_make_buffer_rsrc((void *)Ue, 0, (unsigned)((size_t)c_rows * Kp * 4), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrc_b =
-        __builtin_amdgcn_make_buffer_rsrc((void *)Ve, 0, (unsigned)((size_t)c_rows * Pp * 4), 0x00020000);
+    const intx4_g rsrc_a = gemm_buffer(Ue, (unsigned)((size_t)c_rows * Kp * 4));
+    const intx4_g rsrc_b = gemm_buffer(Ve, (unsigned)((size_t)c_rows * Pp * 4));
     unsigned sa = 0, sb = 0;                            // byte offset of the next slab
-    floatx4 ra[AL], rb[BL];
-    typedef unsigned uintx4_g __attribute__((ext_vector_type(4)));
-    auto load_global = [&]() {
+    // A slab goes from memory straight into LDS (16 bytes per lane, 1 KB contiguous per wavefront and request: the
+    // order of the slab in LDS is the order of the threads' words).  No registers are involved, so the requests are
+    // made a whole slab of MFMAs ahead of the barrier that publishes them.
+    const unsigned wave_bytes = (unsigned)__builtin_amdgcn_readfirstlane(wave) * 1024u;   // (in a scalar register)
+    const unsigned lds_a = (unsigned)(size_t)WINO_G_LDS_PTR(&As[0][0]) + wave_bytes;
+    const unsigned lds_b = (unsigned)(size_t)WINO_G_LDS_PTR(&Bs[0][0]) + wave_bytes;
+    auto request_slab = [&](int buf) {
 #pragma unroll
-        for (int j = 0; j < AL; ++j)
-            ra[j] = __builtin_bit_cast(floatx4, (uintx4_g)__builtin_amdgcn_raw_buffer_load_b128(rsrc_a, oa[j], sa, 0));
+        for (int j = 0; j < AL; ++j) gemm_copy16_to_lds(rsrc_a, lds_a + (unsigned)(buf * BK * BM + j * NT * 4) * 4u, oa[j], sa);
 #pragma unroll
-        for (int j = 0; j < BL; ++j)
-            rb[j] = __builtin_bit_cast(floatx4, (uintx4_g)__builtin_amdgcn_raw_buffer_load_b128(rsrc_b, ob[j], sb, 0));
+        for (int j = 0; j < BL; ++j) gemm_copy16_to_lds(rsrc_b, lds_b + (unsigned)(buf * BK * BN + j * NT * 4) * 4u, ob[j], sb);
         sa += (unsigned)(BK * Kp) * 4u;
         sb += (unsigned)(BK * Pp) * 4u;
     };
-    auto store_lds = [&](int buf) {
-#pragma unroll
-        for (int j = 0; j < AL; ++j) *reinterpret_cast<floatx4 *>(&As[buf][(tid + j * NT) * 4]) = ra[j];
-#pragma unroll
-        for (int j = 0; j < BL; ++j) *reinterpret_cast<floatx4 *>(&Bs[buf][(tid + j * NT) * 4]) = rb[j];
-    };
+    // every copy this wavefront has requested has landed (the multiply makes no other vector-memory request)
+    auto slab_landed = [&]() { __builtin_amdgcn_s_waitcnt(0x0f70); };   // vmcnt(0)
     const int a_off = wm * (TM * 32) + li, b_off = wn * (TN * 32) + li;
     auto lds_load = [&](int buf, int half, float (&a)[HS][TM], float (&b)[HS][TN]) {
 #pragma unroll
@@ -138,18 +155,18 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_f32_kernel(const float *__r
 
     float a0[HS][TM], b0[HS][TN], a1[HS][TM], b1[HS][TN];
     const int nk = min(nk_split, Cp / BK - z * nk_split);   // >= 1 by construction of the launch
-    load_global();
-    store_lds(0);
+    request_slab(0);
+    slab_landed();
     __syncthreads();
     lds_load(0, 0, a0, b0);
     // all slabs but the last: fetch the next slab while multiplying the current one.  Two slabs per trip, so that
     // the LDS buffer of every access is known at compile time and its address is a per-lane base plus a constant
     // (with a buffer index computed in the loop, every LDS read cost a vector add in the MFMA issue slot).
     auto slab = [&](int cur) {
-        load_global();
+        request_slab(cur ^ 1);               // (the other buffer: everybody left it before the last barrier)
         lds_load(cur, 1, a1, b1);
         mma(a0, b0);
-        store_lds(cur ^ 1);
+        slab_landed();
         __syncthreads();
         lds_load(cur ^ 1, 0, a0, b0);
         mma(a1, b1);
