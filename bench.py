@@ -41,11 +41,11 @@ PEAK = {"hbm_GBs": 8000.0, "mfma_f32_TFs": 157.3, "mfma_f16_TFs": 2500.0}
 # `bench.py --probe` (summaries under profiles/); keyed by (workload, kernel).  None until measured.
 MEASURED_TRAFFIC = {
     # profiles/vgg16_n64_fp32_hbm_traffic.md (algorithmic: 487.7 MB resp. 850.0 MB per launch)
-    ("vgg16_3x3_conv_stack_N64_f32", "gemm_f32_kernel<128, 128, 2, 2, 16>"): 514.1e6,
-    ("vgg16_3x3_conv_stack_N64_f32", "fused_lds_kernel<false>"): 1051.7e6,
+    ("vgg16_3x3_conv_stack_N64_f32", "gemm_f32_kernel<128, 128, 2, 2, 16>"): 552.9e6,
+    ("vgg16_3x3_conv_stack_N64_f32", "fused_lds_kernel<false>"): 1052.2e6,
     # profiles/vgg16_n32_fp16_hbm_traffic.md (algorithmic: 328.7 MB resp. 183.5 MB per launch)
-    ("vgg16_3x3_conv_stack_N32_f16", "fused_f16_kernel<false, 2, float>"): 354.4e6,
-    ("vgg16_3x3_conv_stack_N32_f16", "gemm_f16_kernel<128, 128>"): 187.3e6,
+    ("vgg16_3x3_conv_stack_N32_f16", "fused_f16_kernel<false, 2, float>"): 354.6e6,
+    ("vgg16_3x3_conv_stack_N32_f16", "gemm_f16_kernel<128, 128>"): 187.4e6,
 }
 # Titan X (Maxwell) numbers of the paper, F(2x2,3x3), VGG network E (Tables 5 and 6): context only.
 PAPER_TITANX = {"fp32": {1: 7.03, 64: 9.37}, "fp16": {1: 7.06, 64: 10.28}}
@@ -409,16 +409,17 @@ def time_bwd_filter(torch, w, layers, steps):
     for L, dG in zip(layers, grads):
         for _ in range(2):
             w.wino_conv2d_bwd_filter(L.D, L.Y, pad=1, dG=dG, workspace=ws)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        ev[0].record()
+        for i in range(steps):
             w.wino_conv2d_bwd_filter(L.D, L.Y, pad=1, dG=dG, workspace=ws)
+            ev[i + 1].record()
         torch.cuda.synchronize()
-        sec = (time.perf_counter() - t0) / steps
+        sec = stats([ev[i].elapsed_time(ev[i + 1]) for i in range(steps)])["median"] / 1e3   # (a stray slow call is not the rate)
         per.append({"layer": L.name, "ms": sec * 1e3, "eff_tflops": L.flops / sec / 1e12})
     sec = sum(p["ms"] for p in per) / 1e3
     return {"eff_tflops": sum(L.flops for L in layers) / sec / 1e12, "ms_per_step": sec * 1e3, "layers": len(layers),
-            "per_layer": per, "note": "effective flops as for the forward pass"}
+            "per_layer": per, "note": "effective flops as for the forward pass; per layer the median of the timed calls"}
 
 
 def time_f6x6(torch, w, layers, layer_ms, steps):
