@@ -215,7 +215,8 @@ def test_variant_query_host_only(L):
 
 def test_gemm_launch_shape_host_only(L):
     """The block shape and channel shares of the multiply inside a layer call can be asked on the host."""
-    assert w.wino_gemm_launch_shape(512, 512, 64 * 49, 4) == (128, 128, 1)      # conv4.x at N = 64
+    assert w.wino_gemm_launch_shape(256, 256, 64 * 196, 4) == (128, 128, 1)     # conv3.x at N = 64: 27.6 blocks per CU
+    assert w.wino_gemm_launch_shape(512, 512, 64 * 49, 4) == (128, 64, 1)       # conv4.x: 14.06 per CU -> halved blocks
     bm, bn, shares = w.wino_gemm_launch_shape(512, 512, 49, 2)                 # conv5.x at N = 1: small blocks, split sum
     assert (bm, bn) == (64, 64) and shares >= 2
     assert w.wino_gemm_launch_shape(64, 64, 3136, 4)[:2] == (64, 128)
