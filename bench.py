@@ -40,12 +40,13 @@ PEAK = {"hbm_GBs": 8000.0, "mfma_f32_TFs": 157.3, "mfma_f16_TFs": 2500.0}
 # HBM bytes per launch of a workload's dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # `bench.py --probe` (summaries under profiles/); keyed by (workload, kernel).  None until measured.
 MEASURED_TRAFFIC = {
-    # profiles/vgg16_n64_fp32_hbm_traffic.md (algorithmic: 487.7 MB resp. 850.0 MB per launch)
-    ("vgg16_3x3_conv_stack_N64_f32", "gemm_f32_kernel<128, 128, 2, 2, 16>"): 552.9e6,
-    ("vgg16_3x3_conv_stack_N64_f32", "fused_lds_kernel<false>"): 1052.2e6,
+    # profiles/vgg16_n64_fp32_hbm_traffic.md (one-kernel layer: algorithmic 850.0 MB per launch)
+    ("vgg16_3x3_conv_stack_N64_f32", "gemm_f32_kernel<128, 128, 2, 2, 16>"): 985.8e6,   # 2 launches (algorithmic 934.3 MB)
+    ("vgg16_3x3_conv_stack_N64_f32", "gemm_f32_kernel<128, 64, 2, 2, 32>"): 351.9e6,    # 6 launches (algorithmic 338.8 MB)
+    ("vgg16_3x3_conv_stack_N64_f32", "fused_lds_kernel<false>"): 1051.8e6,
     # profiles/vgg16_n32_fp16_hbm_traffic.md (algorithmic: 328.7 MB resp. 183.5 MB per launch)
-    ("vgg16_3x3_conv_stack_N32_f16", "fused_f16_kernel<false, 2, float>"): 354.6e6,
-    ("vgg16_3x3_conv_stack_N32_f16", "gemm_f16_kernel<128, 128>"): 187.4e6,
+    ("vgg16_3x3_conv_stack_N32_f16", "fused_f16_kernel<false, 2, float>"): 354.1e6,
+    ("vgg16_3x3_conv_stack_N32_f16", "gemm_f16_kernel<128, 128>"): 187.3e6,
 }
 # Titan X (Maxwell) numbers of the paper, F(2x2,3x3), VGG network E (Tables 5 and 6): context only.
 PAPER_TITANX = {"fp32": {1: 7.03, 64: 9.37}, "fp16": {1: 7.06, 64: 10.28}}
@@ -322,10 +323,23 @@ def summarize_stages(w, layers, stages, dtype, workload):
                           "GBs": d["bytes"] / d["ms"] / 1e6, "frac_of_hbm_peak": d["bytes"] / d["ms"] / 1e6 / PEAK["hbm_GBs"]}
                       for k, d in dom.items()}
     if dom:
-        name, d = max(dom.items(), key=lambda kv: kv[1]["ms"])
+        # The dominant kernel is the kernel template with the largest share of the step; the library launches the
+        # multiply in two block shapes (two instantiations of one template), which are one kernel here: its figures
+        # are sums over all of its launches, the instances are listed with their launch counts and in `kernels`.
+        fam = {}
+        for k, v in dom.items():
+            f = fam.setdefault(k.split("<")[0], {"flops": 0.0, "ms": 0.0, "launches": 0, "bytes": 0.0, "min_ms": 0.0,
+                                                 "traffic": 0.0, "inst": []})
+            for key in ("flops", "ms", "launches", "bytes", "min_ms"):
+                f[key] += v[key]
+            f["inst"].append((k, v["launches"]))
+            t = MEASURED_TRAFFIC.get((workload, k))
+            f["traffic"] = None if (t is None or f["traffic"] is None) else f["traffic"] + t * v["launches"]
+        fname, d = max(fam.items(), key=lambda kv: kv[1]["ms"])
+        name = d["inst"][0][0] if len(d["inst"]) == 1 else fname + ": " + " + ".join("%d x %s" % (n, k) for k, n in d["inst"])
         ach = d["flops"] / d["ms"] / 1e9
         roof = {"bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
-                "traffic": MEASURED_TRAFFIC.get((workload, name)), "kernel": name,
+                "traffic": None if d["traffic"] is None else d["traffic"] / d["launches"], "kernel": name,
                 "launches_per_step": d["launches"], "avg_launch_ms": d["ms"] / d["launches"],
                 "min_launch_ms": d["min_ms"] / d["launches"], "flops_per_launch": d["flops"] / d["launches"]}
         # a kernel whose flops per algorithmic byte fall below the machine balance (peak flops / peak bytes) is
