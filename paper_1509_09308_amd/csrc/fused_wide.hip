@@ -1,0 +1,260 @@
+// Loops 2-4 of Algorithm 1 (Lavin & Gray) in one kernel, fp32 F(4x4,3x3), for layers with at least 64 filters:
+// the design of fused_lds.hip with twice the filters per transformed tile.  On this chip fp32 MFMAs and ordinary
+// vector instructions of one SIMD share an issue slot, so the arithmetic of the data transform is paid in MFMA
+// time; it is needed once per (tile, channel) and workgroup, whatever the number of filters the workgroup
+// multiplies the result with.
+//
+// Workgroup = 4 wavefronts owning 64 filters x 16 tiles x 36 components (144 accumulators per lane), two per CU.
+// Per step of 16 channels:
+//   1. transform phase: every thread owns one (tile, channel) pair; taps as in fused_lds.hip (buffer loads one
+//      step ahead, out-of-range markers for the implicit zero padding of Section 6); v = B^T (d B) goes to one
+//      of two LDS buffers as [e][channel][tile], so there is one barrier per step;
+//   2. multiply phase: wavefront cg owns components 9 cg .. 9 cg + 8 and walks four sub-steps of 4 channels
+//      (the depth of v_mfma_f32_16x16x4_f32).  The transformed filters do not pass through LDS (64 filters x
+//      16 channels x 36 components would fill it): lane (i, h) fetches U[e][channel h of the sub-step][filters
+//      4 i .. 4 i + 3] with one 16-byte buffer load, the A operands of the component's four MFMAs (MFMA f takes
+//      filter 4 i + f as its row i), and requests the same component of the next sub-step right after these
+//      MFMAs: nine components of MFMAs ahead of its use, in the register it replaces.
+// After the last step the accumulators go through LDS in four pieces (piece f = the filters 4 i + f); every thread
+// gathers the 36 components of one (filter, tile) pair, applies Y = A^T m A and writes its rows.
+// Needs pad = 1, W % 4 == 0 and the images one workgroup touches within 1 GiB.
+#include "wino_internal.h"
+#include "transforms.h"
+
+namespace wino {
+
+typedef float floatx4_w __attribute__((ext_vector_type(4)));
+
+constexpr int FW_K = 64, FW_P = 16, FW_C = 16, FW_T = 256;          // filters, tiles, channels per step, threads
+constexpr int FW_V_FLOATS = 36 * FW_C * FW_P;                       // transformed tiles of a step (one buffer)
+constexpr int FW_MS = 20;                                           // row stride of a piece of M (16 tiles + 4: no bank conflicts)
+constexpr int FW_M_FLOATS = 36 * 16 * FW_MS;                        // one piece of M in the epilogue
+constexpr unsigned FW_MAX_BYTES = 0x40000000u;                      // longest stretch of D one workgroup's buffer covers
+constexpr unsigned FW_ROW_OOB = 0x80000000u, FW_COL_OOB = 0x40000000u;   // offset markers of taps outside the image
+static_assert(FW_M_FLOATS <= 2 * FW_V_FLOATS, "the epilogue reuses the two tile buffers");
+
+// Barrier that orders LDS traffic only: global loads requested earlier stay in flight across it.
+__device__ __forceinline__ void fw_lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// CPAD: the channel count is not a multiple of 16, so the last step holds channel slots past the last channel.
+template <bool CPAD>
+__global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__restrict__ D, const float *__restrict__ U,
+                                                             float *__restrict__ Y, Geo g, int n_kb, int n_items)
+{
+    __shared__ __attribute__((aligned(16))) float smem[2 * FW_V_FLOATS];
+    const int tid = threadIdx.x;
+
+    // Resident workgroups walking a list of (tile block, filter block) items, one contiguous eighth of the items
+    // per XCD: see fused_lds.hip.
+    const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8, slots = gridDim.x / 8;
+    const int per_xcd = (n_items + 7) / 8;
+    const int item_end = min((xcd + 1) * per_xcd, n_items);
+    for (int item = xcd * per_xcd + slot; item < item_end; item += slots) {
+    const int kb = item % n_kb, tb = item / n_kb;
+    const int k0 = kb * FW_K, b0 = tb * FW_P;
+
+    // ---- transform-phase role: (tile, channel slot of the step) ---------------------------------
+    const int tl = tid & 15, cl = tid >> 4;
+    const int b = b0 + tl;
+    const bool tile_ok = b < g.P;
+    int orow = 0;
+    float *ybase = Y;
+    const int tiles_per_image = g.Th * g.Tw;
+    const int img0 = b0 / tiles_per_image;                     // uniform
+    unsigned vo_m[6];                                          // byte offset of columns 1..4 of row p, channel slot cl, step 0
+    unsigned adj_l, adj_r;
+    {
+        const int bb = tile_ok ? b : b0;
+        const int ty = bb % g.Tw;
+        const int t2 = bb / g.Tw;
+        const int tx = t2 % g.Th;
+        const int i = t2 / g.Th;
+        const int x0 = 4 * tx - 1, y0 = 4 * ty - 1;
+        orow = 4 * tx;
+        ybase = Y + ((size_t)i * g.K * g.Ho + orow) * g.Wo + 4 * ty;
+        adj_l = (y0 >= 0) ? 0xfffffffcu : FW_COL_OOB;             // -4 bytes
+        adj_r = (y0 + 5 < g.W) ? 16u : FW_COL_OOB;
+        const unsigned plane0 = (unsigned)((i - img0) * g.C + cl) * (unsigned)(g.H * g.W);
+#pragma unroll
+        for (int p = 0; p < 6; ++p) {
+            const int x = x0 + p;
+            const bool rok = tile_ok && x >= 0 && x < g.H;
+            vo_m[p] = rok ? (plane0 + (unsigned)(x * g.W + y0 + 1)) * 4u : FW_ROW_OOB;   // column y0 + 1 = 4 ty
+        }
+    }
+    const unsigned step_bytes = (unsigned)(FW_C * g.H * g.W) * 4u;
+    const size_t image_floats = (size_t)g.C * g.H * g.W;
+    const size_t left = ((size_t)g.N - img0) * image_floats * 4;
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(D + (size_t)img0 * image_floats), 0, (unsigned)(left < FW_MAX_BYTES ? left : FW_MAX_BYTES), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_u =
+        __builtin_amdgcn_make_buffer_rsrc((void *)U, 0, (unsigned)((size_t)36 * g.Cp * g.Kp * 4), 0x00020000);
+
+    // ---- multiply-phase role -------------------------------------------------------------------
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int cg = wave;
+    const int lj = lane & 15, lk = lane >> 4;
+    floatx4_w acc[9][4];
+#pragma unroll
+    for (int e = 0; e < 9; ++e)
+#pragma unroll
+        for (int f = 0; f < 4; ++f) acc[e][f] = floatx4_w{0.0f, 0.0f, 0.0f, 0.0f};
+
+    const int nsteps = (g.C + FW_C - 1) / FW_C;      // U holds zeros for the channels between C and Cp (a multiple of 16)
+
+    // A operands: U[((9 cg + e) Cp + 4 sub + lk) Kp + k0 + 4 lj .. + 3], sub = 4 step + sub-step.  Where the
+    // filter block reaches past Kp the last four columns are read instead: rows of filters that are never stored.
+    const unsigned uvo = (unsigned)(lk * g.Kp + min(k0 + 4 * lj, g.Kp - 4)) * 4u;
+    const unsigned ue_bytes = (unsigned)(g.Cp * g.Kp) * 4u, usub_bytes = (unsigned)(4 * g.Kp) * 4u;
+    unsigned su = (unsigned)(cg * 9) * ue_bytes;      // scalar offset of component 9 cg in the sub-step requested next
+    floatx4_w ua[9];
+    auto load_ua = [&](int e) {
+        ua[e] = __builtin_bit_cast(floatx4_w, __builtin_amdgcn_raw_buffer_load_b128(rsrc_u, uvo, su + e * ue_bytes, 0));
+    };
+    floatx4_w mid[6];
+    float l[6], r[6];
+    // `valid` false: nothing is fetched (every offset is a marker).  The request is made all the same, so that the
+    // number of loads in flight does not depend on the path taken (the compiler's wait counts take the minimum).
+    auto load_taps = [&](int step, bool valid) {
+        const unsigned so = valid ? (unsigned)step * step_bytes : 0u;
+        const bool ch_ok = valid && (!CPAD || (step * FW_C + cl < g.C));
+#pragma unroll
+        for (int p = 0; p < 6; ++p) {
+            const unsigned om = ch_ok ? vo_m[p] : FW_ROW_OOB;
+            mid[p] = __builtin_bit_cast(floatx4_w, __builtin_amdgcn_raw_buffer_load_b128(rsrc, om, so, 0));
+            l[p] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, om + adj_l, so, 0));
+            r[p] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, om + adj_r, so, 0));
+        }
+    };
+    // this thread's tile: rows then columns (v = B^T (d B)), scatter to LDS buffer `buf` as [e][channel][tile]
+    auto transform = [&](int buf) {
+        float t[6][6];
+#pragma unroll
+        for (int p = 0; p < 6; ++p) {
+            const float d[6] = {l[p], mid[p][0], mid[p][1], mid[p][2], mid[p][3], r[p]};
+            bt_mul<4>(d, t[p]);
+        }
+        float *dst = smem + buf * FW_V_FLOATS + tid;       // cl * 16 + tl = tid
+#pragma unroll
+        for (int q = 0; q < 6; ++q) {
+            const float col[6] = {t[0][q], t[1][q], t[2][q], t[3][q], t[4][q], t[5][q]};
+            float o[6];
+            bt_mul<4>(col, o);
+#pragma unroll
+            for (int p = 0; p < 6; ++p) dst[(p * 6 + q) * (FW_C * FW_P)] = o[p];
+        }
+    };
+    // nine components x four sub-steps x (64 filters x 16 tiles x 4 channels); B operand of lane (j, h) in
+    // sub-step t: channel 4 t + h of tile j, i.e. float e * 256 + t * 64 + lane of the buffer.  The first sub-step
+    // of a step is requested by the caller (after the transform phase, whose registers it would crowd).
+    auto multiply = [&](int buf) {
+        const float *vb = smem + buf * FW_V_FLOATS + cg * 9 * (FW_C * FW_P) + lane;
+        float bq[2];
+        bq[0] = vb[0];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+#pragma unroll
+            for (int e = 0; e < 9; ++e) {
+                const int n = t * 9 + e;
+                if (n + 1 < 36) bq[(n + 1) & 1] = vb[((n + 1) % 9) * (FW_C * FW_P) + ((n + 1) / 9) * 64];
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int f = 0; f < 4; ++f)
+                    acc[e][f] = __builtin_amdgcn_mfma_f32_16x16x4f32(ua[e][f], bq[n & 1], acc[e][f], 0, 0, 0);
+                if (t < 3) load_ua(e);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (t < 3) su += usub_bytes;
+        }
+    };
+    auto request_first_substep = [&]() {
+#pragma unroll
+        for (int e = 0; e < 9; ++e) load_ua(e);
+        su += usub_bytes;
+    };
+
+    // One iteration = transform phase of a step, then its multiply phase; the taps a transform phase consumes were
+    // requested in the iteration before (first: here), right after the barrier, when their registers came free.
+    load_taps(0, true);
+    for (int step = 0; step < nsteps; ++step) {
+        const int buf = step & 1;
+        transform(buf);
+        request_first_substep();
+        fw_lds_barrier();
+        load_taps(step + 1, step + 1 < nsteps);
+        multiply(buf);
+    }
+    __syncthreads();
+
+    // ---- inverse transform: four pieces of 16 filters (piece f = filters k0 + 4 i + f, i = 0..15) ----------
+    float *Ms = smem;
+    const int irow = tid >> 4;                 // 0..15: filter row of the piece handled in the gather
+    const int ot = tid & 15;                   // tile of the gather (same tile as in the transform phase)
+#pragma unroll
+    for (int f = 0; f < 4; ++f) {
+        // accumulator register rr of lane (lj, lk) is row 4 lk + rr, tile lj
+#pragma unroll
+        for (int e = 0; e < 9; ++e)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) Ms[((cg * 9 + e) * 16 + 4 * lk + rr) * FW_MS + lj] = acc[e][f][rr];
+        __syncthreads();
+        const int k = k0 + 4 * irow + f;
+        if (tile_ok && k < g.K) {
+            float m[6][6], tt[4][6], y[4][4];
+#pragma unroll
+            for (int xi = 0; xi < 6; ++xi)
+#pragma unroll
+                for (int nu = 0; nu < 6; ++nu) m[xi][nu] = Ms[((xi * 6 + nu) * 16 + irow) * FW_MS + ot];
+#pragma unroll
+            for (int nu = 0; nu < 6; ++nu) {
+                const float col[6] = {m[0][nu], m[1][nu], m[2][nu], m[3][nu], m[4][nu], m[5][nu]};
+                float o[4];
+                at_mul<4>(col, o);
+#pragma unroll
+                for (int p = 0; p < 4; ++p) tt[p][nu] = o[p];
+            }
+#pragma unroll
+            for (int p = 0; p < 4; ++p) at_mul<4>(tt[p], y[p]);
+            float *dst = ybase + (size_t)k * g.Ho * g.Wo;
+#pragma unroll
+            for (int p = 0; p < 4; ++p)
+                if (orow + p < g.Ho)
+                    __builtin_nontemporal_store(floatx4_w{y[p][0], y[p][1], y[p][2], y[p][3]},
+                                                reinterpret_cast<floatx4_w *>(dst + (size_t)p * g.Wo));
+        }
+        __syncthreads();
+    }
+    }   // items
+}
+
+bool fused_wide_eligible(const Geo &g)
+{
+    // the tiles of one workgroup span at most `span` images; their byte offsets from the first must stay below 2^30
+    const unsigned long long tiles = (unsigned long long)g.Th * g.Tw;
+    const unsigned long long span = (FW_P + tiles - 2) / tiles + 1;
+    const unsigned long long image_bytes = (unsigned long long)g.C * g.H * g.W * 4ull;
+    return g.dt == WINO_F32 && g.m == 4 && g.pad == 1 && g.W % 4 == 0 && g.Kp >= FW_K &&
+           span * image_bytes + 65536 < FW_MAX_BYTES &&
+           (unsigned long long)36 * g.Cp * g.Kp * 4ull < (1ull << 31);   // 32-bit byte offsets into U
+}
+
+hipError_t launch_fused_wide(const Geo &g, const float *D, const float *U, float *Y, hipStream_t s)
+{
+    const int n_kb = (g.Kp + FW_K - 1) / FW_K;
+    const long long items = (long long)((g.P + FW_P - 1) / FW_P) * n_kb;
+    if (items > 0x7fffffffLL) return hipErrorInvalidValue;
+    // two workgroups per CU (what registers and LDS allow) on 256 CUs, in multiples of the 8 XCDs
+    const unsigned grid = (unsigned)(items >= 512 ? 512 : (items + 7) / 8 * 8);
+    if (g.C % FW_C != 0)
+        fused_wide_kernel<true><<<dim3(grid), dim3(FW_T), 0, s>>>(D, U, Y, g, n_kb, (int)items);
+    else
+        fused_wide_kernel<false><<<dim3(grid), dim3(FW_T), 0, s>>>(D, U, Y, g, n_kb, (int)items);
+    return hipGetLastError();
+}
+
+}  // namespace wino

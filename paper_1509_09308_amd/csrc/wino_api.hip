@@ -313,9 +313,13 @@ static int run_layer(const Geo &g, int y_dt, const void *D, const void *G, const
         U = Uw;
     }
     if (flags == WINO_FLAG_FUSED) {
-        // fp32 with pad 1 and W % 4 == 0: the design with two workgroups per CU; otherwise the general one
-        e = fused_lds_eligible(g) ? launch_fused_lds(g, (const float *)D, (const float *)U, (float *)Y, s)
-                                  : launch_fused(g, D, U, Y, y_dt, s);
+        // fp32 with pad 1 and W % 4 == 0: the designs with two workgroups per CU (64 filters per workgroup where
+        // there are that many); otherwise the general one
+        if (fused_wide_eligible(g))
+            e = launch_fused_wide(g, (const float *)D, (const float *)U, (float *)Y, s);
+        else
+            e = fused_lds_eligible(g) ? launch_fused_lds(g, (const float *)D, (const float *)U, (float *)Y, s)
+                                      : launch_fused(g, D, U, Y, y_dt, s);
         if (e != hipSuccess) return hip_fail(e);
         return WINO_OK;
     }

@@ -42,6 +42,8 @@ hipError_t launch_fused(const Geo &g, const void *D, const void *U, void *Y, int
 bool fused_f16_eligible(const Geo &g);
 bool fused_lds_eligible(const Geo &g);
 hipError_t launch_fused_lds(const Geo &g, const float *D, const float *U, float *Y, hipStream_t s);
+bool fused_wide_eligible(const Geo &g);
+hipError_t launch_fused_wide(const Geo &g, const float *D, const float *U, float *Y, hipStream_t s);
 hipError_t launch_fused_f16(const Geo &g, const void *D, const void *U, void *Y, int y_dt, hipStream_t s);
 bool fused_f2_eligible(const Geo &g);
 hipError_t launch_fused_f2(const Geo &g, const float *D, const float *G, float *Y, void *workspace,

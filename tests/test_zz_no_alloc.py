@@ -1,6 +1,8 @@
 """The entry point that allocates nothing (wino_conv2d_fwd_noalloc: workspace built into the library) against
 the entry point it is a variant of (wino_conv2d_fwd: workspace from hipMalloc) and against the oracle.  Same
 kernels, same launch choices: the two outputs must be equal bit for bit."""
+import gc
+
 import numpy as np
 import pytest
 
@@ -16,6 +18,7 @@ def _one_call(torch, w, shape, m, seed):
     D, G = synth.make_layer(N, C, H, W, K, seed=seed)
     d, g = to_gpu(D), to_gpu(G)
     Y = torch.full((N, K, H, W), float("nan"), dtype=torch.float32, device="cuda")
+    gc.collect()                                            # tensors of earlier tests must not be freed in between
     before = torch.cuda.memory_allocated()
     w.wino_conv2d_fwd_noalloc(d, g, Y, pad=1, m=m)
     torch.cuda.synchronize()
