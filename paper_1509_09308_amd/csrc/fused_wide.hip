@@ -27,11 +27,15 @@ typedef float floatx4_w __attribute__((ext_vector_type(4)));
 
 constexpr int FW_K = 64, FW_P = 16, FW_C = 16, FW_T = 256;          // filters, tiles, channels per step, threads
 constexpr int FW_V_FLOATS = 36 * FW_C * FW_P;                       // transformed tiles of a step (one buffer)
-constexpr int FW_MS = 20;                                           // row stride of a piece of M (16 tiles + 4: no bank conflicts)
-constexpr int FW_M_FLOATS = 36 * 16 * FW_MS;                        // one piece of M in the epilogue
+constexpr int FW_M_FLOATS = 36 * 16 * 16;                           // one piece of M in the epilogue: [e][filter row][tile]
 constexpr unsigned FW_MAX_BYTES = 0x40000000u;                      // longest stretch of D one workgroup's buffer covers
 constexpr unsigned FW_ROW_OOB = 0x80000000u, FW_COL_OOB = 0x40000000u;   // offset markers of taps outside the image
 static_assert(FW_M_FLOATS <= 2 * FW_V_FLOATS, "the epilogue reuses the two tile buffers");
+
+// Position of filter row r (0..15) within a component of a piece of M.  Rows are 16 floats, so two rows of equal
+// parity share their banks; a wavefront writes rows r and r + 4 together and reads rows r and r + 1 together, and
+// with this permutation both pairs differ in parity.
+__device__ __forceinline__ int fw_m_row(int r) { return r ^ ((r >> 2) & 1); }
 
 // Barrier that orders LDS traffic only: global loads requested earlier stay in flight across it.
 __device__ __forceinline__ void fw_lds_barrier()
@@ -113,8 +117,8 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
     const unsigned ue_bytes = (unsigned)(g.Cp * g.Kp) * 4u, usub_bytes = (unsigned)(4 * g.Kp) * 4u;
     unsigned su = (unsigned)(cg * 9) * ue_bytes;      // scalar offset of component 9 cg in the sub-step requested next
     floatx4_w ua[9];
-    auto load_ua = [&](int e) {
-        ua[e] = __builtin_bit_cast(floatx4_w, __builtin_amdgcn_raw_buffer_load_b128(rsrc_u, uvo, su + e * ue_bytes, 0));
+    auto load_ua = [&](int e, unsigned vo) {
+        ua[e] = __builtin_bit_cast(floatx4_w, __builtin_amdgcn_raw_buffer_load_b128(rsrc_u, vo, su + e * ue_bytes, 0));
     };
     floatx4_w mid[6];
     float l[6], r[6];
@@ -150,9 +154,12 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
         }
     };
     // nine components x four sub-steps x (64 filters x 16 tiles x 4 channels); B operand of lane (j, h) in
-    // sub-step t: channel 4 t + h of tile j, i.e. float e * 256 + t * 64 + lane of the buffer.  The first sub-step
-    // of a step is requested by the caller (after the transform phase, whose registers it would crowd).
-    auto multiply = [&](int buf) {
+    // sub-step t: channel 4 t + h of tile j, i.e. float e * 256 + t * 64 + lane of the buffer.
+    auto multiply = [&](int buf, bool more) {
+        // the next step's first sub-step is requested during the last sub-step of this one (in flight over the
+        // transform phase); with no next step the request is made with an offset behind the buffer, which fetches
+        // nothing, so that the number of loads in flight does not depend on the path taken
+        const unsigned uvo_next = more ? uvo : 0x80000000u;
         const float *vb = smem + buf * FW_V_FLOATS + cg * 9 * (FW_C * FW_P) + lane;
         float bq[2];
         bq[0] = vb[0];
@@ -166,28 +173,26 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
 #pragma unroll
                 for (int f = 0; f < 4; ++f)
                     acc[e][f] = __builtin_amdgcn_mfma_f32_16x16x4f32(ua[e][f], bq[n & 1], acc[e][f], 0, 0, 0);
-                if (t < 3) load_ua(e);
+                load_ua(e, t < 3 ? uvo : uvo_next);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (t < 3) su += usub_bytes;
+            su += usub_bytes;
         }
-    };
-    auto request_first_substep = [&]() {
-#pragma unroll
-        for (int e = 0; e < 9; ++e) load_ua(e);
-        su += usub_bytes;
     };
 
     // One iteration = transform phase of a step, then its multiply phase; the taps a transform phase consumes were
     // requested in the iteration before (first: here), right after the barrier, when their registers came free.
     load_taps(0, true);
+#pragma unroll
+    for (int e = 0; e < 9; ++e) load_ua(e, uvo);
+    su += usub_bytes;
     for (int step = 0; step < nsteps; ++step) {
         const int buf = step & 1;
+        const bool more = step + 1 < nsteps;
         transform(buf);
-        request_first_substep();
         fw_lds_barrier();
-        load_taps(step + 1, step + 1 < nsteps);
-        multiply(buf);
+        load_taps(step + 1, more);
+        multiply(buf, more);
     }
     __syncthreads();
 
@@ -201,7 +206,7 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
 #pragma unroll
         for (int e = 0; e < 9; ++e)
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) Ms[((cg * 9 + e) * 16 + 4 * lk + rr) * FW_MS + lj] = acc[e][f][rr];
+            for (int rr = 0; rr < 4; ++rr) Ms[((cg * 9 + e) * 16 + fw_m_row(4 * lk + rr)) * 16 + lj] = acc[e][f][rr];
         __syncthreads();
         const int k = k0 + 4 * irow + f;
         if (tile_ok && k < g.K) {
@@ -209,7 +214,7 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
 #pragma unroll
             for (int xi = 0; xi < 6; ++xi)
 #pragma unroll
-                for (int nu = 0; nu < 6; ++nu) m[xi][nu] = Ms[((xi * 6 + nu) * 16 + irow) * FW_MS + ot];
+                for (int nu = 0; nu < 6; ++nu) m[xi][nu] = Ms[((xi * 6 + nu) * 16 + fw_m_row(irow)) * 16 + ot];
 #pragma unroll
             for (int nu = 0; nu < 6; ++nu) {
                 const float col[6] = {m[0][nu], m[1][nu], m[2][nu], m[3][nu], m[4][nu], m[5][nu]};
