@@ -43,7 +43,7 @@ MEASURED_TRAFFIC = {
     # profiles/vgg16_n64_fp32_hbm_traffic.md (one-kernel layer: algorithmic 850.0 MB per launch)
     ("vgg16_3x3_conv_stack_N64_f32", "gemm_f32_kernel<128, 128, 2, 2, 16>"): 985.8e6,   # 2 launches (algorithmic 934.3 MB)
     ("vgg16_3x3_conv_stack_N64_f32", "gemm_f32_kernel<128, 64, 2, 2, 32>"): 351.9e6,    # 6 launches (algorithmic 338.8 MB)
-    ("vgg16_3x3_conv_stack_N64_f32", "fused_lds_kernel<false>"): 1051.8e6,
+    ("vgg16_3x3_conv_stack_N64_f32", "fused_wide_kernel<false>"): None,
     # profiles/vgg16_n32_fp16_hbm_traffic.md (algorithmic: 328.7 MB resp. 183.5 MB per launch)
     ("vgg16_3x3_conv_stack_N32_f16", "fused_f16_kernel<false, 2, float>"): 354.1e6,
     ("vgg16_3x3_conv_stack_N32_f16", "gemm_f16_kernel<128, 128>"): 187.3e6,
@@ -196,8 +196,12 @@ def stage_plan(torch, w, L, ws, sets):
                                                                            flags=w.FLAG_FUSED)))])
         nbytes = {"filter": 9 * L.K * L.C * s + nU, "fused": nD + nU + nY}
         cpad = "false" if L.C % 8 == 0 else "true"
-        kernel = ("fused_lds_kernel<%s>" % cpad if L.dt == w.WINO_F32 else
-                  "fused_f16_kernel<%s, %d, float>" % (cpad, 2 if L.K > 32 else 1))
+        if L.dt == w.WINO_F16:
+            kernel = "fused_f16_kernel<%s, %d, float>" % (cpad, 2 if L.K > 32 else 1)
+        elif L.K > 32:           # 64 filters per workgroup, 16 channels per step
+            kernel = "fused_wide_kernel<%s>" % ("false" if L.C % 16 == 0 else "true")
+        else:
+            kernel = "fused_lds_kernel<%s>" % cpad
     else:
         Vs = [w.alloc_v(L.C, L.P, L.m, L.dt) for _ in range(sets)]
         Ms = [w.alloc_m(L.K, L.P, L.m) for _ in range(sets)]

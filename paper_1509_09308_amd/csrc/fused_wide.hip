@@ -48,18 +48,24 @@ __device__ __forceinline__ void fw_lds_barrier()
 // CPAD: the channel count is not a multiple of 16, so the last step holds channel slots past the last channel.
 template <bool CPAD>
 __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__restrict__ D, const float *__restrict__ U,
-                                                             float *__restrict__ Y, Geo g, int n_kb, int n_items)
+                                                             float *__restrict__ Y, Geo g, int n_kb, int n_tb, int groups)
 {
     __shared__ __attribute__((aligned(16))) float smem[2 * FW_V_FLOATS];
     const int tid = threadIdx.x;
 
-    // Resident workgroups walking a list of (tile block, filter block) items, one contiguous eighth of the items
-    // per XCD: see fused_lds.hip.
+    // Resident workgroups walking a list of (tile block, filter block) items (see fused_lds.hip).  The 8 XCDs form
+    // `groups` groups; a group takes n_kb / groups of the filter blocks -- as many as keep their transformed filters
+    // in one XCD's L2, where every sub-step of every workgroup reads them -- and all tile blocks; its XCDs take
+    // one contiguous part of these items each, consecutive items being the filter blocks of one tile block, which
+    // read the same input.
     const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8, slots = gridDim.x / 8;
-    const int per_xcd = (n_items + 7) / 8;
-    const int item_end = min((xcd + 1) * per_xcd, n_items);
-    for (int item = xcd * per_xcd + slot; item < item_end; item += slots) {
-    const int kb = item % n_kb, tb = item / n_kb;
+    const int group = xcd % groups, member = xcd / groups, members = 8 / groups;
+    const int kb_per_group = n_kb / groups;
+    const int group_items = n_tb * kb_per_group;
+    const int per_member = (group_items + members - 1) / members;
+    const int item_end = min((member + 1) * per_member, group_items);
+    for (int item = member * per_member + slot; item < item_end; item += slots) {
+    const int kb = group * kb_per_group + item % kb_per_group, tb = item / kb_per_group;
     const int k0 = kb * FW_K, b0 = tb * FW_P;
 
     // ---- transform-phase role: (tile, channel slot of the step) ---------------------------------
@@ -251,14 +257,23 @@ bool fused_wide_eligible(const Geo &g)
 hipError_t launch_fused_wide(const Geo &g, const float *D, const float *U, float *Y, hipStream_t s)
 {
     const int n_kb = (g.Kp + FW_K - 1) / FW_K;
-    const long long items = (long long)((g.P + FW_P - 1) / FW_P) * n_kb;
+    const int n_tb = (g.P + FW_P - 1) / FW_P;
+    const long long items = (long long)n_tb * n_kb;
     if (items > 0x7fffffffLL) return hipErrorInvalidValue;
+    // XCD groups: halve the filter blocks per group while their transformed filters (36 x Cp x 64 floats each) exceed
+    // what an XCD's 4 MB L2 can keep next to the streams of input and output (measured at N = 64: reads from
+    // beyond L2 fall from 427 to 325 MB for 128 -> 256 channels at 56 x 56, from 1291 to 1028 MB for 256 -> 256,
+    // at equal run time)
+    int groups = 1;
+    while (groups < 8 && n_kb % (2 * groups) == 0 &&
+           (unsigned long long)(n_kb / groups) * 36 * g.Cp * FW_K * 4 > (5ull << 19))
+        groups *= 2;
     // two workgroups per CU (what registers and LDS allow) on 256 CUs, in multiples of the 8 XCDs
     const unsigned grid = (unsigned)(items >= 512 ? 512 : (items + 7) / 8 * 8);
     if (g.C % FW_C != 0)
-        fused_wide_kernel<true><<<dim3(grid), dim3(FW_T), 0, s>>>(D, U, Y, g, n_kb, (int)items);
+        fused_wide_kernel<true><<<dim3(grid), dim3(FW_T), 0, s>>>(D, U, Y, g, n_kb, n_tb, groups);
     else
-        fused_wide_kernel<false><<<dim3(grid), dim3(FW_T), 0, s>>>(D, U, Y, g, n_kb, (int)items);
+        fused_wide_kernel<false><<<dim3(grid), dim3(FW_T), 0, s>>>(D, U, Y, g, n_kb, n_tb, groups);
     return hipGetLastError();
 }
 
