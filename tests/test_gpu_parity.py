@@ -279,7 +279,12 @@ def test_config5_full_size_sampled(layer):
 @pytest.mark.parametrize("shape", [(2, 16, 8, 8, 16, 1), (1, 4, 12, 12, 8, 1), (2, 64, 28, 28, 64, 1),
                                    (1, 19, 13, 29, 70, 1), (3, 33, 14, 14, 65, 1), (2, 16, 31, 18, 130, 0),
                                    (1, 7, 67, 131, 9, 1), (1, 1, 3, 3, 1, 1), (1, 1, 4, 4, 1, 0), (5, 130, 9, 9, 40, 1),
-                                   (8, 512, 28, 28, 512, 1)])
+                                   (8, 512, 28, 28, 512, 1),
+                                   # 64 filters per workgroup (W % 4 == 0, more than 32 filters): ragged filter block,
+                                   # channels not a multiple of 16, tile count not a multiple of 16, several images
+                                   # per tile block, 8 x 4 filter blocks in XCD groups
+                                   (3, 40, 12, 20, 96, 1), (2, 24, 8, 8, 200, 1), (1, 130, 20, 36, 70, 1),
+                                   (5, 16, 4, 4, 64, 1), (2, 272, 16, 16, 256, 1)])
 def test_fused_path_matches_oracle(shape):
     """F(4x4,3x3) with V and M kept on chip: whole output against the oracle, including ragged
     edges, pad 0, channel counts that are not multiples of 4 and filter counts below a block."""
