@@ -7,8 +7,11 @@
 // Workgroup = 4 wavefronts owning 64 filters x 16 tiles x 36 components (144 accumulators per lane), two per CU.
 // Per step of 16 channels:
 //   1. transform phase: every thread owns one (tile, channel) pair; taps as in fused_lds.hip (buffer loads one
-//      step ahead, out-of-range markers for the implicit zero padding of Section 6); v = B^T (d B) goes to one
-//      of two LDS buffers as [e][channel][tile], so there is one barrier per step;
+//      step ahead, out-of-range markers for the implicit zero padding of Section 6), except that a tile's outer
+//      columns come from the registers of the neighbouring lanes (DPP) instead of from memory: requests of 4 bytes
+//      per lane at a stride of 16 bytes cost the vector memory path as much as the 16-byte ones next to them, and
+//      without them the kernel runs a tenth faster; v = B^T (d B) goes to one of two LDS buffers as
+//      [e][channel][tile], so there is one barrier per step;
 //   2. multiply phase: wavefront cg owns components 9 cg .. 9 cg + 8 and walks four sub-steps of 4 channels
 //      (the depth of v_mfma_f32_16x16x4_f32).  The transformed filters do not pass through LDS (64 filters x
 //      16 channels x 36 components would fill it): lane (i, h) fetches U[e][channel h of the sub-step][filters
@@ -77,7 +80,14 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
     const int tiles_per_image = g.Th * g.Tw;
     const int img0 = b0 / tiles_per_image;                     // uniform
     unsigned vo_m[6];                                          // byte offset of columns 1..4 of row p, channel slot cl, step 0
-    unsigned adj_l, adj_r;
+    // The outer columns (0 and 5) of a tile are column 4 of the tile to its left and column 1 of the tile to its
+    // right.  The 16 tiles of the workgroup sit in the 16 lanes of a DPP row, so a lane takes them from its
+    // neighbours' registers; only the first lane of a row has to fetch its left column and the last lane its right
+    // column (one request per tile row, `edge_adj` = where, or a marker for the lanes in between).  A tile at the
+    // image's left or right border has zeros there (`left_in`, `right_in`), whatever its neighbour lane holds: the
+    // last tile of the tile row above, or the first of the one below.
+    unsigned edge_adj;
+    bool left_in, right_in;
     {
         const int bb = tile_ok ? b : b0;
         const int ty = bb % g.Tw;
@@ -87,8 +97,9 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
         const int x0 = 4 * tx - 1, y0 = 4 * ty - 1;
         orow = 4 * tx;
         ybase = Y + ((size_t)i * g.K * g.Ho + orow) * g.Wo + 4 * ty;
-        adj_l = (y0 >= 0) ? 0xfffffffcu : FW_COL_OOB;             // -4 bytes
-        adj_r = (y0 + 5 < g.W) ? 16u : FW_COL_OOB;
+        left_in = y0 >= 0;
+        right_in = y0 + 5 < g.W;
+        edge_adj = (tl == 0 && left_in) ? 0xfffffffcu /* -4 bytes */ : (tl == 15 && right_in) ? 16u : FW_COL_OOB;
         const unsigned plane0 = (unsigned)((i - img0) * g.C + cl) * (unsigned)(g.H * g.W);
 #pragma unroll
         for (int p = 0; p < 6; ++p) {
@@ -127,7 +138,7 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
         ua[e] = __builtin_bit_cast(floatx4_w, __builtin_amdgcn_raw_buffer_load_b128(rsrc_u, vo, su + e * ue_bytes, 0));
     };
     floatx4_w mid[6];
-    float l[6], r[6];
+    float ed[6];
     // `valid` false: nothing is fetched (every offset is a marker).  The request is made all the same, so that the
     // number of loads in flight does not depend on the path taken (the compiler's wait counts take the minimum).
     auto load_taps = [&](int step, bool valid) {
@@ -137,8 +148,7 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
         for (int p = 0; p < 6; ++p) {
             const unsigned om = ch_ok ? vo_m[p] : FW_ROW_OOB;
             mid[p] = __builtin_bit_cast(floatx4_w, __builtin_amdgcn_raw_buffer_load_b128(rsrc, om, so, 0));
-            l[p] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, om + adj_l, so, 0));
-            r[p] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, om + adj_r, so, 0));
+            ed[p] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, om + edge_adj, so, 0));
         }
     };
     // this thread's tile: rows then columns (v = B^T (d B)), scatter to LDS buffer `buf` as [e][channel][tile]
@@ -146,7 +156,15 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
         float t[6][6];
 #pragma unroll
         for (int p = 0; p < 6; ++p) {
-            const float d[6] = {l[p], mid[p][0], mid[p][1], mid[p][2], mid[p][3], r[p]};
+            // column 4 of the lane below (row_shr:1), column 1 of the lane above (row_shl:1); the first and the last
+            // lane of the row, which have no such neighbour, keep the value they fetched
+            const float c1 = mid[p][0], c4 = mid[p][3];      // (a bit cast applied to a vector element would read element 0)
+            const int e_bits = __builtin_bit_cast(int, ed[p]);
+            const int l_bits = __builtin_amdgcn_update_dpp(e_bits, __builtin_bit_cast(int, c4), 0x111, 0xf, 0xf, false);
+            const int r_bits = __builtin_amdgcn_update_dpp(e_bits, __builtin_bit_cast(int, c1), 0x101, 0xf, 0xf, false);
+            const float lv = left_in ? __builtin_bit_cast(float, l_bits) : 0.0f;
+            const float rv = right_in ? __builtin_bit_cast(float, r_bits) : 0.0f;
+            const float d[6] = {lv, mid[p][0], mid[p][1], mid[p][2], mid[p][3], rv};
             bt_mul<4>(d, t[p]);
         }
         float *dst = smem + buf * FW_V_FLOATS + tid;       // cl * 16 + tl = tid
