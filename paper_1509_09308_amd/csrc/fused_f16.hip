@@ -106,7 +106,16 @@ __global__ __launch_bounds__(256 * KH, 3 - KH) void fused_f16_kernel(const __hal
     const int tiles_per_image = g.Th * g.Tw;
     const int img0 = b0 / tiles_per_image;                     // uniform
     unsigned vo_m[6];                                          // byte offset of columns 1..4 of row p, channel slot cl, step 0
-    unsigned adj_l, adj_r;
+    // The outer columns (0 and 5) of a tile are column 4 of the tile to its left and column 1 of the tile to its
+    // right, and neighbouring tiles sit in neighbouring lanes: a lane takes them from its neighbours' registers
+    // (DPP, within rows of 16 lanes) instead of from memory -- requests of 2 bytes per lane at a stride of 8 bytes
+    // cost the vector memory path as much as the 8-byte ones next to them.  Only the first lane of a row of 16 has
+    // to fetch its left column and the last lane its right column: one 4-byte request per tile row (`edge_adj` =
+    // where, or a marker for the lanes in between) for the word that the missing neighbour would hold, columns
+    // 3 and 4 of the tile to the left resp. 1 and 2 of the tile to the right.  A tile at the image's left or right
+    // border has zeros there (`left_in`, `right_in`), whatever its neighbour lane holds.
+    unsigned edge_adj;
+    bool left_in, right_in;
     {
         const int bb = tile_ok ? b : b0;
         const int ty = bb % g.Tw;
@@ -114,8 +123,9 @@ __global__ __launch_bounds__(256 * KH, 3 - KH) void fused_f16_kernel(const __hal
         const int tx = t2 % g.Th;
         const int i = t2 / g.Th;
         const int x0 = 4 * tx - 1, y0 = 4 * ty - 1;
-        adj_l = (y0 >= 0) ? 0xfffffffeu : HF_COL_OOB;              // -2 bytes
-        adj_r = (y0 + 5 < g.W) ? 8u : HF_COL_OOB;
+        left_in = y0 >= 0;
+        right_in = y0 + 5 < g.W;
+        edge_adj = ((tl & 15) == 0 && left_in) ? 0xfffffffcu /* -4 bytes */ : ((tl & 15) == 15 && right_in) ? 8u : HF_COL_OOB;
         const unsigned plane0 = (unsigned)((i - img0) * g.C + cl) * (unsigned)(g.H * g.W);
 #pragma unroll
         for (int p = 0; p < 6; ++p) {
@@ -143,11 +153,12 @@ __global__ __launch_bounds__(256 * KH, 3 - KH) void fused_f16_kernel(const __hal
 
     const int nsteps = g.Cp / HF_C;
 
-    // raw fp16 taps of one tile: per row the four middle columns (8 bytes) and the two outer ones.
-    // They are requested one step ahead, at the start of the multiply phase of the step before.
+    // raw fp16 taps of one tile: per row the four middle columns (8 bytes) and, in the lanes at the ends of a row
+    // of 16, the word with the outer column.  They are requested one step ahead, at the start of the multiply
+    // phase of the step before.
     typedef unsigned uintx2_h __attribute__((ext_vector_type(2)));
     uintx2_h rmid[6];
-    unsigned short rl[6], rr[6];
+    unsigned red[6];
     auto load_raw = [&](int step) {
         const unsigned so = (unsigned)step * step_bytes;
         const bool ch_ok = !CPAD || (step * HF_C + cl < g.C);
@@ -155,8 +166,7 @@ __global__ __launch_bounds__(256 * KH, 3 - KH) void fused_f16_kernel(const __hal
         for (int p = 0; p < 6; ++p) {
             const unsigned om = ch_ok ? vo_m[p] : HF_ROW_OOB;
             rmid[p] = __builtin_amdgcn_raw_buffer_load_b64(rsrc, om, so, 0);
-            rl[p] = __builtin_amdgcn_raw_buffer_load_b16(rsrc, om + adj_l, so, 0);
-            rr[p] = __builtin_amdgcn_raw_buffer_load_b16(rsrc, om + adj_r, so, 0);
+            red[p] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, om + edge_adj, so, 0);
         }
     };
     // Transformed filters of a step, [e][c8 = step][k] -> Us[e * 32 + k]: direct global -> LDS loads of
@@ -194,8 +204,13 @@ __global__ __launch_bounds__(256 * KH, 3 - KH) void fused_f16_kernel(const __hal
                 const unsigned w01 = rmid[p][0], w23 = rmid[p][1];      // (a bit cast wants a scalar object, not a vector element)
                 const __half2 h01 = __builtin_bit_cast(__half2, w01);
                 const __half2 h23 = __builtin_bit_cast(__half2, w23);
-                const float d[6] = {__half2float(__builtin_bit_cast(__half, rl[p])), __low2float(h01), __high2float(h01),
-                                    __low2float(h23), __high2float(h23), __half2float(__builtin_bit_cast(__half, rr[p]))};
+                // columns (3, 4) of the lane below (row_shr:1), columns (1, 2) of the lane above (row_shl:1); the
+                // first and the last lane of a row of 16, which have no such neighbour, keep the word they fetched
+                const unsigned wl = (unsigned)__builtin_amdgcn_update_dpp((int)red[p], (int)w23, 0x111, 0xf, 0xf, false);
+                const unsigned wr = (unsigned)__builtin_amdgcn_update_dpp((int)red[p], (int)w01, 0x101, 0xf, 0xf, false);
+                const float lv = left_in ? __high2float(__builtin_bit_cast(__half2, wl)) : 0.0f;
+                const float rv = right_in ? __low2float(__builtin_bit_cast(__half2, wr)) : 0.0f;
+                const float d[6] = {lv, __low2float(h01), __high2float(h01), __low2float(h23), __high2float(h23), rv};
                 bt_mul<4>(d, t[p]);
             }
             __half *dst = Vs + ((size_t)(cl >> 2) * HF_P + tl) * 4 + (cl & 3);   // [e][c / 4][tile][c % 4]
