@@ -21,6 +21,8 @@
 // After the last step the accumulators go through LDS in four pieces (piece f = the filters 4 i + f); every thread
 // gathers the 36 components of one (filter, tile) pair, applies Y = A^T m A and writes its rows.
 // Needs pad = 1, W % 4 == 0 and the images one workgroup touches within 1 GiB.
+#include <type_traits>
+
 #include "wino_internal.h"
 #include "transforms.h"
 
@@ -82,11 +84,13 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
     unsigned vo_m[6];                                          // byte offset of columns 1..4 of row p, channel slot cl, step 0
     // The outer columns (0 and 5) of a tile are column 4 of the tile to its left and column 1 of the tile to its
     // right.  The 16 tiles of the workgroup sit in the 16 lanes of a DPP row, so a lane takes them from its
-    // neighbours' registers; only the first lane of a row has to fetch its left column and the last lane its right
-    // column (one request per tile row, `edge_adj` = where, or a marker for the lanes in between).  A tile at the
-    // image's left or right border has zeros there (`left_in`, `right_in`), whatever its neighbour lane holds: the
-    // last tile of the tile row above, or the first of the one below.
-    unsigned edge_adj;
+    // neighbours' registers; only the first lane of a row lacks its left neighbour and the last lane its right one.
+    // Those twelve values per step (six tile rows each) are fetched by ONE request in which lanes 1..6 of the row
+    // ask for the first lane's left column of tile rows 0..5 and lanes 8..13 for the last lane's right column
+    // (`edge_off`; a marker in the other lanes), and handed over by DPP as well.  A tile at the image's left or
+    // right border has zeros there (`left_in`, `right_in`), whatever its neighbour lane holds: the last tile of the
+    // tile row above, or the first of the one below.
+    unsigned edge_off;
     bool left_in, right_in;
     {
         const int bb = tile_ok ? b : b0;
@@ -99,7 +103,6 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
         ybase = Y + ((size_t)i * g.K * g.Ho + orow) * g.Wo + 4 * ty;
         left_in = y0 >= 0;
         right_in = y0 + 5 < g.W;
-        edge_adj = (tl == 0 && left_in) ? 0xfffffffcu /* -4 bytes */ : (tl == 15 && right_in) ? 16u : FW_COL_OOB;
         const unsigned plane0 = (unsigned)((i - img0) * g.C + cl) * (unsigned)(g.H * g.W);
 #pragma unroll
         for (int p = 0; p < 6; ++p) {
@@ -107,6 +110,26 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
             const bool rok = tile_ok && x >= 0 && x < g.H;
             vo_m[p] = rok ? (plane0 + (unsigned)(x * g.W + y0 + 1)) * 4u : FW_ROW_OOB;   // column y0 + 1 = 4 ty
         }
+        // Every lane forms the offsets of its own outer columns (marked where they lie outside the image); lane
+        // 1 + p then takes the left one of tile row p from the first lane of its DPP row and lane 8 + p the right
+        // one from the last lane.  A shift by n also reaches the lanes further on: the left chain runs with n
+        // rising and the right chain with n falling, so that the value from the end lane is the last one a lane
+        // receives.
+        const unsigned adj_l = left_in ? 0xfffffffcu /* -4 bytes */ : FW_COL_OOB, adj_r = right_in ? 16u : FW_COL_OOB;
+        int from_first = (int)FW_COL_OOB, from_last = (int)FW_COL_OOB;
+        from_first = __builtin_amdgcn_update_dpp(from_first, (int)(vo_m[0] + adj_l), 0x111, 0xf, 0xf, false);   // row_shr:1
+        from_first = __builtin_amdgcn_update_dpp(from_first, (int)(vo_m[1] + adj_l), 0x112, 0xf, 0xf, false);
+        from_first = __builtin_amdgcn_update_dpp(from_first, (int)(vo_m[2] + adj_l), 0x113, 0xf, 0xf, false);
+        from_first = __builtin_amdgcn_update_dpp(from_first, (int)(vo_m[3] + adj_l), 0x114, 0xf, 0xf, false);
+        from_first = __builtin_amdgcn_update_dpp(from_first, (int)(vo_m[4] + adj_l), 0x115, 0xf, 0xf, false);
+        from_first = __builtin_amdgcn_update_dpp(from_first, (int)(vo_m[5] + adj_l), 0x116, 0xf, 0xf, false);
+        from_last = __builtin_amdgcn_update_dpp(from_last, (int)(vo_m[5] + adj_r), 0x102, 0xf, 0xf, false);     // row_shl:2
+        from_last = __builtin_amdgcn_update_dpp(from_last, (int)(vo_m[4] + adj_r), 0x103, 0xf, 0xf, false);
+        from_last = __builtin_amdgcn_update_dpp(from_last, (int)(vo_m[3] + adj_r), 0x104, 0xf, 0xf, false);
+        from_last = __builtin_amdgcn_update_dpp(from_last, (int)(vo_m[2] + adj_r), 0x105, 0xf, 0xf, false);
+        from_last = __builtin_amdgcn_update_dpp(from_last, (int)(vo_m[1] + adj_r), 0x106, 0xf, 0xf, false);
+        from_last = __builtin_amdgcn_update_dpp(from_last, (int)(vo_m[0] + adj_r), 0x107, 0xf, 0xf, false);
+        edge_off = (tl >= 1 && tl <= 6) ? (unsigned)from_first : (tl >= 8 && tl <= 13) ? (unsigned)from_last : FW_COL_OOB;
     }
     const unsigned step_bytes = (unsigned)(FW_C * g.H * g.W) * 4u;
     const size_t image_floats = (size_t)g.C * g.H * g.W;
@@ -138,7 +161,7 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
         ua[e] = __builtin_bit_cast(floatx4_w, __builtin_amdgcn_raw_buffer_load_b128(rsrc_u, vo, su + e * ue_bytes, 0));
     };
     floatx4_w mid[6];
-    float ed[6];
+    float ed;
     // `valid` false: nothing is fetched (every offset is a marker).  The request is made all the same, so that the
     // number of loads in flight does not depend on the path taken (the compiler's wait counts take the minimum).
     auto load_taps = [&](int step, bool valid) {
@@ -148,25 +171,34 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
         for (int p = 0; p < 6; ++p) {
             const unsigned om = ch_ok ? vo_m[p] : FW_ROW_OOB;
             mid[p] = __builtin_bit_cast(floatx4_w, __builtin_amdgcn_raw_buffer_load_b128(rsrc, om, so, 0));
-            ed[p] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, om + edge_adj, so, 0));
         }
+        ed = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, ch_ok ? edge_off : FW_ROW_OOB, so, 0));
     };
     // this thread's tile: rows then columns (v = B^T (d B)), scatter to LDS buffer `buf` as [e][channel][tile]
     auto transform = [&](int buf) {
         float t[6][6];
-#pragma unroll
-        for (int p = 0; p < 6; ++p) {
+        // tile row p (a compile-time constant: it selects the DPP shifts)
+        auto row = [&](auto pc) {
+            constexpr int p = decltype(pc)::value;
             // column 4 of the lane below (row_shr:1), column 1 of the lane above (row_shl:1); the first and the last
-            // lane of the row, which have no such neighbour, keep the value they fetched
+            // lane of the row, which have no such neighbour, keep what lane 1 + p resp. 8 + p fetched for them
             const float c1 = mid[p][0], c4 = mid[p][3];      // (a bit cast applied to a vector element would read element 0)
-            const int e_bits = __builtin_bit_cast(int, ed[p]);
-            const int l_bits = __builtin_amdgcn_update_dpp(e_bits, __builtin_bit_cast(int, c4), 0x111, 0xf, 0xf, false);
-            const int r_bits = __builtin_amdgcn_update_dpp(e_bits, __builtin_bit_cast(int, c1), 0x101, 0xf, 0xf, false);
+            const int e_bits = __builtin_bit_cast(int, ed);
+            const int for_first = __builtin_amdgcn_update_dpp(0, e_bits, 0x101 + p, 0xf, 0xf, false);   // row_shl:(1 + p)
+            const int for_last = __builtin_amdgcn_update_dpp(0, e_bits, 0x117 - p, 0xf, 0xf, false);    // row_shr:(7 - p)
+            const int l_bits = __builtin_amdgcn_update_dpp(for_first, __builtin_bit_cast(int, c4), 0x111, 0xf, 0xf, false);
+            const int r_bits = __builtin_amdgcn_update_dpp(for_last, __builtin_bit_cast(int, c1), 0x101, 0xf, 0xf, false);
             const float lv = left_in ? __builtin_bit_cast(float, l_bits) : 0.0f;
             const float rv = right_in ? __builtin_bit_cast(float, r_bits) : 0.0f;
             const float d[6] = {lv, mid[p][0], mid[p][1], mid[p][2], mid[p][3], rv};
             bt_mul<4>(d, t[p]);
-        }
+        };
+        row(std::integral_constant<int, 0>());
+        row(std::integral_constant<int, 1>());
+        row(std::integral_constant<int, 2>());
+        row(std::integral_constant<int, 3>());
+        row(std::integral_constant<int, 4>());
+        row(std::integral_constant<int, 5>());
         float *dst = smem + buf * FW_V_FLOATS + tid;       // cl * 16 + tl = tid
 #pragma unroll
         for (int q = 0; q < 6; ++q) {
