@@ -40,13 +40,12 @@ PEAK = {"hbm_GBs": 8000.0, "mfma_f32_TFs": 157.3, "mfma_f16_TFs": 2500.0}
 # HBM bytes per launch of a workload's dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # `bench.py --probe` (summaries under profiles/); keyed by (workload, kernel).  None until measured.
 MEASURED_TRAFFIC = {
-    # profiles/vgg16_n64_fp32_hbm_traffic.md (one-kernel layer: algorithmic 850.0 MB per launch)
-    ("vgg16_3x3_conv_stack_N64_f32", "gemm_f32_kernel<128, 128, 2, 2, 16>"): 985.8e6,   # 2 launches (algorithmic 934.3 MB)
-    ("vgg16_3x3_conv_stack_N64_f32", "gemm_f32_kernel<128, 64, 2, 2, 32>"): 351.9e6,    # 6 launches (algorithmic 338.8 MB)
-    ("vgg16_3x3_conv_stack_N64_f32", "fused_wide_kernel<false>"): None,
+    # profiles/vgg16_n64_fp32_hbm_traffic.md
+    ("vgg16_3x3_conv_stack_N64_f32", "gemm_f32_kernel<128, 64, 2, 2, 32>"): 351.5e6,    # 6 launches (algorithmic 338.8 MB)
+    ("vgg16_3x3_conv_stack_N64_f32", "fused_wide_kernel<false>"): 1099.1e6,     # 6 launches (algorithmic 706.8 MB)
     # profiles/vgg16_n32_fp16_hbm_traffic.md (algorithmic: 328.7 MB resp. 183.5 MB per launch)
-    ("vgg16_3x3_conv_stack_N32_f16", "fused_f16_kernel<false, 2, float>"): 354.1e6,
-    ("vgg16_3x3_conv_stack_N32_f16", "gemm_f16_kernel<128, 128>"): 187.3e6,
+    ("vgg16_3x3_conv_stack_N32_f16", "fused_f16_kernel<false, 2, float>"): 355.8e6,
+    ("vgg16_3x3_conv_stack_N32_f16", "gemm_f16_kernel<128, 128>"): 187.4e6,
 }
 # Titan X (Maxwell) numbers of the paper, F(2x2,3x3), VGG network E (Tables 5 and 6): context only.
 PAPER_TITANX = {"fp32": {1: 7.03, 64: 9.37}, "fp16": {1: 7.06, 64: 10.28}}
