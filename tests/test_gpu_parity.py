@@ -350,3 +350,33 @@ def test_fused_flag_rejected_where_unsupported():
     with pytest.raises(w.WinoError) as ei:
         w.wino_conv2d_fwd_ex(to_gpu(D2), G=to_gpu(G2), pad=1, m=4, flags=w.FLAG_FUSED)
     assert ei.value.status == w.WINO_EUNSUPPORTED
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("pos", [(0, 0), (3, 27), (4, 0), (7, 28), (11, 55), (12, 31), (15, 32)])
+def test_one_kernel_path_keeps_a_nan_inside_the_tiles_that_read_it(dtype, pos):
+    """The one-kernel kernels take a tile's outer columns from the registers of the neighbouring lanes, which hold
+    the neighbouring tiles -- or, at the image border, the last tile of the tile row above resp. the first of the
+    one below, whose values must not be used.  One NaN in the input must reach exactly the outputs of the tiles
+    whose 6 x 6 window (rows 4 tx - 1 .. 4 tx + 4, columns 4 ty - 1 .. 4 ty + 4) holds it, in the image that has
+    it: a value leaking over from a neighbouring lane would poison a tile outside that set.  Within such a tile
+    the first window row (column) enters only the first transformed component (B^T of Eq. (15) has (4, 0, ...) as
+    its first column), which feeds only the first output row (column); the last one likewise only the last."""
+    torch, w = require_gpu()
+    N, C, H, W, K = 2, 16, 16, 56, 64          # 14 tiles per row: blocks of 16 (or 32) lanes straddle tile rows
+    np_dt = np.float32 if dtype == "f32" else np.float16
+    D, G = synth.make_layer(N, C, H, W, K, seed=4242, dtype=np_dt)
+    x, y = pos
+    D[1, 5, x, y] = np.nan
+    Y = w.wino_conv2d_fwd_ex(to_gpu(D), G=to_gpu(G), pad=1, m=4, flags=w.FLAG_FUSED).float().cpu().numpy()
+    want = np.zeros((N, H, W), dtype=bool)
+    def reached(t, z):          # outputs of tile t along one axis that a NaN at coordinate z of that axis reaches
+        q = z - (4 * t - 1)
+        return [] if q < 0 or q > 5 else [4 * t] if q == 0 else [4 * t + 3] if q == 5 else list(range(4 * t, 4 * t + 4))
+    for tx in range(H // 4):
+        for ty in range(W // 4):
+            for ox in reached(tx, x):
+                for oy in reached(ty, y):
+                    want[1, ox, oy] = True
+    got = np.isnan(Y)
+    assert (got == want[:, None, :, :]).all(), "NaN outputs %d, expected %d" % (got.sum(), want.sum() * K)
