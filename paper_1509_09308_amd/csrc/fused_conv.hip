@@ -408,10 +408,11 @@ bool fused_preferred(const Geo &g)
         return (long long)g.K * g.C <= 100LL * (g.K + g.C) && (long long)((g.P + 31) / 32) * ((g.K + 63) / 64) >= 256;
     if (!fused_lds_eligible(g)) return g.K <= 128 && blocks >= 512;
     if ((long long)g.K * g.C <= 100LL * (g.K + g.C) && blocks >= 512) return true;
-    // with 64 filters per workgroup (fused_wide.hip) the tie moves up past 256 -> 256 channels (56 x 56: 0.59 against
-    // 0.73 ms at N = 64, 0.38 against 0.41 at N = 32, 0.21 against 0.22 at N = 16) and sits at 256 -> 512
-    // (28 x 28, K C / (K + C) = 171: 0.39 against 0.39 ms at N = 64), which stays with the four stages
-    if (fused_wide_eligible(g) && (long long)g.K * g.C <= 130LL * (g.K + g.C) &&
+    // with 64 filters per workgroup (fused_wide.hip) the crossover moves up past 256 -> 256 channels (56 x 56: 0.59
+    // against 0.73 ms at N = 64, 0.38 against 0.41 at N = 32, 0.21 against 0.22 at N = 16) and 256 -> 512 (28 x 28,
+    // K C / (K + C) = 171: 0.32 against 0.36 ms at N = 64, 0.19 against 0.21 at N = 32, a tie at N = 16); 512 -> 512
+    // (256) stays with the four stages (0.71 against 0.65 ms)
+    if (fused_wide_eligible(g) && (long long)g.K * g.C <= 175LL * (g.K + g.C) &&
         (long long)((g.P + 15) / 16) * ((g.Kp + 63) / 64) >= 512)
         return true;
     // small batches: with very few filters and channels (64 -> 64) one launch that does everything still beats

@@ -185,7 +185,7 @@ def test_variant_query_host_only(L):
     assert w.wino_conv2d_variant(64, 256, 56, 56, 256, 1, 4) == w.FLAG_FUSED        # 128: 64 filters per workgroup win
     assert w.wino_conv2d_variant(32, 256, 56, 56, 256, 1, 4) == w.FLAG_FUSED
     assert w.wino_conv2d_variant(4, 256, 56, 56, 256, 1, 4) == w.FLAG_UNFUSED       # ... with a workgroup for every slot
-    assert w.wino_conv2d_variant(64, 256, 28, 28, 512, 1, 4) == w.FLAG_UNFUSED      # 171
+    assert w.wino_conv2d_variant(64, 256, 28, 28, 512, 1, 4) == w.FLAG_FUSED        # 171: still ahead
     assert w.wino_conv2d_variant(1, 64, 224, 224, 64, 1, 4) == w.FLAG_FUSED         # batch 1, 64 -> 64: 196 workgroups suffice
     assert w.wino_conv2d_variant(1, 128, 112, 112, 128, 1, 4) == w.FLAG_UNFUSED     # too few workgroups
     assert w.wino_conv2d_variant(64, 64, 224, 224, 64, 1, 2) == w.FLAG_UNFUSED      # F(2x2) has no fused kernel
