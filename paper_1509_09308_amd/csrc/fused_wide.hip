@@ -166,13 +166,17 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
     // number of loads in flight does not depend on the path taken (the compiler's wait counts take the minimum).
     auto load_taps = [&](int step, bool valid) {
         const unsigned so = valid ? (unsigned)step * step_bytes : 0u;
-        const bool ch_ok = valid && (!CPAD || (step * FW_C + cl < g.C));
+        // (an OR with a uniform mask, not a choice between two offsets: the compiler turns the latter into a branch
+        // around two load instructions, and behind the join it waits for every request in flight)
+        const unsigned off_mask = valid ? 0u : FW_ROW_OOB;
+        const bool ch_ok = !CPAD || (step * FW_C + cl < g.C);
 #pragma unroll
         for (int p = 0; p < 6; ++p) {
-            const unsigned om = ch_ok ? vo_m[p] : FW_ROW_OOB;
+            const unsigned om = (ch_ok ? vo_m[p] : FW_ROW_OOB) | off_mask;
             mid[p] = __builtin_bit_cast(floatx4_w, __builtin_amdgcn_raw_buffer_load_b128(rsrc, om, so, 0));
         }
-        ed = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, ch_ok ? edge_off : FW_ROW_OOB, so, 0));
+        ed = __builtin_bit_cast(float,
+                                __builtin_amdgcn_raw_buffer_load_b32(rsrc, (ch_ok ? edge_off : FW_ROW_OOB) | off_mask, so, 0));
     };
     // this thread's tile: rows then columns (v = B^T (d B)), scatter to LDS buffer `buf` as [e][channel][tile]
     auto transform = [&](int buf) {
@@ -239,6 +243,9 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
     // One iteration = transform phase of a step, then its multiply phase; the taps a transform phase consumes were
     // requested in the iteration before (first: here), right after the barrier, when their registers came free.
     load_taps(0, true);
+    // (kept in this order: were the filter requests moved ahead of the taps, the wait for the taps at the top of
+    // the loop -- which the compiler derives from both ways into it -- would also end the filter requests' flight)
+    __builtin_amdgcn_sched_barrier(0x38f);        // everything but memory requests may cross
 #pragma unroll
     for (int e = 0; e < 9; ++e) load_ua(e, uvo);
     su += usub_bytes;
