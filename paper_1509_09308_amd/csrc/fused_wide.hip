@@ -188,8 +188,9 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
             // lane of the row, which have no such neighbour, keep what lane 1 + p resp. 8 + p fetched for them
             const float c1 = mid[p][0], c4 = mid[p][3];      // (a bit cast applied to a vector element would read element 0)
             const int e_bits = __builtin_bit_cast(int, ed);
-            const int for_first = __builtin_amdgcn_update_dpp(0, e_bits, 0x101 + p, 0xf, 0xf, false);   // row_shl:(1 + p)
-            const int for_last = __builtin_amdgcn_update_dpp(0, e_bits, 0x117 - p, 0xf, 0xf, false);    // row_shr:(7 - p)
+            // (lanes without a source lane read 0: only the first resp. the last lane's value is used)
+            const int for_first = __builtin_amdgcn_mov_dpp(e_bits, 0x101 + p, 0xf, 0xf, true);   // row_shl:(1 + p)
+            const int for_last = __builtin_amdgcn_mov_dpp(e_bits, 0x117 - p, 0xf, 0xf, true);    // row_shr:(7 - p)
             const int l_bits = __builtin_amdgcn_update_dpp(for_first, __builtin_bit_cast(int, c4), 0x111, 0xf, 0xf, false);
             const int r_bits = __builtin_amdgcn_update_dpp(for_last, __builtin_bit_cast(int, c1), 0x101, 0xf, 0xf, false);
             const float lv = left_in ? __builtin_bit_cast(float, l_bits) : 0.0f;

@@ -24,12 +24,12 @@ template <> __device__ __forceinline__ void bt_mul<4>(const float *d, float *o)
     const float s31 = d[3] - 4.0f * d[1];   // d3 - 4 d1
     const float t42 = d[4] - d[2];          // d4 - d2
     const float t31 = 2.0f * (d[3] - d[1]); // 2 d3 - 2 d1
-    o[0] = 4.0f * d[0] - 5.0f * d[2] + d[4];
+    o[0] = fmaf(4.0f, d[0], fmaf(-5.0f, d[2], d[4]));   // two instructions (written as a sum of products: three)
     o[1] = s42 + s31;
     o[2] = s42 - s31;
     o[3] = t42 + t31;
     o[4] = t42 - t31;
-    o[5] = 4.0f * d[1] - 5.0f * d[3] + d[5];
+    o[5] = fmaf(4.0f, d[1], fmaf(-5.0f, d[3], d[5]));
 }
 
 template <> __device__ __forceinline__ void bt_mul<6>(const float *d, float *o)
