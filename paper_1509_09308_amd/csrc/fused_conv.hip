@@ -411,10 +411,18 @@ bool fused_preferred(const Geo &g)
     // with 64 filters per workgroup (fused_wide.hip) the crossover moves up past 256 -> 256 channels (56 x 56: 0.59
     // against 0.73 ms at N = 64, 0.38 against 0.41 at N = 32, 0.21 against 0.22 at N = 16) and 256 -> 512 (28 x 28,
     // K C / (K + C) = 171: 0.32 against 0.36 ms at N = 64, 0.19 against 0.21 at N = 32, a tie at N = 16); 512 -> 512
-    // (256) stays with the four stages (0.71 against 0.65 ms)
-    if (fused_wide_eligible(g) && (long long)g.K * g.C <= 175LL * (g.K + g.C) &&
-        (long long)((g.P + 15) / 16) * ((g.Kp + 63) / 64) >= 512)
-        return true;
+    // (256) was a loss (0.71 against 0.65 ms) until the items of a partly filled last round were shared between
+    // workgroups.  Since then it depends on how well the rounds are filled (fused_wide_fill): at 28 x 28, 512 -> 512
+    // channels, -6 % at N = 64 (fill 0.93), -9 % at N = 40 (0.96), -3 % at N = 48 and 96 (0.88, 0.92), -6 % at
+    // N = 128, but +9 % at N = 32 (0.77) and +3 % at N = 24 (0.80); 384 -> 384: -7 % at N = 64 (0.88), -2 % at
+    // N = 32 (0.79); 512 -> 512 at 56 x 56: -1 to -6 % (0.92 to 0.97).
+    const long long wide_items = (long long)((g.P + 15) / 16) * ((g.Kp + 63) / 64);
+    // Three quarters of the resident workgroups suffice up to 175 (320 -> 320 at 28 x 28: -26 % with 490 items,
+    // -12 % with 368; 384 -> 384: -8 % with 444; 512 -> 256: a tie with 392, +23 % with 296).
+    if (fused_wide_eligible(g)) {
+        if ((long long)g.K * g.C <= 175LL * (g.K + g.C) && wide_items >= 384) return true;
+        if ((long long)g.K * g.C <= 256LL * (g.K + g.C) && wide_items >= 512 && fused_wide_fill(g) >= 0.85) return true;
+    }
     // small batches: with very few filters and channels (64 -> 64) one launch that does everything still beats
     // three launches as soon as it has a workgroup for every other CU (batch 1, 224 x 224: 32 vs 37 us)
     const long long items = (long long)((g.P + 31) / 32) * (g.Kp / 32);

@@ -21,6 +21,12 @@
 // After the last step the accumulators go through LDS in four pieces (piece f = the filters 4 i + f); every thread
 // gathers the 36 components of one (filter, tile) pair, applies Y = A^T m A and writes its rows.
 // Needs pad = 1, W % 4 == 0 and the images one workgroup touches within 1 GiB.
+//
+// The 512 resident workgroups take the items of their XCD round by round.  A last round that fills only part of
+// them would leave most CUs idle for the length of an item, so its items are cut into shares of their channel
+// steps, one workgroup per share: each share applies the (linear) inverse transform to its partial sums, stores
+// partial outputs in the workspace and takes a ticket; the share that arrives last adds the partial outputs in
+// share order and writes Y.  Nobody waits for anybody, and the result does not depend on the order of arrival.
 #include <type_traits>
 
 #include "wino_internal.h"
@@ -36,6 +42,56 @@ constexpr int FW_M_FLOATS = 36 * 16 * 16;                           // one piece
 constexpr unsigned FW_MAX_BYTES = 0x40000000u;                      // longest stretch of D one workgroup's buffer covers
 constexpr unsigned FW_ROW_OOB = 0x80000000u, FW_COL_OOB = 0x40000000u;   // offset markers of taps outside the image
 static_assert(FW_M_FLOATS <= 2 * FW_V_FLOATS, "the epilogue reuses the two tile buffers");
+constexpr int FW_GRID = 512;                                        // resident workgroups: two per CU
+constexpr int FW_SHARE_FLOATS = FW_K * FW_P * 16;                   // partial outputs of one share
+constexpr int FW_TICKET_BYTES = FW_GRID * 4;                        // arrival counters in front of the partial outputs
+
+// The items an XCD's workgroups walk (`count` of them, `slots` workgroups): `full` items in rounds that occupy
+// every workgroup, then `tail` items cut into `shares` shares of their `nsteps` channel steps each.  Items of
+// fewer than 16 steps are not shared, nor are items that could only be halved: the workgroups of a partly filled
+// round have their CUs to themselves and run 1.7 times faster for it, and the hand-over costs about 10 us
+// (measured at batch 64: 256 channels and more gain 2-9 % per layer, 64 and 128 channels lose 1.5 %).
+struct FwRounds {
+    int full, tail, shares;
+};
+__host__ __device__ inline FwRounds fw_rounds(int count, int slots, int nsteps, bool may_share)
+{
+    FwRounds r;
+    r.full = may_share && nsteps >= 16 ? count / slots * slots : count;
+    r.tail = count - r.full;
+    r.shares = 1;
+    while (r.tail > 0 && r.shares < 8 && r.shares * 2 * r.tail <= slots && nsteps % (r.shares * 2) == 0) r.shares *= 2;
+    if (r.shares < 4) r.full = count, r.tail = 0, r.shares = 1;      // the last round runs whole items
+    return r;
+}
+// Items of XCD `xcd`: [first, first + count) of its group's list (see the kernel).
+__host__ __device__ inline void fw_list(int xcd, int groups, int n_kb, int n_tb, int *first, int *count)
+{
+    const int member = xcd / groups, members = 8 / groups;
+    const int group_items = n_tb * (n_kb / groups);
+    const int per_member = (group_items + members - 1) / members;
+    const int end = (member + 1) * per_member < group_items ? (member + 1) * per_member : group_items;
+    *first = member * per_member;
+    *count = end > *first ? end - *first : 0;
+}
+
+// Partial outputs pass between workgroups that may sit on different XCDs, whose L2 caches are not coherent with
+// each other: they are written and read with agent-scope atomic accesses (relaxed, 8 bytes), which go through to
+// the level all XCDs share.  A store counts in the wavefront's vmcnt until that level has acknowledged it, so
+// every wavefront waits for vmcnt(0) before the barrier that precedes the ticket (see fused_f2.hip).
+typedef float floatx2_w __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void fw_st_agent(float *p, float a, float b)
+{
+    const floatx2_w v = {a, b};
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), __builtin_bit_cast(unsigned long long, v),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ floatx2_w fw_ld_agent(const float *p)
+{
+    const unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+    return __builtin_bit_cast(floatx2_w, u);
+}
 
 // Position of filter row r (0..15) within a component of a piece of M.  Rows are 16 floats, so two rows of equal
 // parity share their banks; a wavefront writes rows r and r + 4 together and reads rows r and r + 1 together, and
@@ -53,7 +109,8 @@ __device__ __forceinline__ void fw_lds_barrier()
 // CPAD: the channel count is not a multiple of 16, so the last step holds channel slots past the last channel.
 template <bool CPAD>
 __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__restrict__ D, const float *__restrict__ U,
-                                                             float *__restrict__ Y, Geo g, int n_kb, int n_tb, int groups)
+                                                             float *__restrict__ Y, Geo g, int n_kb, int n_tb, int groups,
+                                                             float *__restrict__ part)
 {
     __shared__ __attribute__((aligned(16))) float smem[2 * FW_V_FLOATS];
     const int tid = threadIdx.x;
@@ -64,12 +121,29 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
     // one contiguous part of these items each, consecutive items being the filter blocks of one tile block, which
     // read the same input.
     const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8, slots = gridDim.x / 8;
-    const int group = xcd % groups, member = xcd / groups, members = 8 / groups;
+    const int group = xcd % groups;
     const int kb_per_group = n_kb / groups;
-    const int group_items = n_tb * kb_per_group;
-    const int per_member = (group_items + members - 1) / members;
-    const int item_end = min((member + 1) * per_member, group_items);
-    for (int item = member * per_member + slot; item < item_end; item += slots) {
+    int first, count;
+    fw_list(xcd, groups, n_kb, n_tb, &first, &count);
+    // (no shares without a workspace for partial outputs: `part` null)
+    const int nsteps_all = (g.C + FW_C - 1) / FW_C;  // U holds zeros for the channels between C and Cp (a multiple of 16)
+    const FwRounds rounds = fw_rounds(count, slots, nsteps_all, part != nullptr);
+    const int full = rounds.full, tail = rounds.tail, shares = rounds.shares;
+    unsigned int *const tickets = reinterpret_cast<unsigned int *>(part);
+    float *const partial = part + FW_TICKET_BYTES / 4;
+    for (int it = slot;; it += slots) {
+    int item, step0 = 0, nsteps = nsteps_all;
+    bool shared = false;
+    if (it < full) {
+        item = first + it;
+    } else if (it - full < tail * shares) {
+        item = first + full + (it - full) % tail;
+        shared = true;
+        nsteps = nsteps_all / shares;
+        step0 = (it - full) / tail * nsteps;
+    } else {
+        break;
+    }
     const int kb = group * kb_per_group + item % kb_per_group, tb = item / kb_per_group;
     const int k0 = kb * FW_K, b0 = tb * FW_P;
 
@@ -149,13 +223,11 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
 #pragma unroll
         for (int f = 0; f < 4; ++f) acc[e][f] = floatx4_w{0.0f, 0.0f, 0.0f, 0.0f};
 
-    const int nsteps = (g.C + FW_C - 1) / FW_C;      // U holds zeros for the channels between C and Cp (a multiple of 16)
-
     // A operands: U[((9 cg + e) Cp + 4 sub + lk) Kp + k0 + 4 lj .. + 3], sub = 4 step + sub-step.  Where the
     // filter block reaches past Kp the last four columns are read instead: rows of filters that are never stored.
     const unsigned uvo = (unsigned)(lk * g.Kp + min(k0 + 4 * lj, g.Kp - 4)) * 4u;
     const unsigned ue_bytes = (unsigned)(g.Cp * g.Kp) * 4u, usub_bytes = (unsigned)(4 * g.Kp) * 4u;
-    unsigned su = (unsigned)(cg * 9) * ue_bytes;      // scalar offset of component 9 cg in the sub-step requested next
+    unsigned su = (unsigned)(cg * 9) * ue_bytes + (unsigned)(4 * step0) * usub_bytes;      // scalar offset of component 9 cg in the sub-step requested next
     floatx4_w ua[9];
     auto load_ua = [&](int e, unsigned vo) {
         ua[e] = __builtin_bit_cast(floatx4_w, __builtin_amdgcn_raw_buffer_load_b128(rsrc_u, vo, su + e * ue_bytes, 0));
@@ -243,7 +315,7 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
 
     // One iteration = transform phase of a step, then its multiply phase; the taps a transform phase consumes were
     // requested in the iteration before (first: here), right after the barrier, when their registers came free.
-    load_taps(0, true);
+    load_taps(step0, true);
     // (kept in this order: were the filter requests moved ahead of the taps, the wait for the taps at the top of
     // the loop -- which the compiler derives from both ways into it -- would also end the filter requests' flight)
     __builtin_amdgcn_sched_barrier(0x38f);        // everything but memory requests may cross
@@ -255,7 +327,7 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
         const bool more = step + 1 < nsteps;
         transform(buf);
         fw_lds_barrier();
-        load_taps(step + 1, more);
+        load_taps(step0 + step + 1, more);
         multiply(buf, more);
     }
     __syncthreads();
@@ -289,14 +361,72 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
             }
 #pragma unroll
             for (int p = 0; p < 4; ++p) at_mul<4>(tt[p], y[p]);
-            float *dst = ybase + (size_t)k * g.Ho * g.Wo;
+            if (!shared) {
+                float *dst = ybase + (size_t)k * g.Ho * g.Wo;
 #pragma unroll
-            for (int p = 0; p < 4; ++p)
-                if (orow + p < g.Ho)
-                    __builtin_nontemporal_store(floatx4_w{y[p][0], y[p][1], y[p][2], y[p][3]},
-                                                reinterpret_cast<floatx4_w *>(dst + (size_t)p * g.Wo));
+                for (int p = 0; p < 4; ++p)
+                    if (orow + p < g.Ho)
+                        __builtin_nontemporal_store(floatx4_w{y[p][0], y[p][1], y[p][2], y[p][3]},
+                                                    reinterpret_cast<floatx4_w *>(dst + (size_t)p * g.Wo));
+            } else {
+                // partial outputs of this share: [piece f][half row j][thread] pairs of floats
+                float *dst = partial + (size_t)(xcd * slots + (it - full)) * FW_SHARE_FLOATS + (f * 8 * FW_T + tid) * 2;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) fw_st_agent(dst + j * FW_T * 2, y[j >> 1][2 * (j & 1)], y[j >> 1][2 * (j & 1) + 1]);
+            }
         }
         __syncthreads();
+    }
+    if (shared) {
+        // ---- the share that arrives last adds the partial outputs of all shares, in share order ----
+        const int j_item = (it - full) % tail;
+        unsigned int *const ticket = &tickets[xcd * slots + j_item];
+        __builtin_amdgcn_s_waitcnt(0x0f70);       // vmcnt(0): this wavefront's partial outputs have been acknowledged ...
+        __syncthreads();                          // ... and so have those of the other three
+        int *const s_last = reinterpret_cast<int *>(smem);
+        if (tid == 0)
+            *s_last = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(shares - 1);
+        __syncthreads();
+        const bool last = *s_last != 0;
+        __syncthreads();                          // (smem is written again by the next item)
+        if (last) {
+            // two shares (64 loads per thread) in flight at a time; the sums run over the shares in order
+            floatx2_w y2[4][8];
+#pragma unroll
+            for (int f = 0; f < 4; ++f)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) y2[f][j] = floatx2_w{0.0f, 0.0f};
+            const float *src0 = partial + (size_t)(xcd * slots + j_item) * FW_SHARE_FLOATS + tid * 2;
+            for (int z = 0; z < shares; z += 2) {
+                floatx2_w v[2][4][8];
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int f = 0; f < 4; ++f)
+#pragma unroll
+                        for (int j = 0; j < 8; ++j)
+                            v[h][f][j] = fw_ld_agent(src0 + (size_t)((z + h) * tail) * FW_SHARE_FLOATS + (f * 8 + j) * FW_T * 2);
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int f = 0; f < 4; ++f)
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) y2[f][j] += v[h][f][j];
+            }
+#pragma unroll
+            for (int f = 0; f < 4; ++f) {
+                const int k = k0 + 4 * irow + f;
+                if (tile_ok && k < g.K) {
+                    float *dst = ybase + (size_t)k * g.Ho * g.Wo;
+#pragma unroll
+                    for (int p = 0; p < 4; ++p)
+                        if (orow + p < g.Ho)
+                            __builtin_nontemporal_store(
+                                floatx4_w{y2[f][2 * p][0], y2[f][2 * p][1], y2[f][2 * p + 1][0], y2[f][2 * p + 1][1]},
+                                reinterpret_cast<floatx4_w *>(dst + (size_t)p * g.Wo));
+                }
+            }
+        }
     }
     }   // items
 }
@@ -312,26 +442,73 @@ bool fused_wide_eligible(const Geo &g)
            (unsigned long long)36 * g.Cp * g.Kp * 4ull < (1ull << 31);   // 32-bit byte offsets into U
 }
 
-hipError_t launch_fused_wide(const Geo &g, const float *D, const float *U, float *Y, hipStream_t s)
+// XCD groups: halve the filter blocks per group while their transformed filters (36 x Cp x 64 floats each) exceed
+// what an XCD's 4 MB L2 can keep next to the streams of input and output (measured at N = 64: reads from
+// beyond L2 fall from 427 to 325 MB for 128 -> 256 channels at 56 x 56, from 1291 to 1028 MB for 256 -> 256,
+// at equal run time).
+static int fw_groups(const Geo &g, int n_kb)
+{
+    int groups = 1;
+    while (groups < 8 && n_kb % (2 * groups) == 0 &&
+           (unsigned long long)(n_kb / groups) * 36 * g.Cp * FW_K * 4 > (5ull << 19))
+        groups *= 2;
+    return groups;
+}
+
+// How well the rounds of a launch are filled: items per workgroup / rounds the slowest XCD takes, a last round
+// costing 1 / shares + 0.2 rounds when shared, else 0.6 rounds up to half full (its workgroups alone on their
+// CUs) and a whole one beyond (a model of the measurements quoted in fused_preferred).
+double fused_wide_fill(const Geo &g)
+{
+    const int n_kb = (g.Kp + FW_K - 1) / FW_K;
+    const long long n_tb = (g.P + FW_P - 1) / FW_P;
+    if (n_tb * n_kb < FW_GRID || n_tb * n_kb > 0x7fffffffLL) return 0.0;
+    const int groups = fw_groups(g, n_kb), slots = FW_GRID / 8, nsteps = (g.C + FW_C - 1) / FW_C;
+    double worst = 0.0;
+    for (int xcd = 0; xcd < 8; ++xcd) {
+        int first, count;
+        fw_list(xcd, groups, n_kb, (int)n_tb, &first, &count);
+        const FwRounds r = fw_rounds(count, slots, nsteps, true);
+        double rounds = (double)(r.full / slots);
+        if (r.shares > 1)
+            rounds += 1.0 / r.shares + 0.2;
+        else if (r.full % slots != 0)
+            rounds += r.full % slots * 2 <= slots ? 0.6 : 1.0;
+        worst = rounds > worst ? rounds : worst;
+    }
+    return (double)(n_tb * n_kb) / FW_GRID / worst;
+}
+
+size_t fused_wide_part_bytes() { return FW_TICKET_BYTES + (size_t)FW_GRID * FW_SHARE_FLOATS * sizeof(float); }
+
+// Sets the arrival counters to zero (a kernel, not a memset: the launch may be recorded into a graph).
+__global__ void fused_wide_clear_kernel(unsigned int *tickets) { tickets[threadIdx.x] = 0u; }
+
+hipError_t launch_fused_wide(const Geo &g, const float *D, const float *U, float *Y, void *part, size_t part_bytes,
+                             hipStream_t s)
 {
     const int n_kb = (g.Kp + FW_K - 1) / FW_K;
     const int n_tb = (g.P + FW_P - 1) / FW_P;
     const long long items = (long long)n_tb * n_kb;
     if (items > 0x7fffffffLL) return hipErrorInvalidValue;
-    // XCD groups: halve the filter blocks per group while their transformed filters (36 x Cp x 64 floats each) exceed
-    // what an XCD's 4 MB L2 can keep next to the streams of input and output (measured at N = 64: reads from
-    // beyond L2 fall from 427 to 325 MB for 128 -> 256 channels at 56 x 56, from 1291 to 1028 MB for 256 -> 256,
-    // at equal run time)
-    int groups = 1;
-    while (groups < 8 && n_kb % (2 * groups) == 0 &&
-           (unsigned long long)(n_kb / groups) * 36 * g.Cp * FW_K * 4 > (5ull << 19))
-        groups *= 2;
+    const int groups = fw_groups(g, n_kb);
     // two workgroups per CU (what registers and LDS allow) on 256 CUs, in multiples of the 8 XCDs
-    const unsigned grid = (unsigned)(items >= 512 ? 512 : (items + 7) / 8 * 8);
+    const unsigned grid = (unsigned)(items >= FW_GRID ? FW_GRID : (items + 7) / 8 * 8);
+    // Shares need the full grid (their places in the workspace and the counters are numbered by it) and room for
+    // the counters and the partial outputs; otherwise, or where no XCD has a last round to share, whole items.
+    float *p = (float *)part;
+    bool any = false;
+    for (int xcd = 0; xcd < 8 && grid == FW_GRID; ++xcd) {
+        int first, count;
+        fw_list(xcd, groups, n_kb, (int)n_tb, &first, &count);
+        any = any || fw_rounds(count, FW_GRID / 8, (g.C + FW_C - 1) / FW_C, true).shares > 1;
+    }
+    if (!any || p == nullptr || part_bytes < fused_wide_part_bytes()) p = nullptr;
+    if (p != nullptr) fused_wide_clear_kernel<<<dim3(1), dim3(FW_GRID), 0, s>>>((unsigned int *)p);
     if (g.C % FW_C != 0)
-        fused_wide_kernel<true><<<dim3(grid), dim3(FW_T), 0, s>>>(D, U, Y, g, n_kb, n_tb, groups);
+        fused_wide_kernel<true><<<dim3(grid), dim3(FW_T), 0, s>>>(D, U, Y, g, n_kb, n_tb, groups, p);
     else
-        fused_wide_kernel<false><<<dim3(grid), dim3(FW_T), 0, s>>>(D, U, Y, g, n_kb, n_tb, groups);
+        fused_wide_kernel<false><<<dim3(grid), dim3(FW_T), 0, s>>>(D, U, Y, g, n_kb, n_tb, groups, p);
     return hipGetLastError();
 }
 

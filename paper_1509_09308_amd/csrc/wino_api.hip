@@ -316,7 +316,7 @@ static int run_layer(const Geo &g, int y_dt, const void *D, const void *G, const
         // fp32 with pad 1 and W % 4 == 0: the designs with two workgroups per CU (64 filters per workgroup where
         // there are that many); otherwise the general one
         if (fused_wide_eligible(g))
-            e = launch_fused_wide(g, (const float *)D, (const float *)U, (float *)Y, s);
+            e = launch_fused_wide(g, (const float *)D, (const float *)U, (float *)Y, Vw, vb + mb, s);
         else
             e = fused_lds_eligible(g) ? launch_fused_lds(g, (const float *)D, (const float *)U, (float *)Y, s)
                                       : launch_fused(g, D, U, Y, y_dt, s);

@@ -43,7 +43,11 @@ bool fused_f16_eligible(const Geo &g);
 bool fused_lds_eligible(const Geo &g);
 hipError_t launch_fused_lds(const Geo &g, const float *D, const float *U, float *Y, hipStream_t s);
 bool fused_wide_eligible(const Geo &g);
-hipError_t launch_fused_wide(const Geo &g, const float *D, const float *U, float *Y, hipStream_t s);
+// `part`: room for partial outputs (fused_wide_part_bytes(), 256-byte aligned), or null
+hipError_t launch_fused_wide(const Geo &g, const float *D, const float *U, float *Y, void *part, size_t part_bytes,
+                             hipStream_t s);
+size_t fused_wide_part_bytes();
+double fused_wide_fill(const Geo &g);      // 0 .. 1: how well the launch fills its rounds of resident workgroups
 hipError_t launch_fused_f16(const Geo &g, const void *D, const void *U, void *Y, int y_dt, hipStream_t s);
 bool fused_f2_eligible(const Geo &g);
 hipError_t launch_fused_f2(const Geo &g, const float *D, const float *G, float *Y, void *workspace,

@@ -298,6 +298,29 @@ def test_fused_path_matches_oracle(shape):
     print("fused %s rel err %.3e max abs err %.3e" % (shape, e, worst))
 
 
+@pytest.mark.parametrize("shape", [(2, 256, 96, 96, 512),    # 72 items per XCD: a last round of 8 items in 8 shares
+                                   (2, 344, 96, 96, 512),    # channels not a multiple of 16: 22 steps, 2 shares
+                                   (6, 256, 72, 72, 320)])   # lists of 77 and 71 items (4 and 8 shares), ragged last tile block
+def test_fused_path_shares_the_items_of_a_partly_filled_last_round(shape):
+    """Layers with at least 512 (tile block, filter block) items whose last round fills only part of the resident
+    workgroups: the channel steps of those items are shared between workgroups that hand partial outputs over
+    through the workspace.  Whole output against the oracle; a second call must reproduce the first bit for bit
+    (the partial outputs are added in share order, whichever share arrives last)."""
+    torch, w = require_gpu()
+    N, C, H, W, K = shape
+    D, G = synth.make_layer(N, C, H, W, K, seed=sum(shape) + 41)
+    ref = direct.conv2d_fwd(D, G, pad=1)
+    d, g = to_gpu(D), to_gpu(G)
+    ws = w.alloc_workspace(N, C, H, W, K, 1, 4)
+    ws.view(torch.float32).fill_(float("nan"))            # nothing may depend on what the workspace held
+    Y1 = w.wino_conv2d_fwd_ex(d, G=g, pad=1, m=4, flags=w.FLAG_FUSED, workspace=ws)
+    Y2 = w.wino_conv2d_fwd_ex(d, G=g, pad=1, m=4, flags=w.FLAG_FUSED, workspace=ws)
+    torch.cuda.synchronize()
+    e, worst = check_close(Y1.cpu().numpy(), ref, TOL[("f32", 4)], "fused with shares %s" % (shape,), 4)
+    assert torch.equal(Y1, Y2)
+    print("fused with shares %s rel err %.3e max abs err %.3e" % (shape, e, worst))
+
+
 def test_fused_path_exact_on_integers_and_equals_unfused_bookkeeping():
     """Integer data and filters scaled by 576: the only roundings are those of the 1/6-type
     constants, and every output position must be the right one (distinct values per pixel)."""

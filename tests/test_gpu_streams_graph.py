@@ -59,6 +59,30 @@ def test_one_launch_layers_on_overlapping_streams():
             check_close(Y.cpu().numpy(), ref, TOL[("f32", 2)], "stream %d" % i, 2)
 
 
+def test_shared_last_round_on_overlapping_streams():
+    """The one-kernel F(4x4,3x3) layer hands partial outputs and arrival counters over through the caller's
+    workspace: calls on different streams with workspaces of their own may overlap, and each must give the result
+    the same call gives alone, bit for bit."""
+    torch, w = require_gpu()
+    N, C, H, W, K = 2, 256, 96, 96, 512                     # a last round of 8 items per XCD, 8 shares each
+    D, G = synth.make_layer(N, C, H, W, K, seed=78)
+    d, g = to_gpu(D), to_gpu(G)
+    U = w.wino_filter_transform(g, 4)
+    alone = w.wino_conv2d_fwd_ex(d, U=U, K=K, pad=1, m=4, flags=w.FLAG_FUSED)
+    torch.cuda.synchronize()
+    check_close(alone.cpu().numpy(), direct.conv2d_fwd(D, G, pad=1), TOL[("f32", 4)], "shares, alone", 4)
+    streams = [torch.cuda.Stream() for _ in range(6)]
+    wss = [w.alloc_workspace(N, C, H, W, K, 1, 4) for _ in streams]
+    outs = [None] * len(streams)
+    for rep in range(3):
+        for i, st in enumerate(streams):
+            with torch.cuda.stream(st):
+                outs[i] = w.wino_conv2d_fwd_ex(d, U=U, K=K, pad=1, m=4, flags=w.FLAG_FUSED, workspace=wss[i])
+        torch.cuda.synchronize()
+        for i, Y in enumerate(outs):
+            assert torch.equal(Y, alone), "stream %d, round %d" % (i, rep)
+
+
 def test_captured_graph_replays_equal_eager():
     torch, w = require_gpu()
     layers = [synth.VGG16_LAYERS[i] for i in (1, 4, 8, 11)]

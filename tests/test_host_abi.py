@@ -180,7 +180,9 @@ def test_variant_query_host_only(L):
     # the VGG layers with few filters and many tiles go to the one-kernel path, the rest do not
     assert w.wino_conv2d_variant(64, 64, 224, 224, 64, 1, 4) == w.FLAG_FUSED
     assert w.wino_conv2d_variant(64, 128, 112, 112, 128, 1, 4) == w.FLAG_FUSED
-    assert w.wino_conv2d_variant(64, 512, 28, 28, 512, 1, 4) == w.FLAG_UNFUSED
+    assert w.wino_conv2d_variant(64, 512, 28, 28, 512, 1, 4) == w.FLAG_FUSED        # 256: where the rounds fill (3 + a shared one)
+    assert w.wino_conv2d_variant(32, 512, 28, 28, 512, 1, 4) == w.FLAG_UNFUSED      # ... two rounds for 1.5
+    assert w.wino_conv2d_variant(8, 512, 28, 28, 512, 1, 4) == w.FLAG_UNFUSED       # fewer items than workgroups
     assert w.wino_conv2d_variant(64, 128, 56, 56, 256, 1, 4) == w.FLAG_FUSED        # K C / (K + C) = 85
     assert w.wino_conv2d_variant(64, 256, 56, 56, 256, 1, 4) == w.FLAG_FUSED        # 128: 64 filters per workgroup win
     assert w.wino_conv2d_variant(32, 256, 56, 56, 256, 1, 4) == w.FLAG_FUSED
