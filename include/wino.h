@@ -96,7 +96,10 @@ size_t wino_filter_bytes(int K, int C, int m, int dt);           /* U */
 size_t wino_v_bytes(int C, long long P, int m, int dt);          /* V */
 size_t wino_m_bytes(int K, long long P, int m);                  /* M */
 /* Workspace wino_conv2d_fwd_ex needs: room for U, V and M of this problem (M several times over
- * when the library splits the channel reduction of a small problem across workgroups). */
+ * when the library splits the channel reduction of a small problem across workgroups).  The
+ * one-kernel paths keep only U there; the fp32 one may use the part behind U (32 MiB of it, where
+ * V and M leave that much) for partial outputs and arrival counters of workgroups that share an
+ * item, so calls that overlap on one GPU need workspaces of their own. */
 size_t wino_workspace_bytes(int N, int C, int H, int W, int K, int pad, int m, int dt);
 
 /* ---- the four stages of Algorithm 1, one entry point each ------------------------------- */
@@ -145,7 +148,8 @@ int wino_conv2d_fwd_noalloc(int N, int C, int H, int W, int K, int pad, int m, c
                             void *Y, void *stream);
 /* General form.  U may be NULL (then G is transformed into the workspace first) or the output
  * of wino_filter_transform_ex for the same (K, C, m, dt) (then G may be NULL).  Never
- * allocates.  `workspace` must hold wino_workspace_bytes() bytes. */
+ * allocates.  `workspace` must hold wino_workspace_bytes() bytes; its contents on entry do not
+ * matter and are unspecified on return. */
 int wino_conv2d_fwd_ex(int N, int C, int H, int W, int K, int pad, int m, int dt, int y_dt, const void *D,
                        const void *G, const void *U, void *Y, void *workspace, size_t workspace_bytes,
                        unsigned flags, void *stream);
