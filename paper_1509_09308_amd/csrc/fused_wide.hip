@@ -45,6 +45,7 @@ static_assert(FW_M_FLOATS <= 2 * FW_V_FLOATS, "the epilogue reuses the two tile 
 constexpr int FW_GRID = 512;                                        // resident workgroups: two per CU
 constexpr int FW_SHARE_FLOATS = FW_K * FW_P * 16;                   // partial outputs of one share
 constexpr int FW_TICKET_BYTES = FW_GRID * 4;                        // arrival counters in front of the partial outputs
+static_assert(FW_GRID == 512, "the filter transform in front clears 512 counters");
 
 // The items an XCD's workgroups walk (`count` of them, `slots` workgroups): `full` items in rounds that occupy
 // every workgroup, then `tail` items cut into `shares` shares of their `nsteps` channel steps each.  Items of
@@ -484,8 +485,25 @@ size_t fused_wide_part_bytes() { return FW_TICKET_BYTES + (size_t)FW_GRID * FW_S
 // Sets the arrival counters to zero (a kernel, not a memset: the launch may be recorded into a graph).
 __global__ void fused_wide_clear_kernel(unsigned int *tickets) { tickets[threadIdx.x] = 0u; }
 
+// Shares need the full grid (their places in the workspace and the counters are numbered by it) and room for the
+// counters and the partial outputs; otherwise, or where no XCD has a last round to share, whole items.
+bool fused_wide_shares(const Geo &g, const void *part, size_t part_bytes)
+{
+    const int n_kb = (g.Kp + FW_K - 1) / FW_K;
+    const long long n_tb = (g.P + FW_P - 1) / FW_P;
+    if (part == nullptr || part_bytes < fused_wide_part_bytes() || n_tb * n_kb < FW_GRID || n_tb * n_kb > 0x7fffffffLL)
+        return false;
+    const int groups = fw_groups(g, n_kb);
+    for (int xcd = 0; xcd < 8; ++xcd) {
+        int first, count;
+        fw_list(xcd, groups, n_kb, (int)n_tb, &first, &count);
+        if (fw_rounds(count, FW_GRID / 8, (g.C + FW_C - 1) / FW_C, true).shares > 1) return true;
+    }
+    return false;
+}
+
 hipError_t launch_fused_wide(const Geo &g, const float *D, const float *U, float *Y, void *part, size_t part_bytes,
-                             hipStream_t s)
+                             bool cleared, hipStream_t s)
 {
     const int n_kb = (g.Kp + FW_K - 1) / FW_K;
     const int n_tb = (g.P + FW_P - 1) / FW_P;
@@ -494,17 +512,8 @@ hipError_t launch_fused_wide(const Geo &g, const float *D, const float *U, float
     const int groups = fw_groups(g, n_kb);
     // two workgroups per CU (what registers and LDS allow) on 256 CUs, in multiples of the 8 XCDs
     const unsigned grid = (unsigned)(items >= FW_GRID ? FW_GRID : (items + 7) / 8 * 8);
-    // Shares need the full grid (their places in the workspace and the counters are numbered by it) and room for
-    // the counters and the partial outputs; otherwise, or where no XCD has a last round to share, whole items.
-    float *p = (float *)part;
-    bool any = false;
-    for (int xcd = 0; xcd < 8 && grid == FW_GRID; ++xcd) {
-        int first, count;
-        fw_list(xcd, groups, n_kb, (int)n_tb, &first, &count);
-        any = any || fw_rounds(count, FW_GRID / 8, (g.C + FW_C - 1) / FW_C, true).shares > 1;
-    }
-    if (!any || p == nullptr || part_bytes < fused_wide_part_bytes()) p = nullptr;
-    if (p != nullptr) fused_wide_clear_kernel<<<dim3(1), dim3(FW_GRID), 0, s>>>((unsigned int *)p);
+    float *p = fused_wide_shares(g, part, part_bytes) ? (float *)part : nullptr;
+    if (p != nullptr && !cleared) fused_wide_clear_kernel<<<dim3(1), dim3(FW_GRID), 0, s>>>((unsigned int *)p);
     if (g.C % FW_C != 0)
         fused_wide_kernel<true><<<dim3(grid), dim3(FW_T), 0, s>>>(D, U, Y, g, n_kb, n_tb, groups, p);
     else

@@ -301,13 +301,16 @@ static int run_layer(const Geo &g, int y_dt, const void *D, const void *G, const
     }
     if (flags == WINO_FLAG_AUTO && fused_y_ok(g, y_dt) && fused_preferred(g)) flags = WINO_FLAG_FUSED;
     bool v_done = false;
+    // the one-kernel fp32 layer keeps arrival counters behind U: the filter transform in front of it clears them
+    const bool wide = flags == WINO_FLAG_FUSED && fused_wide_eligible(g);
+    unsigned int *const counters = wide && U == nullptr && fused_wide_shares(g, Vw, vb + mb) ? (unsigned int *)Vw : nullptr;
     if (U == nullptr) {
         if (!bwd && flags != WINO_FLAG_FUSED && prep_eligible(g)) {
             // filters and input tiles are transformed by one launch
             e = launch_prep(g, G, Uw, D, Vw, s);
             v_done = true;
         } else {
-            e = bwd ? launch_filter_transform_bwd(g, G, Uw, s) : launch_filter_transform(g, G, Uw, s);
+            e = bwd ? launch_filter_transform_bwd(g, G, Uw, s, counters) : launch_filter_transform(g, G, Uw, s, counters);
         }
         if (e != hipSuccess) return hip_fail(e);
         U = Uw;
@@ -315,8 +318,8 @@ static int run_layer(const Geo &g, int y_dt, const void *D, const void *G, const
     if (flags == WINO_FLAG_FUSED) {
         // fp32 with pad 1 and W % 4 == 0: the designs with two workgroups per CU (64 filters per workgroup where
         // there are that many); otherwise the general one
-        if (fused_wide_eligible(g))
-            e = launch_fused_wide(g, (const float *)D, (const float *)U, (float *)Y, Vw, vb + mb, s);
+        if (wide)
+            e = launch_fused_wide(g, (const float *)D, (const float *)U, (float *)Y, Vw, vb + mb, counters != nullptr, s);
         else
             e = fused_lds_eligible(g) ? launch_fused_lds(g, (const float *)D, (const float *)U, (float *)Y, s)
                                       : launch_fused(g, D, U, Y, y_dt, s);
