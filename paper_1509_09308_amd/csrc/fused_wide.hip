@@ -326,11 +326,18 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
     for (int step = 0; step < nsteps; ++step) {
         const int buf = step & 1;
         const bool more = step + 1 < nsteps;
+        // A wavefront in its transform phase or epilogue shares its SIMD with one of the other workgroup, which
+        // as a rule is issuing MFMAs; at equal priority the two take turns, one vector instruction per MFMA (the
+        // 100 vector instructions of an epilogue piece take 3 500 cycles that way).  With the higher priority here
+        // the phase passes quickly and the wavefront is back at its own MFMAs sooner: 2-3 % per layer.
+        __builtin_amdgcn_s_setprio(3);
         transform(buf);
+        __builtin_amdgcn_s_setprio(0);
         fw_lds_barrier();
         load_taps(step0 + step + 1, more);
         multiply(buf, more);
     }
+    __builtin_amdgcn_s_setprio(2);
     __syncthreads();
 
     // ---- inverse transform: four pieces of 16 filters (piece f = filters k0 + 4 i + f, i = 0..15) ----------
@@ -378,6 +385,7 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
         }
         __syncthreads();
     }
+    __builtin_amdgcn_s_setprio(0);
     if (shared) {
         // ---- the share that arrives last adds the partial outputs of all shares, in share order ----
         const int j_item = (it - full) % tail;
