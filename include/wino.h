@@ -183,6 +183,14 @@ int wino_conv2d_bwd_filter(int N, int C, int H, int W, int K, int pad, int dt, c
  * the first two; WINO_FLAG_ONE_LAUNCH is answered for untransformed filters, G given); a negative
  * wino_status_t (e.g. -WINO_EUNSUPPORTED) if the call would be rejected. */
 int wino_conv2d_variant(int N, int C, int H, int W, int K, int pad, int m, int dt, int y_dt, unsigned flags);
+/* Host-side query: how the one-kernel fp32 F(4x4,3x3) layer (64 filters x 16 tiles per item, Section 6's
+ * fusion of the transforms into the multiply) deals its items to the GPU's 8 XCDs when the workspace has room for
+ * partial outputs.  out[4 x + 0..3] for XCD x: number of items, how many of them run in rounds that occupy all
+ * 64 resident workgroups of the XCD, how many are left for the last round, and the number of shares each of those
+ * is cut into (1: none; shares x items of the last round <= 64, and the shares divide the item's channel steps
+ * of 16 channels).  Returns the number of workgroups of the launch, or a negative wino_status_t
+ * (-WINO_EUNSUPPORTED where that kernel does not apply). */
+int wino_one_kernel_plan(int N, int C, int H, int W, int K, int pad, int m, int dt, int out[32]);
 /* Eq. (1) evaluated directly on the GPU: any R x S filter, stride and padding; for layers the
  * fast algorithm does not cover (e.g. the 3-channel first layer of Table 3).
  * D[N][C][H][W], G[K][C][R][S] -> Y[N][K][Ho][Wo] with Ho = (H + 2 pad - R) / stride + 1 (Wo alike); D, G and Y

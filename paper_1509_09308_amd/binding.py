@@ -61,6 +61,7 @@ def lib():
             "wino_conv2d_fwd_noalloc": (i, [i] * 7 + [p, p, p, p]),
             "wino_conv2d_fwd_ex": (i, [i] * 9 + [p, p, p, p, p, sz, u, p]),
             "wino_conv2d_variant": (i, [i] * 9 + [u]),
+            "wino_one_kernel_plan": (i, [i] * 8 + [ip]),
             "wino_filter_transform_bwd": (i, [i, i, i, i, p, p, p]),
             "wino_bwd_filter_workspace_bytes": (sz, [i] * 5),
             "wino_conv2d_bwd_filter": (i, [i] * 7 + [p, p, p, p, sz, p]),
@@ -79,7 +80,7 @@ EXPORTS = ["wino_status_string", "wino_last_hip_error", "wino_num_tiles", "wino_
            "wino_padded_dims", "wino_u_offset", "wino_v_offset", "wino_m_offset", "wino_filter_bytes",
            "wino_v_bytes", "wino_m_bytes", "wino_workspace_bytes", "wino_filter_transform",
            "wino_filter_transform_ex", "wino_input_transform", "wino_batched_gemm", "wino_gemm_launch_shape",
-           "wino_output_transform", "wino_conv2d_fwd", "wino_conv2d_fwd_noalloc", "wino_conv2d_fwd_ex", "wino_conv2d_variant", "wino_filter_transform_bwd", "wino_conv2d_bwd_data",
+           "wino_output_transform", "wino_conv2d_fwd", "wino_conv2d_fwd_noalloc", "wino_conv2d_fwd_ex", "wino_conv2d_variant", "wino_one_kernel_plan", "wino_filter_transform_bwd", "wino_conv2d_bwd_data",
            "wino_bwd_filter_workspace_bytes", "wino_conv2d_bwd_filter",
            "direct_conv2d_fwd",
            "wino_shutdown"]
@@ -357,6 +358,15 @@ def wino_conv2d_fwd_ex(D, G=None, U=None, pad=1, m=4, Y=None, y_dtype=None, work
                                     _ptr(workspace), workspace.numel() * workspace.element_size(), flags,
                                     _stream(stream)), "wino_conv2d_fwd_ex")
     return Y
+
+
+def wino_one_kernel_plan(N, C, H, W, K, pad=1, m=4, dt=WINO_F32):
+    """(workgroups of the launch, [(items, in full rounds, in the last round, shares)] per XCD) of the one-kernel fp32 layer."""
+    out = (ctypes.c_int * 32)()
+    grid = int(lib().wino_one_kernel_plan(N, C, H, W, K, pad, m, dt, out))
+    if grid < 0:
+        raise WinoError(-grid, "wino_one_kernel_plan")
+    return grid, [tuple(int(out[4 * x + j]) for j in range(4)) for x in range(8)]
 
 
 def wino_gemm_launch_shape(K, C, P, m, dt=WINO_F32):

@@ -510,6 +510,23 @@ bool fused_wide_shares(const Geo &g, const void *part, size_t part_bytes)
     return false;
 }
 
+int fused_wide_plan(const Geo &g, int out[32])
+{
+    const int n_kb = (g.Kp + FW_K - 1) / FW_K;
+    const long long n_tb = (g.P + FW_P - 1) / FW_P;
+    const long long items = n_tb * n_kb;
+    if (items > 0x7fffffffLL) return -1;
+    const int groups = fw_groups(g, n_kb);
+    const int grid = (int)(items >= FW_GRID ? FW_GRID : (items + 7) / 8 * 8);
+    for (int xcd = 0; xcd < 8; ++xcd) {
+        int first, count;
+        fw_list(xcd, groups, n_kb, (int)n_tb, &first, &count);
+        const FwRounds r = fw_rounds(count, grid / 8, (g.C + FW_C - 1) / FW_C, grid == FW_GRID);
+        out[4 * xcd] = count, out[4 * xcd + 1] = r.full, out[4 * xcd + 2] = r.tail, out[4 * xcd + 3] = r.shares;
+    }
+    return grid;
+}
+
 hipError_t launch_fused_wide(const Geo &g, const float *D, const float *U, float *Y, void *part, size_t part_bytes,
                              bool cleared, hipStream_t s)
 {

@@ -276,6 +276,17 @@ int wino_conv2d_variant(int N, int C, int H, int W, int K, int pad, int m, int d
     return WINO_FLAG_UNFUSED;
 }
 
+int wino_one_kernel_plan(int N, int C, int H, int W, int K, int pad, int m, int dt, int out[32])
+{
+    Geo g;
+    const int st = make_geo(N, C, H, W, K, pad, m, dt, &g);
+    if (st != WINO_OK) return -st;
+    if (out == nullptr) return -WINO_EINVAL;
+    if (!fused_eligible(g) || !fused_wide_eligible(g)) return -WINO_EUNSUPPORTED;
+    const int grid = fused_wide_plan(g, out);
+    return grid < 0 ? -WINO_EINVAL : grid;
+}
+
 // Shared driver of the forward layer and of the input gradient: `g` is the geometry the kernels see,
 // `bwd` selects the filter transform (plain, or rotated and transposed).
 static int run_layer(const Geo &g, int y_dt, const void *D, const void *G, const void *U, void *Y, void *workspace,

@@ -51,6 +51,7 @@ bool fused_wide_eligible(const Geo &g);
 hipError_t launch_fused_wide(const Geo &g, const float *D, const float *U, float *Y, void *part, size_t part_bytes,
                              bool cleared, hipStream_t s);
 bool fused_wide_shares(const Geo &g, const void *part, size_t part_bytes);
+int fused_wide_plan(const Geo &g, int out[32]);      // per XCD: items, in full rounds, in the last round, shares; returns the grid
 size_t fused_wide_part_bytes();
 double fused_wide_fill(const Geo &g);      // 0 .. 1: how well the launch fills its rounds of resident workgroups
 hipError_t launch_fused_f16(const Geo &g, const void *D, const void *U, void *Y, int y_dt, hipStream_t s);

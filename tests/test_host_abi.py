@@ -239,3 +239,53 @@ def test_bench_refuses_more_than_one_gpu():
     res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert res.returncode != 0
     assert "one GPU" in res.stderr and res.stdout.strip() == ""
+
+
+def test_one_kernel_plan_covers_every_item_once_and_shares_fit():
+    """The deal of (tile block, filter block) items to XCDs and rounds that the one-kernel fp32 layer's workgroups
+    follow (the kernel evaluates the same functions): every item belongs to exactly one XCD's list, a shared last
+    round fits the XCD's 64 workgroups, the shares divide the channel steps, and only long items are shared."""
+    import math
+    w = binding
+    rng = __import__("numpy").random.default_rng(5)
+    seen_shared = 0
+    cases = [(64, 256, 56, 56, 256), (64, 512, 28, 28, 512), (64, 256, 28, 28, 512), (64, 64, 224, 224, 64),
+             (64, 128, 112, 112, 128), (2, 256, 96, 96, 512), (6, 256, 72, 72, 320), (2, 344, 96, 96, 512),
+             (1, 64, 224, 224, 64), (8, 512, 28, 28, 512), (3, 40, 12, 20, 96)]
+    for _ in range(300):
+        cases.append((int(rng.integers(1, 200)), int(rng.integers(1, 700)), int(rng.integers(3, 80)),
+                      4 * int(rng.integers(1, 24)), int(rng.integers(33, 700))))
+    planned = 0
+    for N, C, H, W, K in cases:
+        try:
+            grid, plan = w.wino_one_kernel_plan(N, C, H, W, K)
+        except binding.WinoError as e:                      # inputs beyond the kernel's 32-bit offsets
+            assert e.status == w.WINO_EUNSUPPORTED and N * C * H * W * 4 > 2 ** 29, (N, C, H, W, K)
+            continue
+        planned += 1
+        P = w.wino_num_tiles(N, H, W, 1, 4)
+        Kp = w.wino_padded_dims(K, C, P, 4)[0]
+        items = ((P + 15) // 16) * ((Kp + 63) // 64)
+        nsteps = (C + 15) // 16
+        assert grid == (512 if items >= 512 else (items + 7) // 8 * 8), (N, C, H, W, K)
+        assert sum(p[0] for p in plan) == items, (N, C, H, W, K, plan)
+        for count, full, tail, shares in plan:
+            assert full + tail == count and full >= 0 and tail >= 0 and shares >= 1
+            if shares > 1:
+                seen_shared += 1
+                assert grid == 512 and full % 64 == 0 and 0 < tail and tail * shares <= 64
+                assert shares in (2, 4, 8) and nsteps % shares == 0 and nsteps >= 16
+                assert shares >= 4 or full == 0
+            else:
+                assert tail == 0
+    assert seen_shared > 20 and planned > 200
+    # the VGG layers this is made for: conv3.2 (8 items of the last round in 8 shares on every XCD), conv4.2 (4 in 8)
+    assert w.wino_one_kernel_plan(64, 256, 56, 56, 256)[1] == [(392, 384, 8, 8)] * 8
+    assert w.wino_one_kernel_plan(64, 512, 28, 28, 512)[1] == [(196, 192, 4, 8)] * 8
+    assert all(p[3] == 1 for p in w.wino_one_kernel_plan(64, 64, 224, 224, 64)[1])
+    L = binding.lib()
+    out = (ctypes.c_int * 32)()
+    assert L.wino_one_kernel_plan(2, 8, 8, 8, 8, 1, 2, 0, out) == -w.WINO_EUNSUPPORTED      # F(2x2)
+    assert L.wino_one_kernel_plan(2, 8, 8, 10, 8, 1, 4, 0, out) == -w.WINO_EUNSUPPORTED     # W % 4 != 0
+    assert L.wino_one_kernel_plan(2, 8, 8, 8, 8, 1, 4, 1, out) == -w.WINO_EUNSUPPORTED      # fp16 storage
+    assert L.wino_one_kernel_plan(0, 8, 8, 8, 8, 1, 4, 0, out) == -w.WINO_EINVAL
