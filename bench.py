@@ -41,8 +41,8 @@ PEAK = {"hbm_GBs": 8000.0, "mfma_f32_TFs": 157.3, "mfma_f16_TFs": 2500.0}
 # `bench.py --probe` (summaries under profiles/); keyed by (workload, kernel).  None until measured.
 MEASURED_TRAFFIC = {
     # profiles/vgg16_n64_fp32_hbm_traffic.md
-    ("vgg16_3x3_conv_stack_N64_f32", "gemm_f32_kernel<128, 64, 2, 2, 32>"): 231.8e6,    # 3 launches (algorithmic 222.3 MB)
-    ("vgg16_3x3_conv_stack_N64_f32", "fused_wide_kernel<false>"): 1145.7e6,     # 9 launches (algorithmic 544.5 MB)
+    ("vgg16_3x3_conv_stack_N64_f32", "fused_wide_kernel<4, false>"): 1147.9e6,     # 9 launches (algorithmic 544.5 MB)
+    ("vgg16_3x3_conv_stack_N64_f32", "fused_wide_kernel<2, false>"): 323.2e6,      # 3 launches (algorithmic 68.2 MB)
     # profiles/vgg16_n32_fp16_hbm_traffic.md (algorithmic: 328.7 MB resp. 183.5 MB per launch)
     ("vgg16_3x3_conv_stack_N32_f16", "fused_f16_kernel<false, 2, float>"): 355.9e6,
     ("vgg16_3x3_conv_stack_N32_f16", "gemm_f16_kernel<128, 128>"): 187.3e6,
@@ -198,7 +198,7 @@ def stage_plan(torch, w, L, ws, sets):
         if L.dt == w.WINO_F16:
             kernel = "fused_f16_kernel<%s, %d, float>" % (cpad, 2 if L.K > 32 else 1)
         elif L.K > 32:           # 64 filters per workgroup, 16 channels per step
-            kernel = "fused_wide_kernel<%s>" % ("false" if L.C % 16 == 0 else "true")
+            kernel = "fused_wide_kernel<%d, %s>" % (L.m, "false" if L.C % 16 == 0 else "true")
         else:
             kernel = "fused_lds_kernel<%s>" % cpad
     else:
@@ -636,6 +636,23 @@ def stack_leg(torch, w, args, N, dtype, policy, cfg_idx, steps, warmup, cold=Tru
     if not args.no_stages:
         stages = time_stages(torch, w, layers, ws, max(5, steps), cold=cold)
         out.update(summarize_stages(w, layers, stages, dtype, workload))
+        if "transform_roofline" not in out:
+            # The step runs every Winograd layer in one kernel: the four stages of Algorithm 1 as kernels of their own
+            # are measured beside it, on the last layer of each algorithm forced through them.
+            import copy
+            ref_layers = []
+            for m in sorted({L.m for L in layers if not L.direct}):
+                L = copy.copy([x for x in layers if not x.direct and x.m == m][-1])
+                L.variant = w.FLAG_UNFUSED
+                ref_layers.append(L)
+            ref = summarize_stages(w, ref_layers, time_stages(torch, w, ref_layers, ws, max(5, steps), cold=cold), dtype, workload)
+            out["four_stage_reference"] = {"layers": [L.name for L in ref_layers], "stages": ref["stages"], "kernels": ref["kernels"],
+                                           "note": "not part of the step: these layers forced through the four stages"}
+            if "transform_roofline" in ref:
+                tr = dict(ref["transform_roofline"])
+                tr["kernels"] = "input_transform + output_transform of %s forced through the four stages (the step runs none)" \
+                                % " and ".join("%s (m=%d)" % (L.name, L.m) for L in ref_layers)
+                out["transform_roofline"] = tr
     if baseline and not args.no_cpu_baseline:
         run_step(w, layers, ws)
         torch.cuda.synchronize()

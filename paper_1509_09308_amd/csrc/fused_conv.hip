@@ -389,7 +389,9 @@ __global__ __launch_bounds__(512) void fused_f4_kernel(const float *__restrict__
 bool fused_eligible(const Geo &g)
 {
     if (g.dt == WINO_F16) return fused_f16_eligible(g);
-    if (g.dt != WINO_F32 || g.m != 4) return false;
+    if (g.dt != WINO_F32) return false;
+    if (g.m == 2) return fused_wide_eligible(g);      // F(2x2): only the 64-filter design
+    if (g.m != 4) return false;
     // 32-bit byte offsets into D below the out-of-bounds marker
     const unsigned long long bytes = (unsigned long long)g.N * g.C * g.H * g.W * 4ull;
     return bytes < (1ull << 31) - 65536;
@@ -406,6 +408,15 @@ bool fused_preferred(const Geo &g)
     const long long blocks = (long long)((g.P + FP - 1) / FP) * ((g.K + FK - 1) / FK);
     if (g.dt == WINO_F16)   // same crossover as in fp32 (N = 32: 128 -> 256 channels 0.139 vs 0.155 ms, 256 -> 256 0.249 vs 0.197)
         return (long long)g.K * g.C <= 100LL * (g.K + g.C) && (long long)((g.P + 31) / 32) * ((g.K + 63) / 64) >= 256;
+    if (g.m == 2) {
+        // F(2x2,3x3) in one kernel (fused_wide.hip) against its four stages, whose V and M are 4 values per output:
+        // -58 % for 64 -> 64 channels at 224 x 224 (N = 32), -39 % for 128 -> 128 at 112 x 112, -22 % for 256 -> 256
+        // at 56 x 56, -6 % for 512 -> 512 at 28 x 28 (all N = 64); 512 -> 512 at 14 x 14: -5 % at N = 64, -2 % at
+        // N = 32, -11 % at N = 16 (392 items); 512 -> 512 at 28 x 28, N = 8 (784 items): -3 %.  Below some hundred
+        // items the launch does not fill the GPU.
+        const long long items = (long long)((g.P + 15) / 16) * ((g.Kp + 63) / 64);
+        return (long long)g.K * g.C <= 256LL * (g.K + g.C) && items >= 384;
+    }
     if (!fused_lds_eligible(g)) return g.K <= 128 && blocks >= 512;
     if ((long long)g.K * g.C <= 100LL * (g.K + g.C) && blocks >= 512) return true;
     // with 64 filters per workgroup (fused_wide.hip) the crossover moves up past 256 -> 256 channels (56 x 56: 0.59

@@ -37,13 +37,13 @@ namespace wino {
 typedef float floatx4_w __attribute__((ext_vector_type(4)));
 
 constexpr int FW_K = 64, FW_P = 16, FW_C = 16, FW_T = 256;          // filters, tiles, channels per step, threads
-constexpr int FW_V_FLOATS = 36 * FW_C * FW_P;                       // transformed tiles of a step (one buffer)
-constexpr int FW_M_FLOATS = 36 * 16 * 16;                           // one piece of M in the epilogue: [e][filter row][tile]
+constexpr int fw_v_floats(int m) { return (m + 2) * (m + 2) * FW_C * FW_P; }   // transformed tiles of a step (one buffer)
+constexpr int fw_m_floats(int m) { return (m + 2) * (m + 2) * 16 * 16; }       // one piece of M in the epilogue: [e][filter row][tile]
 constexpr unsigned FW_MAX_BYTES = 0x40000000u;                      // longest stretch of D one workgroup's buffer covers
 constexpr unsigned FW_ROW_OOB = 0x80000000u, FW_COL_OOB = 0x40000000u;   // offset markers of taps outside the image
-static_assert(FW_M_FLOATS <= 2 * FW_V_FLOATS, "the epilogue reuses the two tile buffers");
+static_assert(fw_m_floats(4) <= 2 * fw_v_floats(4) && fw_m_floats(2) <= 2 * fw_v_floats(2), "the epilogue reuses the two tile buffers");
 constexpr int FW_GRID = 512;                                        // resident workgroups: two per CU
-constexpr int FW_SHARE_FLOATS = FW_K * FW_P * 16;                   // partial outputs of one share
+constexpr int FW_SHARE_FLOATS = FW_K * FW_P * 16;                   // partial outputs of one share (F(4x4); a quarter of it used by F(2x2))
 constexpr int FW_TICKET_BYTES = FW_GRID * 4;                        // arrival counters in front of the partial outputs
 static_assert(FW_GRID == 512, "the filter transform in front clears 512 counters");
 
@@ -107,12 +107,33 @@ __device__ __forceinline__ void fw_lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// The M x M outputs of one (filter, tile) pair: whole rows of 16 (F(4x4)) or 8 bytes (F(2x2)), not kept in the caches;
+// `rows` = rows of the image left from the tile's first one.
+template <int M>
+__device__ __forceinline__ void fw_store_rows(float *dst, int Wo, int rows, const float (&y)[M][M])
+{
+#pragma unroll
+    for (int p = 0; p < M; ++p)
+        if (p < rows) {
+            if constexpr (M == 4)
+                __builtin_nontemporal_store(floatx4_w{y[p][0], y[p][1], y[p][2], y[p][3]},
+                                            reinterpret_cast<floatx4_w *>(dst + (size_t)p * Wo));
+            else
+                __builtin_nontemporal_store(floatx2_w{y[p][0], y[p][1]}, reinterpret_cast<floatx2_w *>(dst + (size_t)p * Wo));
+        }
+}
+
+// M: F(M x M, 3 x 3), 4 or 2 (the comments name the numbers of F(4x4): 6 x 6 tiles, 36 components, 9 per wavefront;
+// F(2x2) has 4 x 4, 16 and 4, its rows are 8-byte loads and stores).
 // CPAD: the channel count is not a multiple of 16, so the last step holds channel slots past the last channel.
-template <bool CPAD>
+template <int M, bool CPAD>
 __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__restrict__ D, const float *__restrict__ U,
                                                              float *__restrict__ Y, Geo g, int n_kb, int n_tb, int groups,
                                                              float *__restrict__ part)
 {
+    constexpr int A = M + 2, NE = A * A, EW = NE / 4;          // tile edge, components, components per wavefront
+    constexpr int FW_V_FLOATS = fw_v_floats(M);
+    typedef float mid_t __attribute__((ext_vector_type(M)));   // the M middle columns of a tile row
     __shared__ __attribute__((aligned(16))) float smem[2 * FW_V_FLOATS];
     const int tid = threadIdx.x;
 
@@ -156,7 +177,7 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
     float *ybase = Y;
     const int tiles_per_image = g.Th * g.Tw;
     const int img0 = b0 / tiles_per_image;                     // uniform
-    unsigned vo_m[6];                                          // byte offset of columns 1..4 of row p, channel slot cl, step 0
+    unsigned vo_m[A];                                          // byte offset of columns 1..4 of row p, channel slot cl, step 0
     // The outer columns (0 and 5) of a tile are column 4 of the tile to its left and column 1 of the tile to its
     // right.  The 16 tiles of the workgroup sit in the 16 lanes of a DPP row, so a lane takes them from its
     // neighbours' registers; only the first lane of a row lacks its left neighbour and the last lane its right one.
@@ -173,38 +194,40 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
         const int t2 = bb / g.Tw;
         const int tx = t2 % g.Th;
         const int i = t2 / g.Th;
-        const int x0 = 4 * tx - 1, y0 = 4 * ty - 1;
-        orow = 4 * tx;
-        ybase = Y + ((size_t)i * g.K * g.Ho + orow) * g.Wo + 4 * ty;
+        const int x0 = M * tx - 1, y0 = M * ty - 1;
+        orow = M * tx;
+        ybase = Y + ((size_t)i * g.K * g.Ho + orow) * g.Wo + M * ty;
         left_in = y0 >= 0;
-        right_in = y0 + 5 < g.W;
+        right_in = y0 + A - 1 < g.W;
         const unsigned plane0 = (unsigned)((i - img0) * g.C + cl) * (unsigned)(g.H * g.W);
 #pragma unroll
-        for (int p = 0; p < 6; ++p) {
+        for (int p = 0; p < A; ++p) {
             const int x = x0 + p;
             const bool rok = tile_ok && x >= 0 && x < g.H;
-            vo_m[p] = rok ? (plane0 + (unsigned)(x * g.W + y0 + 1)) * 4u : FW_ROW_OOB;   // column y0 + 1 = 4 ty
+            vo_m[p] = rok ? (plane0 + (unsigned)(x * g.W + y0 + 1)) * 4u : FW_ROW_OOB;   // column y0 + 1 = M ty
         }
         // Every lane forms the offsets of its own outer columns (marked where they lie outside the image); lane
         // 1 + p then takes the left one of tile row p from the first lane of its DPP row and lane 8 + p the right
         // one from the last lane.  A shift by n also reaches the lanes further on: the left chain runs with n
         // rising and the right chain with n falling, so that the value from the end lane is the last one a lane
         // receives.
-        const unsigned adj_l = left_in ? 0xfffffffcu /* -4 bytes */ : FW_COL_OOB, adj_r = right_in ? 16u : FW_COL_OOB;
+        const unsigned adj_l = left_in ? 0xfffffffcu /* -4 bytes */ : FW_COL_OOB, adj_r = right_in ? 4u * M : FW_COL_OOB;
         int from_first = (int)FW_COL_OOB, from_last = (int)FW_COL_OOB;
         from_first = __builtin_amdgcn_update_dpp(from_first, (int)(vo_m[0] + adj_l), 0x111, 0xf, 0xf, false);   // row_shr:1
         from_first = __builtin_amdgcn_update_dpp(from_first, (int)(vo_m[1] + adj_l), 0x112, 0xf, 0xf, false);
         from_first = __builtin_amdgcn_update_dpp(from_first, (int)(vo_m[2] + adj_l), 0x113, 0xf, 0xf, false);
         from_first = __builtin_amdgcn_update_dpp(from_first, (int)(vo_m[3] + adj_l), 0x114, 0xf, 0xf, false);
-        from_first = __builtin_amdgcn_update_dpp(from_first, (int)(vo_m[4] + adj_l), 0x115, 0xf, 0xf, false);
-        from_first = __builtin_amdgcn_update_dpp(from_first, (int)(vo_m[5] + adj_l), 0x116, 0xf, 0xf, false);
-        from_last = __builtin_amdgcn_update_dpp(from_last, (int)(vo_m[5] + adj_r), 0x102, 0xf, 0xf, false);     // row_shl:2
-        from_last = __builtin_amdgcn_update_dpp(from_last, (int)(vo_m[4] + adj_r), 0x103, 0xf, 0xf, false);
+        if constexpr (M == 4) {
+            from_first = __builtin_amdgcn_update_dpp(from_first, (int)(vo_m[A - 2] + adj_l), 0x115, 0xf, 0xf, false);
+            from_first = __builtin_amdgcn_update_dpp(from_first, (int)(vo_m[A - 1] + adj_l), 0x116, 0xf, 0xf, false);
+            from_last = __builtin_amdgcn_update_dpp(from_last, (int)(vo_m[A - 1] + adj_r), 0x102, 0xf, 0xf, false);     // row_shl:2
+            from_last = __builtin_amdgcn_update_dpp(from_last, (int)(vo_m[A - 2] + adj_r), 0x103, 0xf, 0xf, false);
+        }
         from_last = __builtin_amdgcn_update_dpp(from_last, (int)(vo_m[3] + adj_r), 0x104, 0xf, 0xf, false);
         from_last = __builtin_amdgcn_update_dpp(from_last, (int)(vo_m[2] + adj_r), 0x105, 0xf, 0xf, false);
         from_last = __builtin_amdgcn_update_dpp(from_last, (int)(vo_m[1] + adj_r), 0x106, 0xf, 0xf, false);
         from_last = __builtin_amdgcn_update_dpp(from_last, (int)(vo_m[0] + adj_r), 0x107, 0xf, 0xf, false);
-        edge_off = (tl >= 1 && tl <= 6) ? (unsigned)from_first : (tl >= 8 && tl <= 13) ? (unsigned)from_last : FW_COL_OOB;
+        edge_off = (tl >= 1 && tl <= A) ? (unsigned)from_first : (tl >= 8 && tl <= 7 + A) ? (unsigned)from_last : FW_COL_OOB;
     }
     const unsigned step_bytes = (unsigned)(FW_C * g.H * g.W) * 4u;
     const size_t image_floats = (size_t)g.C * g.H * g.W;
@@ -212,15 +235,15 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void *)(D + (size_t)img0 * image_floats), 0, (unsigned)(left < FW_MAX_BYTES ? left : FW_MAX_BYTES), 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrc_u =
-        __builtin_amdgcn_make_buffer_rsrc((void *)U, 0, (unsigned)((size_t)36 * g.Cp * g.Kp * 4), 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc((void *)U, 0, (unsigned)((size_t)NE * g.Cp * g.Kp * 4), 0x00020000);
 
     // ---- multiply-phase role -------------------------------------------------------------------
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int cg = wave;
     const int lj = lane & 15, lk = lane >> 4;
-    floatx4_w acc[9][4];
+    floatx4_w acc[EW][4];
 #pragma unroll
-    for (int e = 0; e < 9; ++e)
+    for (int e = 0; e < EW; ++e)
 #pragma unroll
         for (int f = 0; f < 4; ++f) acc[e][f] = floatx4_w{0.0f, 0.0f, 0.0f, 0.0f};
 
@@ -228,12 +251,15 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
     // filter block reaches past Kp the last four columns are read instead: rows of filters that are never stored.
     const unsigned uvo = (unsigned)(lk * g.Kp + min(k0 + 4 * lj, g.Kp - 4)) * 4u;
     const unsigned ue_bytes = (unsigned)(g.Cp * g.Kp) * 4u, usub_bytes = (unsigned)(4 * g.Kp) * 4u;
-    unsigned su = (unsigned)(cg * 9) * ue_bytes + (unsigned)(4 * step0) * usub_bytes;      // scalar offset of component 9 cg in the sub-step requested next
-    floatx4_w ua[9];
-    auto load_ua = [&](int e, unsigned vo) {
-        ua[e] = __builtin_bit_cast(floatx4_w, __builtin_amdgcn_raw_buffer_load_b128(rsrc_u, vo, su + e * ue_bytes, 0));
+    unsigned su = (unsigned)(cg * EW) * ue_bytes + (unsigned)(4 * step0) * usub_bytes;      // scalar offset of component 9 cg in the sub-step requested next
+    // KC sub-steps of filter operands are in flight: one for F(4x4) (nine components of MFMAs, 1152 cycles, ahead of
+    // their use), two for F(2x2), whose sub-step has only four components
+    constexpr int KC = M == 4 ? 1 : 2;
+    floatx4_w ua[KC * EW];
+    auto load_ua = [&](int slot, int e, unsigned vo) {
+        ua[slot] = __builtin_bit_cast(floatx4_w, __builtin_amdgcn_raw_buffer_load_b128(rsrc_u, vo, su + e * ue_bytes, 0));
     };
-    floatx4_w mid[6];
+    mid_t mid[A];
     float ed;
     // `valid` false: nothing is fetched (every offset is a marker).  The request is made all the same, so that the
     // number of loads in flight does not depend on the path taken (the compiler's wait counts take the minimum).
@@ -244,22 +270,25 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
         const unsigned off_mask = valid ? 0u : FW_ROW_OOB;
         const bool ch_ok = !CPAD || (step * FW_C + cl < g.C);
 #pragma unroll
-        for (int p = 0; p < 6; ++p) {
+        for (int p = 0; p < A; ++p) {
             const unsigned om = (ch_ok ? vo_m[p] : FW_ROW_OOB) | off_mask;
-            mid[p] = __builtin_bit_cast(floatx4_w, __builtin_amdgcn_raw_buffer_load_b128(rsrc, om, so, 0));
+            if constexpr (M == 4)
+                mid[p] = __builtin_bit_cast(mid_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, om, so, 0));
+            else
+                mid[p] = __builtin_bit_cast(mid_t, __builtin_amdgcn_raw_buffer_load_b64(rsrc, om, so, 0));
         }
         ed = __builtin_bit_cast(float,
                                 __builtin_amdgcn_raw_buffer_load_b32(rsrc, (ch_ok ? edge_off : FW_ROW_OOB) | off_mask, so, 0));
     };
     // this thread's tile: rows then columns (v = B^T (d B)), scatter to LDS buffer `buf` as [e][channel][tile]
     auto transform = [&](int buf) {
-        float t[6][6];
+        float t[A][A];
         // tile row p (a compile-time constant: it selects the DPP shifts)
         auto row = [&](auto pc) {
             constexpr int p = decltype(pc)::value;
             // column 4 of the lane below (row_shr:1), column 1 of the lane above (row_shl:1); the first and the last
             // lane of the row, which have no such neighbour, keep what lane 1 + p resp. 8 + p fetched for them
-            const float c1 = mid[p][0], c4 = mid[p][3];      // (a bit cast applied to a vector element would read element 0)
+            const float c1 = mid[p][0], c4 = mid[p][M - 1];  // (a bit cast applied to a vector element would read element 0)
             const int e_bits = __builtin_bit_cast(int, ed);
             // (lanes without a source lane read 0: only the first resp. the last lane's value is used)
             const int for_first = __builtin_amdgcn_mov_dpp(e_bits, 0x101 + p, 0xf, 0xf, true);   // row_shl:(1 + p)
@@ -268,23 +297,29 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
             const int r_bits = __builtin_amdgcn_update_dpp(for_last, __builtin_bit_cast(int, c1), 0x101, 0xf, 0xf, false);
             const float lv = left_in ? __builtin_bit_cast(float, l_bits) : 0.0f;
             const float rv = right_in ? __builtin_bit_cast(float, r_bits) : 0.0f;
-            const float d[6] = {lv, mid[p][0], mid[p][1], mid[p][2], mid[p][3], rv};
-            bt_mul<4>(d, t[p]);
+            float d[A];
+            d[0] = lv, d[A - 1] = rv;
+#pragma unroll
+            for (int q = 0; q < M; ++q) d[1 + q] = mid[p][q];
+            bt_mul<M>(d, t[p]);
         };
         row(std::integral_constant<int, 0>());
         row(std::integral_constant<int, 1>());
         row(std::integral_constant<int, 2>());
         row(std::integral_constant<int, 3>());
-        row(std::integral_constant<int, 4>());
-        row(std::integral_constant<int, 5>());
+        if constexpr (M == 4) {
+            row(std::integral_constant<int, A - 2>());
+            row(std::integral_constant<int, A - 1>());
+        }
         float *dst = smem + buf * FW_V_FLOATS + tid;       // cl * 16 + tl = tid
 #pragma unroll
-        for (int q = 0; q < 6; ++q) {
-            const float col[6] = {t[0][q], t[1][q], t[2][q], t[3][q], t[4][q], t[5][q]};
-            float o[6];
-            bt_mul<4>(col, o);
+        for (int q = 0; q < A; ++q) {
+            float col[A], o[A];
 #pragma unroll
-            for (int p = 0; p < 6; ++p) dst[(p * 6 + q) * (FW_C * FW_P)] = o[p];
+            for (int p = 0; p < A; ++p) col[p] = t[p][q];
+            bt_mul<M>(col, o);
+#pragma unroll
+            for (int p = 0; p < A; ++p) dst[(p * A + q) * (FW_C * FW_P)] = o[p];
         }
     };
     // nine components x four sub-steps x (64 filters x 16 tiles x 4 channels); B operand of lane (j, h) in
@@ -294,20 +329,20 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
         // transform phase); with no next step the request is made with an offset behind the buffer, which fetches
         // nothing, so that the number of loads in flight does not depend on the path taken
         const unsigned uvo_next = more ? uvo : 0x80000000u;
-        const float *vb = smem + buf * FW_V_FLOATS + cg * 9 * (FW_C * FW_P) + lane;
+        const float *vb = smem + buf * FW_V_FLOATS + cg * EW * (FW_C * FW_P) + lane;
         float bq[2];
         bq[0] = vb[0];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
 #pragma unroll
-            for (int e = 0; e < 9; ++e) {
-                const int n = t * 9 + e;
-                if (n + 1 < 36) bq[(n + 1) & 1] = vb[((n + 1) % 9) * (FW_C * FW_P) + ((n + 1) / 9) * 64];
+            for (int e = 0; e < EW; ++e) {
+                const int n = t * EW + e, slot = (t % KC) * EW + e;
+                if (n + 1 < 4 * EW) bq[(n + 1) & 1] = vb[((n + 1) % EW) * (FW_C * FW_P) + ((n + 1) / EW) * 64];
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int f = 0; f < 4; ++f)
-                    acc[e][f] = __builtin_amdgcn_mfma_f32_16x16x4f32(ua[e][f], bq[n & 1], acc[e][f], 0, 0, 0);
-                load_ua(e, t < 3 ? uvo : uvo_next);
+                    acc[e][f] = __builtin_amdgcn_mfma_f32_16x16x4f32(ua[slot][f], bq[n & 1], acc[e][f], 0, 0, 0);
+                load_ua(slot, e, t + KC < 4 ? uvo : uvo_next);      // the same component KC sub-steps on
                 __builtin_amdgcn_sched_barrier(0);
             }
             su += usub_bytes;
@@ -321,8 +356,11 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
     // the loop -- which the compiler derives from both ways into it -- would also end the filter requests' flight)
     __builtin_amdgcn_sched_barrier(0x38f);        // everything but memory requests may cross
 #pragma unroll
-    for (int e = 0; e < 9; ++e) load_ua(e, uvo);
-    su += usub_bytes;
+    for (int kc = 0; kc < KC; ++kc) {
+#pragma unroll
+        for (int e = 0; e < EW; ++e) load_ua(kc * EW + e, e, uvo);
+        su += usub_bytes;
+    }
     for (int step = 0; step < nsteps; ++step) {
         const int buf = step & 1;
         const bool more = step + 1 < nsteps;
@@ -341,6 +379,7 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
     __syncthreads();
 
     // ---- inverse transform: four pieces of 16 filters (piece f = filters k0 + 4 i + f, i = 0..15) ----------
+    constexpr int NJ = M * M / 2;              // pairs of outputs per (filter, tile)
     float *Ms = smem;
     const int irow = tid >> 4;                 // 0..15: filter row of the piece handled in the gather
     const int ot = tid & 15;                   // tile of the gather (same tile as in the transform phase)
@@ -348,39 +387,36 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
     for (int f = 0; f < 4; ++f) {
         // accumulator register rr of lane (lj, lk) is row 4 lk + rr, tile lj
 #pragma unroll
-        for (int e = 0; e < 9; ++e)
+        for (int e = 0; e < EW; ++e)
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) Ms[((cg * 9 + e) * 16 + fw_m_row(4 * lk + rr)) * 16 + lj] = acc[e][f][rr];
+            for (int rr = 0; rr < 4; ++rr) Ms[((cg * EW + e) * 16 + fw_m_row(4 * lk + rr)) * 16 + lj] = acc[e][f][rr];
         __syncthreads();
         const int k = k0 + 4 * irow + f;
         if (tile_ok && k < g.K) {
-            float m[6][6], tt[4][6], y[4][4];
+            float m[A][A], tt[M][A], y[M][M];
 #pragma unroll
-            for (int xi = 0; xi < 6; ++xi)
+            for (int xi = 0; xi < A; ++xi)
 #pragma unroll
-                for (int nu = 0; nu < 6; ++nu) m[xi][nu] = Ms[((xi * 6 + nu) * 16 + fw_m_row(irow)) * 16 + ot];
+                for (int nu = 0; nu < A; ++nu) m[xi][nu] = Ms[((xi * A + nu) * 16 + fw_m_row(irow)) * 16 + ot];
 #pragma unroll
-            for (int nu = 0; nu < 6; ++nu) {
-                const float col[6] = {m[0][nu], m[1][nu], m[2][nu], m[3][nu], m[4][nu], m[5][nu]};
-                float o[4];
-                at_mul<4>(col, o);
+            for (int nu = 0; nu < A; ++nu) {
+                float col[A], o[M];
 #pragma unroll
-                for (int p = 0; p < 4; ++p) tt[p][nu] = o[p];
+                for (int xi = 0; xi < A; ++xi) col[xi] = m[xi][nu];
+                at_mul<M>(col, o);
+#pragma unroll
+                for (int p = 0; p < M; ++p) tt[p][nu] = o[p];
             }
 #pragma unroll
-            for (int p = 0; p < 4; ++p) at_mul<4>(tt[p], y[p]);
+            for (int p = 0; p < M; ++p) at_mul<M>(tt[p], y[p]);
             if (!shared) {
-                float *dst = ybase + (size_t)k * g.Ho * g.Wo;
-#pragma unroll
-                for (int p = 0; p < 4; ++p)
-                    if (orow + p < g.Ho)
-                        __builtin_nontemporal_store(floatx4_w{y[p][0], y[p][1], y[p][2], y[p][3]},
-                                                    reinterpret_cast<floatx4_w *>(dst + (size_t)p * g.Wo));
+                fw_store_rows<M>(ybase + (size_t)k * g.Ho * g.Wo, g.Wo, g.Ho - orow, y);
             } else {
-                // partial outputs of this share: [piece f][half row j][thread] pairs of floats
-                float *dst = partial + (size_t)(xcd * slots + (it - full)) * FW_SHARE_FLOATS + (f * 8 * FW_T + tid) * 2;
+                // partial outputs of this share: [piece f][pair j of a row][thread] pairs of floats
+                float *dst = partial + (size_t)(xcd * slots + (it - full)) * FW_SHARE_FLOATS + (f * NJ * FW_T + tid) * 2;
 #pragma unroll
-                for (int j = 0; j < 8; ++j) fw_st_agent(dst + j * FW_T * 2, y[j >> 1][2 * (j & 1)], y[j >> 1][2 * (j & 1) + 1]);
+                for (int j = 0; j < NJ; ++j)
+                    fw_st_agent(dst + j * FW_T * 2, y[j / (M / 2)][2 * (j % (M / 2))], y[j / (M / 2)][2 * (j % (M / 2)) + 1]);
             }
         }
         __syncthreads();
@@ -399,40 +435,40 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
         const bool last = *s_last != 0;
         __syncthreads();                          // (smem is written again by the next item)
         if (last) {
-            // two shares (64 loads per thread) in flight at a time; the sums run over the shares in order
-            floatx2_w y2[4][8];
+            // two shares (64 loads per thread for F(4x4)) in flight at a time; the sums run over the shares in order
+            floatx2_w y2[4][NJ];
 #pragma unroll
             for (int f = 0; f < 4; ++f)
 #pragma unroll
-                for (int j = 0; j < 8; ++j) y2[f][j] = floatx2_w{0.0f, 0.0f};
+                for (int j = 0; j < NJ; ++j) y2[f][j] = floatx2_w{0.0f, 0.0f};
             const float *src0 = partial + (size_t)(xcd * slots + j_item) * FW_SHARE_FLOATS + tid * 2;
             for (int z = 0; z < shares; z += 2) {
-                floatx2_w v[2][4][8];
+                floatx2_w v[2][4][NJ];
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
 #pragma unroll
                     for (int f = 0; f < 4; ++f)
 #pragma unroll
-                        for (int j = 0; j < 8; ++j)
-                            v[h][f][j] = fw_ld_agent(src0 + (size_t)((z + h) * tail) * FW_SHARE_FLOATS + (f * 8 + j) * FW_T * 2);
+                        for (int j = 0; j < NJ; ++j)
+                            v[h][f][j] = fw_ld_agent(src0 + (size_t)((z + h) * tail) * FW_SHARE_FLOATS + (f * NJ + j) * FW_T * 2);
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
 #pragma unroll
                     for (int f = 0; f < 4; ++f)
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) y2[f][j] += v[h][f][j];
+                        for (int j = 0; j < NJ; ++j) y2[f][j] += v[h][f][j];
             }
 #pragma unroll
             for (int f = 0; f < 4; ++f) {
                 const int k = k0 + 4 * irow + f;
                 if (tile_ok && k < g.K) {
-                    float *dst = ybase + (size_t)k * g.Ho * g.Wo;
+                    float y[M][M];
 #pragma unroll
-                    for (int p = 0; p < 4; ++p)
-                        if (orow + p < g.Ho)
-                            __builtin_nontemporal_store(
-                                floatx4_w{y2[f][2 * p][0], y2[f][2 * p][1], y2[f][2 * p + 1][0], y2[f][2 * p + 1][1]},
-                                reinterpret_cast<floatx4_w *>(dst + (size_t)p * g.Wo));
+                    for (int j = 0; j < NJ; ++j) {
+                        y[j / (M / 2)][2 * (j % (M / 2))] = y2[f][j][0];
+                        y[j / (M / 2)][2 * (j % (M / 2)) + 1] = y2[f][j][1];
+                    }
+                    fw_store_rows<M>(ybase + (size_t)k * g.Ho * g.Wo, g.Wo, g.Ho - orow, y);
                 }
             }
         }
@@ -446,12 +482,12 @@ bool fused_wide_eligible(const Geo &g)
     const unsigned long long tiles = (unsigned long long)g.Th * g.Tw;
     const unsigned long long span = (FW_P + tiles - 2) / tiles + 1;
     const unsigned long long image_bytes = (unsigned long long)g.C * g.H * g.W * 4ull;
-    return g.dt == WINO_F32 && g.m == 4 && g.pad == 1 && g.W % 4 == 0 && g.Kp >= FW_K &&
+    return g.dt == WINO_F32 && (g.m == 4 || g.m == 2) && g.pad == 1 && g.W % g.m == 0 && g.Kp >= FW_K &&
            span * image_bytes + 65536 < FW_MAX_BYTES &&
-           (unsigned long long)36 * g.Cp * g.Kp * 4ull < (1ull << 31);   // 32-bit byte offsets into U
+           (unsigned long long)g.a2 * g.Cp * g.Kp * 4ull < (1ull << 31);   // 32-bit byte offsets into U
 }
 
-// XCD groups: halve the filter blocks per group while their transformed filters (36 x Cp x 64 floats each) exceed
+// XCD groups: halve the filter blocks per group while their transformed filters (alpha^2 x Cp x 64 floats each) exceed
 // what an XCD's 4 MB L2 can keep next to the streams of input and output (measured at N = 64: reads from
 // beyond L2 fall from 427 to 325 MB for 128 -> 256 channels at 56 x 56, from 1291 to 1028 MB for 256 -> 256,
 // at equal run time).
@@ -459,7 +495,7 @@ static int fw_groups(const Geo &g, int n_kb)
 {
     int groups = 1;
     while (groups < 8 && n_kb % (2 * groups) == 0 &&
-           (unsigned long long)(n_kb / groups) * 36 * g.Cp * FW_K * 4 > (5ull << 19))
+           (unsigned long long)(n_kb / groups) * g.a2 * g.Cp * FW_K * 4 > (5ull << 19))
         groups *= 2;
     return groups;
 }
@@ -539,10 +575,15 @@ hipError_t launch_fused_wide(const Geo &g, const float *D, const float *U, float
     const unsigned grid = (unsigned)(items >= FW_GRID ? FW_GRID : (items + 7) / 8 * 8);
     float *p = fused_wide_shares(g, part, part_bytes) ? (float *)part : nullptr;
     if (p != nullptr && !cleared) fused_wide_clear_kernel<<<dim3(1), dim3(FW_GRID), 0, s>>>((unsigned int *)p);
-    if (g.C % FW_C != 0)
-        fused_wide_kernel<true><<<dim3(grid), dim3(FW_T), 0, s>>>(D, U, Y, g, n_kb, n_tb, groups, p);
+    const bool cpad = g.C % FW_C != 0;
+    if (g.m == 4 && cpad)
+        fused_wide_kernel<4, true><<<dim3(grid), dim3(FW_T), 0, s>>>(D, U, Y, g, n_kb, n_tb, groups, p);
+    else if (g.m == 4)
+        fused_wide_kernel<4, false><<<dim3(grid), dim3(FW_T), 0, s>>>(D, U, Y, g, n_kb, n_tb, groups, p);
+    else if (cpad)
+        fused_wide_kernel<2, true><<<dim3(grid), dim3(FW_T), 0, s>>>(D, U, Y, g, n_kb, n_tb, groups, p);
     else
-        fused_wide_kernel<false><<<dim3(grid), dim3(FW_T), 0, s>>>(D, U, Y, g, n_kb, n_tb, groups, p);
+        fused_wide_kernel<2, false><<<dim3(grid), dim3(FW_T), 0, s>>>(D, U, Y, g, n_kb, n_tb, groups, p);
     return hipGetLastError();
 }
 

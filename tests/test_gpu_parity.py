@@ -321,6 +321,51 @@ def test_fused_path_shares_the_items_of_a_partly_filled_last_round(shape):
     print("fused with shares %s rel err %.3e max abs err %.3e" % (shape, e, worst))
 
 
+@pytest.mark.parametrize("shape", [(3, 40, 12, 20, 96), (2, 24, 8, 8, 200), (1, 130, 20, 36, 70), (5, 16, 4, 4, 64),
+                                   (2, 272, 16, 16, 256),
+                                   (2, 16, 10, 14, 64), (1, 20, 7, 6, 40), (1, 3, 5, 2, 33),     # widths that 4 does not divide
+                                   (3, 256, 40, 40, 512), (2, 256, 66, 66, 512)])              # a shared last round (4 shares)
+def test_fused_f2x2_path_matches_oracle(shape):
+    """F(2x2,3x3) in one kernel (the 64-filter design with 4 x 4 tiles: 16 components, 8-byte rows): whole output
+    against the oracle; the call repeated must give the same bits."""
+    torch, w = require_gpu()
+    N, C, H, W, K = shape
+    D, G = synth.make_layer(N, C, H, W, K, seed=sum(shape) + 42)
+    ref = direct.conv2d_fwd(D, G, pad=1)
+    d, g = to_gpu(D), to_gpu(G)
+    assert w.wino_conv2d_variant(N, C, H, W, K, 1, 2, flags=w.FLAG_FUSED) == w.FLAG_FUSED
+    ws = w.alloc_workspace(N, C, H, W, K, 1, 2)
+    ws.view(torch.float32).fill_(float("nan"))
+    Y1 = w.wino_conv2d_fwd_ex(d, G=g, pad=1, m=2, flags=w.FLAG_FUSED, workspace=ws)
+    Y2 = w.wino_conv2d_fwd_ex(d, U=w.wino_filter_transform(g, 2), K=K, pad=1, m=2, flags=w.FLAG_FUSED, workspace=ws)
+    torch.cuda.synchronize()
+    assert Y1.shape == ref.shape
+    e, worst = check_close(Y1.cpu().numpy(), ref, TOL[("f32", 2)], "fused F(2x2) %s" % (shape,), 2)
+    assert torch.equal(Y1, Y2)
+    print("fused F(2x2) %s rel err %.3e max abs err %.3e" % (shape, e, worst))
+
+
+def test_fused_f2x2_delta_filter_bitwise_and_full_size_sampled():
+    """With a centre-one filter every intermediate of F(2x2) is exact in fp32: the one-kernel path must return D bit
+    for bit (every tile, row and column in its place).  And conv5.x of the N=64 stack through this path (the shape it
+    is chosen for: 3 full rounds and a shared one), sampled against the oracle."""
+    torch, w = require_gpu()
+    N, C, H, W, K = 3, 72, 14, 22, 72
+    D = (np.arange(N * C * H * W, dtype=np.float32) % 65521).reshape(N, C, H, W)
+    np.random.default_rng(1).shuffle(D.reshape(-1))
+    G = np.zeros((K, C, 3, 3), dtype=np.float32)
+    G[np.arange(K), np.arange(C), 1, 1] = 1.0
+    Y = w.wino_conv2d_fwd_ex(to_gpu(D), G=to_gpu(G), pad=1, m=2, flags=w.FLAG_FUSED)
+    torch.cuda.synchronize()
+    assert np.array_equal(Y.cpu().numpy(), D)
+    name, C, HW, K = synth.VGG16_LAYERS[12]
+    N = 64
+    D, G = synth.make_layer(N, C, HW, HW, K, synth.layer_seed(4, 12))
+    Y = w.wino_conv2d_fwd_ex(to_gpu(D), G=to_gpu(G), pad=1, m=2, flags=w.FLAG_FUSED)
+    pts = synth.sample_points((N, K, HW, HW), 4000, seed=12, edge=2)
+    _sampled_check(torch, Y, D, G, pts, TOL[("f32", 2)], "%s N=64 F(2x2) in one kernel" % name, 2)
+
+
 def test_fused_path_exact_on_integers_and_equals_unfused_bookkeeping():
     """Integer data and filters scaled by 576: the only roundings are those of the 1/6-type
     constants, and every output position must be the right one (distinct values per pixel)."""

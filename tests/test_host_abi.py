@@ -190,7 +190,10 @@ def test_variant_query_host_only(L):
     assert w.wino_conv2d_variant(64, 256, 28, 28, 512, 1, 4) == w.FLAG_FUSED        # 171: still ahead
     assert w.wino_conv2d_variant(1, 64, 224, 224, 64, 1, 4) == w.FLAG_FUSED         # batch 1, 64 -> 64: 196 workgroups suffice
     assert w.wino_conv2d_variant(1, 128, 112, 112, 128, 1, 4) == w.FLAG_UNFUSED     # too few workgroups
-    assert w.wino_conv2d_variant(64, 64, 224, 224, 64, 1, 2) == w.FLAG_UNFUSED      # F(2x2) has no fused kernel
+    assert w.wino_conv2d_variant(64, 64, 224, 224, 64, 1, 2) == w.FLAG_FUSED        # F(2x2): the 64-filter design
+    assert w.wino_conv2d_variant(64, 512, 14, 14, 512, 1, 2) == w.FLAG_FUSED
+    assert w.wino_conv2d_variant(1, 512, 14, 14, 512, 1, 2) == w.FLAG_UNFUSED       # ... where it fills the GPU
+    assert w.wino_conv2d_variant(64, 32, 56, 56, 32, 1, 2) == w.FLAG_UNFUSED        # ... and has 33 filters or more
     assert w.wino_conv2d_variant(64, 64, 224, 224, 64, 1, 4, flags=w.FLAG_UNFUSED) == w.FLAG_UNFUSED
     assert w.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 4, flags=w.FLAG_FUSED) == w.FLAG_FUSED
     assert L.wino_conv2d_variant(2, 8, 8, 8, 8, 1, 2, 0, 0, w.FLAG_FUSED) == -w.WINO_EUNSUPPORTED
@@ -285,7 +288,9 @@ def test_one_kernel_plan_covers_every_item_once_and_shares_fit():
     assert all(p[3] == 1 for p in w.wino_one_kernel_plan(64, 64, 224, 224, 64)[1])
     L = binding.lib()
     out = (ctypes.c_int * 32)()
-    assert L.wino_one_kernel_plan(2, 8, 8, 8, 8, 1, 2, 0, out) == -w.WINO_EUNSUPPORTED      # F(2x2)
+    assert L.wino_one_kernel_plan(2, 8, 8, 8, 8, 1, 4, 0, out) == -w.WINO_EUNSUPPORTED      # fewer than 33 filters
+    assert L.wino_one_kernel_plan(2, 8, 8, 8, 40, 0, 4, 0, out) == -w.WINO_EUNSUPPORTED     # pad 0
+    assert w.wino_one_kernel_plan(64, 512, 14, 14, 512, 1, 2)[1] == [(196, 192, 4, 8)] * 8  # F(2x2): conv5.x
     assert L.wino_one_kernel_plan(2, 8, 8, 10, 8, 1, 4, 0, out) == -w.WINO_EUNSUPPORTED     # W % 4 != 0
     assert L.wino_one_kernel_plan(2, 8, 8, 8, 8, 1, 4, 1, out) == -w.WINO_EUNSUPPORTED      # fp16 storage
     assert L.wino_one_kernel_plan(0, 8, 8, 8, 8, 1, 4, 0, out) == -w.WINO_EINVAL
