@@ -1,4 +1,5 @@
-// Loops 2-4 of Algorithm 1 (Lavin & Gray) in one kernel, fp32 F(4x4,3x3), for layers with more than 32 filters:
+// Loops 2-4 of Algorithm 1 (Lavin & Gray) in one kernel, fp32 F(4x4,3x3) and F(2x2,3x3) (the algorithm of the
+// paper's own fused kernel, Section 6), for layers with more than 32 filters.  Described for F(4x4,3x3):
 // the design of fused_lds.hip with twice the filters per transformed tile.  On this chip fp32 MFMAs and ordinary
 // vector instructions of one SIMD share an issue slot, so the arithmetic of the data transform is paid in MFMA
 // time; it is needed once per (tile, channel) and workgroup, whatever the number of filters the workgroup
