@@ -97,7 +97,7 @@ size_t wino_v_bytes(int C, long long P, int m, int dt);          /* V */
 size_t wino_m_bytes(int K, long long P, int m);                  /* M */
 /* Workspace wino_conv2d_fwd_ex needs: room for U, V and M of this problem (M several times over
  * when the library splits the channel reduction of a small problem across workgroups).  The
- * one-kernel paths keep only U there; the fp32 one may use the part behind U (32 MiB of it, where
+ * one-kernel paths keep only U there; the fp32 one may use the part behind U (up to 32 MiB of it, where
  * V and M leave that much) for partial outputs and arrival counters of workgroups that share an
  * item, so calls that overlap on one GPU need workspaces of their own. */
 size_t wino_workspace_bytes(int N, int C, int H, int W, int K, int pad, int m, int dt);
@@ -185,11 +185,11 @@ int wino_conv2d_bwd_filter(int N, int C, int H, int W, int K, int pad, int dt, c
 int wino_conv2d_variant(int N, int C, int H, int W, int K, int pad, int m, int dt, int y_dt, unsigned flags);
 /* Host-side query: how the one-kernel fp32 F(4x4,3x3) layer (64 filters x 16 tiles per item, Section 6's
  * fusion of the transforms into the multiply) deals its items to the GPU's 8 XCDs when the workspace has room for
- * partial outputs.  out[4 x + 0..3] for XCD x: number of items, how many of them run in rounds that occupy all
- * 64 resident workgroups of the XCD, how many are left for the last round, and the number of shares each of those
- * is cut into (1: none; shares x items of the last round <= 64, and the shares divide the item's channel steps
- * of 16 channels).  Returns the number of workgroups of the launch, or a negative wino_status_t
- * (-WINO_EUNSUPPORTED where that kernel does not apply). */
+ * partial outputs (m = 4 or 2).  out[4 x + 0..3] for XCD x: number of items, how many of them run in rounds that
+ * occupy all resident workgroups of the XCD (64 for m = 4, 96 for m = 2), how many are left for the last round,
+ * and the number of shares each of those is cut into (1: none; shares x items of the last round <= the resident
+ * workgroups, and the shares divide the item's channel steps of 16 channels).  Returns the number of workgroups
+ * of the launch, or a negative wino_status_t (-WINO_EUNSUPPORTED where that kernel does not apply). */
 int wino_one_kernel_plan(int N, int C, int H, int W, int K, int pad, int m, int dt, int out[32]);
 /* Eq. (1) evaluated directly on the GPU: any R x S filter, stride and padding; for layers the
  * fast algorithm does not cover (e.g. the 3-channel first layer of Table 3).

@@ -6,22 +6,22 @@
 
 namespace wino {
 
-// Side job of the first block: 512 words set to zero for the kernel that follows on the stream (the arrival
+// Side job of the first block: 1024 words set to zero for the kernel that follows on the stream (the arrival
 // counters of the one-kernel layer, which would otherwise need a launch of their own); null: nothing.
-__device__ __forceinline__ void ft_zero512(unsigned int *zero512)
+__device__ __forceinline__ void ft_zero1024(unsigned int *zero1024)
 {
-    if (zero512 != nullptr && blockIdx.x == 0 && blockIdx.y == 0) {
-        zero512[threadIdx.x] = 0u;
-        zero512[threadIdx.x + 256] = 0u;
+    if (zero1024 != nullptr && blockIdx.x == 0 && blockIdx.y == 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) zero1024[threadIdx.x + 256 * i] = 0u;
     }
 }
 
 template <int M, typename T>
 __global__ __launch_bounds__(256) void filter_transform_kernel(const T *__restrict__ G, T *__restrict__ U, int K,
-                                                               int C, int Kp, int Cp, unsigned int *zero512)
+                                                               int C, int Kp, int Cp, unsigned int *zero1024)
 {
     __shared__ float gs[FT_LDS];
-    ft_zero512(zero512);
+    ft_zero1024(zero1024);
     filter_transform_block<M, T>(G, U, K, C, Kp, Cp, blockIdx.x, blockIdx.y, gs);
 }
 
@@ -41,10 +41,10 @@ __global__ __launch_bounds__(256) void filter_transform_f16_kernel(const __half 
 // g~[u][v] = g_{k,c}[2-u][2-v].  One thread per (k', c'), k' fastest.
 template <int M, typename T>
 __global__ __launch_bounds__(256) void filter_transform_bwd_kernel(const T *__restrict__ G, T *__restrict__ U, int K,
-                                                                   int C, int Kp2, int Cp2, unsigned int *zero512)
+                                                                   int C, int Kp2, int Cp2, unsigned int *zero1024)
 {
     constexpr int A = M + 2;
-    ft_zero512(zero512);
+    ft_zero1024(zero1024);
     const int k2 = blockIdx.x * 64 + threadIdx.x % 64;   // = c of G
     const int c2 = blockIdx.y * 4 + threadIdx.x / 64;    // = k of G
     if (k2 >= Kp2 || c2 >= Cp2) return;
@@ -77,37 +77,37 @@ __global__ __launch_bounds__(256) void filter_transform_bwd_kernel(const T *__re
 }
 
 // `g` describes the swapped layer (g.K = channels of the forward layer, g.C = its filters).
-hipError_t launch_filter_transform_bwd(const Geo &g, const void *G, void *U, hipStream_t s, unsigned int *zero512)
+hipError_t launch_filter_transform_bwd(const Geo &g, const void *G, void *U, hipStream_t s, unsigned int *zero1024)
 {
     dim3 grid((g.Kp + 63) / 64, (g.Cp + 3) / 4), block(256);
     const int K = g.C, C = g.K;   // extents of G[K][C][3][3]
     if (g.dt == WINO_F32) {
         if (g.m == 2)
-            filter_transform_bwd_kernel<2, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, K, C, g.Kp, g.Cp, zero512);
+            filter_transform_bwd_kernel<2, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, K, C, g.Kp, g.Cp, zero1024);
         else if (g.m == 4)
-            filter_transform_bwd_kernel<4, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, K, C, g.Kp, g.Cp, zero512);
+            filter_transform_bwd_kernel<4, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, K, C, g.Kp, g.Cp, zero1024);
         else
-            filter_transform_bwd_kernel<6, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, K, C, g.Kp, g.Cp, zero512);
+            filter_transform_bwd_kernel<6, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, K, C, g.Kp, g.Cp, zero1024);
     } else {
         if (g.m == 2)
-            filter_transform_bwd_kernel<2, __half><<<grid, block, 0, s>>>((const __half *)G, (__half *)U, K, C, g.Kp, g.Cp, zero512);
+            filter_transform_bwd_kernel<2, __half><<<grid, block, 0, s>>>((const __half *)G, (__half *)U, K, C, g.Kp, g.Cp, zero1024);
         else
-            filter_transform_bwd_kernel<4, __half><<<grid, block, 0, s>>>((const __half *)G, (__half *)U, K, C, g.Kp, g.Cp, zero512);
+            filter_transform_bwd_kernel<4, __half><<<grid, block, 0, s>>>((const __half *)G, (__half *)U, K, C, g.Kp, g.Cp, zero1024);
     }
     return hipGetLastError();
 }
 
-hipError_t launch_filter_transform(const Geo &g, const void *G, void *U, hipStream_t s, unsigned int *zero512)
+hipError_t launch_filter_transform(const Geo &g, const void *G, void *U, hipStream_t s, unsigned int *zero1024)
 {
-    if (g.dt != WINO_F32 && zero512 != nullptr) return hipErrorInvalidValue;
+    if (g.dt != WINO_F32 && zero1024 != nullptr) return hipErrorInvalidValue;
     dim3 grid((g.Kp + 63) / 64, (g.Cp + 3) / 4), block(256);
     if (g.dt == WINO_F32) {
         if (g.m == 2)
-            filter_transform_kernel<2, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, g.K, g.C, g.Kp, g.Cp, zero512);
+            filter_transform_kernel<2, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, g.K, g.C, g.Kp, g.Cp, zero1024);
         else if (g.m == 4)
-            filter_transform_kernel<4, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, g.K, g.C, g.Kp, g.Cp, zero512);
+            filter_transform_kernel<4, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, g.K, g.C, g.Kp, g.Cp, zero1024);
         else
-            filter_transform_kernel<6, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, g.K, g.C, g.Kp, g.Cp, zero512);
+            filter_transform_kernel<6, float><<<grid, block, 0, s>>>((const float *)G, (float *)U, g.K, g.C, g.Kp, g.Cp, zero1024);
     } else {
         dim3 gridh((g.Kp + 63) / 64, g.Cp / 8);
         if (g.m == 2)

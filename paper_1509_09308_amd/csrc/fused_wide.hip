@@ -43,10 +43,13 @@ constexpr int fw_m_floats(int m) { return (m + 2) * (m + 2) * 16 * 16; }       /
 constexpr unsigned FW_MAX_BYTES = 0x40000000u;                      // longest stretch of D one workgroup's buffer covers
 constexpr unsigned FW_ROW_OOB = 0x80000000u, FW_COL_OOB = 0x40000000u;   // offset markers of taps outside the image
 static_assert(fw_m_floats(4) <= 2 * fw_v_floats(4) && fw_m_floats(2) <= 2 * fw_v_floats(2), "the epilogue reuses the two tile buffers");
-constexpr int FW_GRID = 512;                                        // resident workgroups: two per CU
-constexpr int FW_SHARE_FLOATS = FW_K * FW_P * 16;                   // partial outputs of one share (F(4x4); a quarter of it used by F(2x2))
-constexpr int FW_TICKET_BYTES = FW_GRID * 4;                        // arrival counters in front of the partial outputs
-static_assert(FW_GRID == 512, "the filter transform in front clears 512 counters");
+// Resident workgroups: registers and LDS allow two per CU for F(4x4) and three for F(2x2) (145 registers, 32 KB).
+constexpr int fw_per_cu(int m) { return m == 4 ? 2 : 3; }
+constexpr int fw_grid(int m) { return 256 * fw_per_cu(m); }
+constexpr int fw_share_floats(int m) { return FW_K * FW_P * m * m; }       // partial outputs of one share
+constexpr int FW_TICKETS = 1024;                                    // arrival counters in front of the partial outputs
+constexpr int FW_TICKET_BYTES = FW_TICKETS * 4;
+static_assert(fw_grid(4) <= FW_TICKETS && fw_grid(2) <= FW_TICKETS, "one counter per resident workgroup at most");
 
 // The items an XCD's workgroups walk (`count` of them, `slots` workgroups): `full` items in rounds that occupy
 // every workgroup, then `tail` items cut into `shares` shares of their `nsteps` channel steps each.  Items of
@@ -128,7 +131,7 @@ __device__ __forceinline__ void fw_store_rows(float *dst, int Wo, int rows, cons
 // F(2x2) has 4 x 4, 16 and 4, its rows are 8-byte loads and stores).
 // CPAD: the channel count is not a multiple of 16, so the last step holds channel slots past the last channel.
 template <int M, bool CPAD>
-__global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__restrict__ D, const float *__restrict__ U,
+__global__ __launch_bounds__(FW_T, fw_per_cu(M)) void fused_wide_kernel(const float *__restrict__ D, const float *__restrict__ U,
                                                              float *__restrict__ Y, Geo g, int n_kb, int n_tb, int groups,
                                                              float *__restrict__ part)
 {
@@ -414,7 +417,7 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
                 fw_store_rows<M>(ybase + (size_t)k * g.Ho * g.Wo, g.Wo, g.Ho - orow, y);
             } else {
                 // partial outputs of this share: [piece f][pair j of a row][thread] pairs of floats
-                float *dst = partial + (size_t)(xcd * slots + (it - full)) * FW_SHARE_FLOATS + (f * NJ * FW_T + tid) * 2;
+                float *dst = partial + (size_t)(xcd * slots + (it - full)) * fw_share_floats(M) + (f * NJ * FW_T + tid) * 2;
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
                     fw_st_agent(dst + j * FW_T * 2, y[j / (M / 2)][2 * (j % (M / 2))], y[j / (M / 2)][2 * (j % (M / 2)) + 1]);
@@ -442,7 +445,7 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
             for (int f = 0; f < 4; ++f)
 #pragma unroll
                 for (int j = 0; j < NJ; ++j) y2[f][j] = floatx2_w{0.0f, 0.0f};
-            const float *src0 = partial + (size_t)(xcd * slots + j_item) * FW_SHARE_FLOATS + tid * 2;
+            const float *src0 = partial + (size_t)(xcd * slots + j_item) * fw_share_floats(M) + tid * 2;
             for (int z = 0; z < shares; z += 2) {
                 floatx2_w v[2][4][NJ];
 #pragma unroll
@@ -451,7 +454,7 @@ __global__ __launch_bounds__(FW_T, 2) void fused_wide_kernel(const float *__rest
                     for (int f = 0; f < 4; ++f)
 #pragma unroll
                         for (int j = 0; j < NJ; ++j)
-                            v[h][f][j] = fw_ld_agent(src0 + (size_t)((z + h) * tail) * FW_SHARE_FLOATS + (f * NJ + j) * FW_T * 2);
+                            v[h][f][j] = fw_ld_agent(src0 + (size_t)((z + h) * tail) * fw_share_floats(M) + (f * NJ + j) * FW_T * 2);
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -508,8 +511,9 @@ double fused_wide_fill(const Geo &g)
 {
     const int n_kb = (g.Kp + FW_K - 1) / FW_K;
     const long long n_tb = (g.P + FW_P - 1) / FW_P;
-    if (n_tb * n_kb < FW_GRID || n_tb * n_kb > 0x7fffffffLL) return 0.0;
-    const int groups = fw_groups(g, n_kb), slots = FW_GRID / 8, nsteps = (g.C + FW_C - 1) / FW_C;
+    const int full_grid = fw_grid(g.m);
+    if (n_tb * n_kb < full_grid || n_tb * n_kb > 0x7fffffffLL) return 0.0;
+    const int groups = fw_groups(g, n_kb), slots = full_grid / 8, nsteps = (g.C + FW_C - 1) / FW_C;
     double worst = 0.0;
     for (int xcd = 0; xcd < 8; ++xcd) {
         int first, count;
@@ -522,10 +526,13 @@ double fused_wide_fill(const Geo &g)
             rounds += r.full % slots * 2 <= slots ? 0.6 : 1.0;
         worst = rounds > worst ? rounds : worst;
     }
-    return (double)(n_tb * n_kb) / FW_GRID / worst;
+    return (double)(n_tb * n_kb) / full_grid / worst;
 }
 
-size_t fused_wide_part_bytes() { return FW_TICKET_BYTES + (size_t)FW_GRID * FW_SHARE_FLOATS * sizeof(float); }
+size_t fused_wide_part_bytes(const Geo &g)
+{
+    return FW_TICKET_BYTES + (size_t)fw_grid(g.m) * fw_share_floats(g.m) * sizeof(float);
+}
 
 // Sets the arrival counters to zero (a kernel, not a memset: the launch may be recorded into a graph).
 __global__ void fused_wide_clear_kernel(unsigned int *tickets) { tickets[threadIdx.x] = 0u; }
@@ -536,13 +543,13 @@ bool fused_wide_shares(const Geo &g, const void *part, size_t part_bytes)
 {
     const int n_kb = (g.Kp + FW_K - 1) / FW_K;
     const long long n_tb = (g.P + FW_P - 1) / FW_P;
-    if (part == nullptr || part_bytes < fused_wide_part_bytes() || n_tb * n_kb < FW_GRID || n_tb * n_kb > 0x7fffffffLL)
+    if (part == nullptr || part_bytes < fused_wide_part_bytes(g) || n_tb * n_kb < fw_grid(g.m) || n_tb * n_kb > 0x7fffffffLL)
         return false;
     const int groups = fw_groups(g, n_kb);
     for (int xcd = 0; xcd < 8; ++xcd) {
         int first, count;
         fw_list(xcd, groups, n_kb, (int)n_tb, &first, &count);
-        if (fw_rounds(count, FW_GRID / 8, (g.C + FW_C - 1) / FW_C, true).shares > 1) return true;
+        if (fw_rounds(count, fw_grid(g.m) / 8, (g.C + FW_C - 1) / FW_C, true).shares > 1) return true;
     }
     return false;
 }
@@ -554,11 +561,11 @@ int fused_wide_plan(const Geo &g, int out[32])
     const long long items = n_tb * n_kb;
     if (items > 0x7fffffffLL) return -1;
     const int groups = fw_groups(g, n_kb);
-    const int grid = (int)(items >= FW_GRID ? FW_GRID : (items + 7) / 8 * 8);
+    const int grid = (int)(items >= fw_grid(g.m) ? fw_grid(g.m) : (items + 7) / 8 * 8);
     for (int xcd = 0; xcd < 8; ++xcd) {
         int first, count;
         fw_list(xcd, groups, n_kb, (int)n_tb, &first, &count);
-        const FwRounds r = fw_rounds(count, grid / 8, (g.C + FW_C - 1) / FW_C, grid == FW_GRID);
+        const FwRounds r = fw_rounds(count, grid / 8, (g.C + FW_C - 1) / FW_C, grid == fw_grid(g.m));
         out[4 * xcd] = count, out[4 * xcd + 1] = r.full, out[4 * xcd + 2] = r.tail, out[4 * xcd + 3] = r.shares;
     }
     return grid;
@@ -572,10 +579,10 @@ hipError_t launch_fused_wide(const Geo &g, const float *D, const float *U, float
     const long long items = (long long)n_tb * n_kb;
     if (items > 0x7fffffffLL) return hipErrorInvalidValue;
     const int groups = fw_groups(g, n_kb);
-    // two workgroups per CU (what registers and LDS allow) on 256 CUs, in multiples of the 8 XCDs
-    const unsigned grid = (unsigned)(items >= FW_GRID ? FW_GRID : (items + 7) / 8 * 8);
+    // as many workgroups as stay resident on 256 CUs, in multiples of the 8 XCDs
+    const unsigned grid = (unsigned)(items >= fw_grid(g.m) ? fw_grid(g.m) : (items + 7) / 8 * 8);
     float *p = fused_wide_shares(g, part, part_bytes) ? (float *)part : nullptr;
-    if (p != nullptr && !cleared) fused_wide_clear_kernel<<<dim3(1), dim3(FW_GRID), 0, s>>>((unsigned int *)p);
+    if (p != nullptr && !cleared) fused_wide_clear_kernel<<<dim3(1), dim3(FW_TICKETS), 0, s>>>((unsigned int *)p);
     const bool cpad = g.C % FW_C != 0;
     if (g.m == 4 && cpad)
         fused_wide_kernel<4, true><<<dim3(grid), dim3(FW_T), 0, s>>>(D, U, Y, g, n_kb, n_tb, groups, p);

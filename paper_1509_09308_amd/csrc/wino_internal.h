@@ -29,10 +29,10 @@ inline int pad_c(int C, int dt) { return round_up(C, dt == WINO_F16 ? 32 : 16); 
 inline int pad_p(long long P) { return round_up(P, 32); }
 
 // Kernel launchers (each enqueues on `s` and returns the launch status).
-// `zero512` (fp32 only, may be null): 512 words the first block sets to zero for the kernel that follows
-hipError_t launch_filter_transform(const Geo &g, const void *G, void *U, hipStream_t s, unsigned int *zero512 = nullptr);
+// `zero1024` (fp32 only, may be null): 1024 words the first block sets to zero for the kernel that follows
+hipError_t launch_filter_transform(const Geo &g, const void *G, void *U, hipStream_t s, unsigned int *zero1024 = nullptr);
 hipError_t launch_filter_transform_bwd(const Geo &g, const void *G, void *U, hipStream_t s,
-                                       unsigned int *zero512 = nullptr);
+                                       unsigned int *zero1024 = nullptr);
 hipError_t launch_input_transform(const Geo &g, const void *D, void *V, hipStream_t s);
 int gemm_splits(const Geo &g);
 void gemm_launch_shape(const Geo &g, int *bm, int *bn, int *splits);
@@ -45,14 +45,14 @@ bool fused_f16_eligible(const Geo &g);
 bool fused_lds_eligible(const Geo &g);
 hipError_t launch_fused_lds(const Geo &g, const float *D, const float *U, float *Y, hipStream_t s);
 bool fused_wide_eligible(const Geo &g);
-// `part`: room for arrival counters and partial outputs (fused_wide_part_bytes(), 256-byte aligned), or null;
+// `part`: room for arrival counters and partial outputs (fused_wide_part_bytes(g), 256-byte aligned), or null;
 // `cleared`: the counters (the first 512 words of `part`) have been set to zero by a kernel in front on the stream.
 // fused_wide_shares: whether the launch will use `part` at all.
 hipError_t launch_fused_wide(const Geo &g, const float *D, const float *U, float *Y, void *part, size_t part_bytes,
                              bool cleared, hipStream_t s);
 bool fused_wide_shares(const Geo &g, const void *part, size_t part_bytes);
 int fused_wide_plan(const Geo &g, int out[32]);      // per XCD: items, in full rounds, in the last round, shares; returns the grid
-size_t fused_wide_part_bytes();
+size_t fused_wide_part_bytes(const Geo &g);
 double fused_wide_fill(const Geo &g);      // 0 .. 1: how well the launch fills its rounds of resident workgroups
 hipError_t launch_fused_f16(const Geo &g, const void *D, const void *U, void *Y, int y_dt, hipStream_t s);
 bool fused_f2_eligible(const Geo &g);
