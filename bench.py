@@ -41,8 +41,8 @@ PEAK = {"hbm_GBs": 8000.0, "mfma_f32_TFs": 157.3, "mfma_f16_TFs": 2500.0}
 # `bench.py --probe` (summaries under profiles/); keyed by (workload, kernel).  None until measured.
 MEASURED_TRAFFIC = {
     # profiles/vgg16_n64_fp32_hbm_traffic.md
-    ("vgg16_3x3_conv_stack_N64_f32", "fused_wide_kernel<4, false>"): 1147.9e6,     # 9 launches (algorithmic 544.5 MB)
-    ("vgg16_3x3_conv_stack_N64_f32", "fused_wide_kernel<2, false>"): 323.2e6,      # 3 launches (algorithmic 68.2 MB)
+    ("vgg16_3x3_conv_stack_N64_f32", "fused_wide_kernel<4, false>"): 1137.0e6,     # 9 launches (algorithmic 544.5 MB)
+    ("vgg16_3x3_conv_stack_N64_f32", "fused_wide_kernel<2, false>"): 303.5e6,      # 3 launches (algorithmic 68.2 MB)
     # profiles/vgg16_n32_fp16_hbm_traffic.md (algorithmic: 328.7 MB resp. 183.5 MB per launch)
     ("vgg16_3x3_conv_stack_N32_f16", "fused_f16_kernel<false, 2, float>"): 355.9e6,
     ("vgg16_3x3_conv_stack_N32_f16", "gemm_f16_kernel<128, 128>"): 187.3e6,
