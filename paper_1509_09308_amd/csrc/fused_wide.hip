@@ -21,10 +21,10 @@
 //      MFMAs: nine components of MFMAs ahead of its use, in the register it replaces.
 // After the last step the accumulators go through LDS in four pieces (piece f = the filters 4 i + f); every thread
 // gathers the 36 components of one (filter, tile) pair, applies Y = A^T m A and writes its rows.
-// Needs pad = 1, W % 4 == 0 and the images one workgroup touches within 1 GiB.
+// Needs pad = 1, W % m == 0 and the images one workgroup touches within 1 GiB.
 //
-// The resident workgroups (512; 768 for F(2x2)) take the items of their XCD round by round.  A last round that fills only part of
-// them would leave most CUs idle for the length of an item, so its items are cut into shares of their channel
+// The resident workgroups (512; 768 for F(2x2)) take the items of their XCD round by round.  A last round that fills
+// only part of them would leave most CUs idle for the length of an item, so its items are cut into shares of their channel
 // steps, one workgroup per share: each share applies the (linear) inverse transform to its partial sums, stores
 // partial outputs in the workspace and takes a ticket; the share that arrives last adds the partial outputs in
 // share order and writes Y.  Nobody waits for anybody, and the result does not depend on the order of arrival.
