@@ -431,6 +431,10 @@ bool fused_preferred(const Geo &g)
     // Three quarters of the resident workgroups suffice up to 175 (320 -> 320 at 28 x 28: -26 % with 490 items,
     // -12 % with 368; 384 -> 384: -8 % with 444; 512 -> 256: a tie with 392, +23 % with 296).
     if (fused_wide_eligible(g)) {
+        // Up to 256 items every workgroup has a CU to itself: with 196 of them 64 -> 128 and 128 -> 128 channels at
+        // 112 x 112 (N = 2), 128 -> 128 at 56 x 56 (N = 8) and 128 -> 256 (N = 4) run 20-23 % faster in one kernel
+        // (104 items: 19 % slower; 296, where CUs begin to hold two: a tie).
+        if ((long long)g.K * g.C <= 100LL * (g.K + g.C) && wide_items >= 192 && wide_items <= 256) return true;
         if ((long long)g.K * g.C <= 175LL * (g.K + g.C) && wide_items >= 384) return true;
         if ((long long)g.K * g.C <= 256LL * (g.K + g.C) && wide_items >= 512 && fused_wide_fill(g) >= 0.85) return true;
     }

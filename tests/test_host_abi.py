@@ -190,6 +190,8 @@ def test_variant_query_host_only(L):
     assert w.wino_conv2d_variant(64, 256, 28, 28, 512, 1, 4) == w.FLAG_FUSED        # 171: still ahead
     assert w.wino_conv2d_variant(1, 64, 224, 224, 64, 1, 4) == w.FLAG_FUSED         # batch 1, 64 -> 64: 196 workgroups suffice
     assert w.wino_conv2d_variant(1, 128, 112, 112, 128, 1, 4) == w.FLAG_UNFUSED     # too few workgroups
+    assert w.wino_conv2d_variant(2, 128, 112, 112, 128, 1, 4) == w.FLAG_FUSED       # 196: one per CU
+    assert w.wino_conv2d_variant(3, 128, 112, 112, 128, 1, 4) == w.FLAG_UNFUSED     # 296: some CUs hold two
     assert w.wino_conv2d_variant(64, 64, 224, 224, 64, 1, 2) == w.FLAG_FUSED        # F(2x2): the 64-filter design
     assert w.wino_conv2d_variant(64, 512, 14, 14, 512, 1, 2) == w.FLAG_FUSED
     assert w.wino_conv2d_variant(1, 512, 14, 14, 512, 1, 2) == w.FLAG_UNFUSED       # ... where it fills the GPU
